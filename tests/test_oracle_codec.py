@@ -1,0 +1,211 @@
+"""Pins for the oracle's packing, byte layout and whole-codec invariants.
+
+Expected values come from the paper's worked packing example and ratio
+arithmetic (tests/golden/), from the documented byte layout parsed here in
+numpy, and from identities (Parseval, orthogonal projection) that do not
+involve the oracle.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from paper_1811_08596_amd import workloads
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def read_kv(name):
+    out = {}
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                k, v = line.split("=", 1)
+                out[k.strip()] = v.strip()
+    return out
+
+
+def as_complex(spec, L):
+    return np.asarray(spec).reshape(-1, L + 2).view(np.complex64)
+
+
+def test_paper_packing_example(ref):
+    g = read_kv("packing_example.txt")
+    sub = {"a": 1.5, "b": -2.25, "c": 3.0, "0": 0.0}
+    sparse = np.array([sub[t] for t in g["sparse"].split()], np.float32)
+    status, loc, dense = ref.pack_dense(sparse)
+    assert list(status) == [int(t) for t in g["status"].split()]
+    assert list(loc) == [int(t) for t in g["location"].split()]
+    assert list(dense) == [sub[t] for t in g["dense"].split()]
+
+
+def test_paper_ratio_arithmetic(ref):
+    g = read_kv("compression_ratio.txt")
+    kept = 1.0 - float(g["dropped_fraction"])
+    N = int(g["code_bits"])
+    assert round(1.0 / kept, 2) == float(g["topk_ratio"])
+    # payload bits per gradient element in this format: 2 codes per kept complex bin, B ~ L/2 bins
+    L = 1 << 20
+    k = ref.kept_per_chunk(L, kept)
+    payload_bits = 2 * k * N
+    ratio = 32.0 * L / payload_bits
+    assert abs(ratio - float(g["fft_ratio"])) < 0.05
+    # whole record (bitmap + header) is what is actually sent; the bitmap costs ~1/2 bit per element
+    S = ref.record_stride(L, k, N)
+    assert abs(S - (16 + 4 * ((L // 2 + 1 + 31) // 32) + payload_bits / 8)) < 16
+    assert 32.0 * L / (8 * S) < ratio
+
+
+@pytest.mark.parametrize("bits", [3, 6, 8, 10, 16, 32])
+@pytest.mark.parametrize("L,theta", [(32, 0.0), (32, 1 / 17), (64, 31 / 33), (64, 1.0), (128, 0.5), (2048, 0.3)])
+def test_layout_and_roundtrip_of_codes(ref, bits, L, theta):
+    n = 2 * L + 5
+    g = workloads.small_mixed(n, seed=bits)
+    spec = ref.rfft(g, L)
+    packed = ref.encode_spectrum(spec, n, L, theta, bits)
+    B, C = L // 2 + 1, 3
+    k = ref.kept_per_chunk(L, theta)
+    m = ref.mantissa_bits(bits)
+    h = ref.parse_header(packed)
+    S = ref.record_stride(L, k, bits)
+    W = (B + 31) // 32
+    assert S == -(-(16 + 4 * W + 4 * (-(-2 * k * bits // 32))) // 16) * 16
+    assert packed.size == ref.packed_bytes(n, L, theta, bits) == 64 + C * S
+    assert h == dict(magic=b"FSP1", version=1, n=n, L=L, C=C, bits=bits, m=m, k=k, S=S, theta=float(np.float32(theta)))
+    assert not packed[44:64].any()
+    X = as_complex(spec, L)
+    dec = as_complex(ref.decode_spectrum(packed, n, L, theta, bits), L)
+    for c in range(C):
+        pb, vmax, kk, w3, bitmap, codes = ref.record_fields(packed, L, c)
+        assert kk == k and w3 == 0 and bitmap.sum() == k
+        keys = np.array([ref.key(z.real, z.imag) for z in X[c]], np.uint32)
+        assert np.array_equal(bitmap, ref.select(keys, k))
+        kept = np.flatnonzero(bitmap)
+        comps = np.abs(X[c][kept].view(np.float32)).view(np.uint32)
+        assert vmax == (comps.max() if k else 0)
+        assert pb == ref.pbase(vmax, bits, m)
+        got = ref.unpack_codes(codes, 2 * k, bits)
+        want = [ref.quantize(int(u), pb, bits, m) for u in X[c][kept].view(np.float32).view(np.uint32)]
+        assert list(got) == want
+        # padding after the last code is zero
+        allbits = np.unpackbits(codes, bitorder="little")
+        assert not allbits[2 * k * bits:].any()
+        # decode = scatter of dequantised codes, zeros elsewhere
+        back = np.zeros(B, np.complex64)
+        back.view(np.uint32)[np.repeat(2 * kept, 2) + np.tile([0, 1], k)] = \
+            [ref.dequantize(int(cd), pb, bits, m) for cd in got]
+        assert np.array_equal(back.view(np.uint32), dec[c].view(np.uint32))
+
+
+def test_impulse_and_zero_chunks_keep_lowest_bins(ref):
+    L, theta, bits = 256, 0.25, 8
+    k = ref.kept_per_chunk(L, theta)
+    for g in (np.eye(1, L, 0, dtype=np.float32)[0], np.zeros(L, np.float32)):
+        packed = ref.compress(g, L, theta, bits)
+        _, vmax, _, _, bitmap, _ = ref.record_fields(packed, L, 0)
+        assert np.array_equal(np.flatnonzero(bitmap), np.arange(k))
+        out = ref.decompress(packed, L, L, theta, bits)
+        if not g.any():
+            assert vmax == 0 and not out.any()
+
+
+def test_no_sparsification_no_quantization_is_identity(ref):
+    """theta keeps everything, quantization off => iFFT(FFT(g)) = g."""
+    for L in (64, 4096):
+        g = workloads.small_mixed(3 * L - 1, seed=9)
+        out = ref.decompress(ref.compress(g, L, 1.0, 32), g.size, L, 1.0, 32)
+        assert np.linalg.norm(out - g) <= 1e-6 * np.linalg.norm(g)
+
+
+def test_error_energy_equals_dropped_energy(ref):
+    """bits=32: the reconstruction error is the dropped bins' energy (Parseval), and alpha <= 1, falling with theta."""
+    L = 1024
+    g = workloads.small_mixed(L, seed=11)
+    X = np.fft.rfft(g.astype(np.float64))
+    w = np.full(L // 2 + 1, 2.0)
+    w[0] = w[-1] = 1.0
+    power = w * np.abs(X) ** 2 / L
+    order = np.argsort(-np.abs(X), kind="stable")
+    prev = 2.0
+    for theta in (0.0, 0.1, 0.3, 0.5, 0.9, 1.0):
+        k = ref.kept_per_chunk(L, theta)
+        out = ref.decompress(ref.compress(g, L, theta, 32), L, L, theta, 32)
+        err = float(((out.astype(np.float64) - g) ** 2).sum())
+        want = float(power[order[k:]].sum())
+        assert abs(err - want) <= 1e-5 * power.sum()
+        alpha = np.sqrt(err / power.sum())
+        assert alpha <= 1.0 + 1e-6 and alpha <= prev + 1e-9
+        prev = alpha
+    assert prev < 1e-6
+
+
+def test_quantized_alpha_bounded(ref):
+    """Assumption 2's alpha = |v - v_hat| / |v| stays in [0,1] for one worker, with 8-bit codes too."""
+    for cfg in (workloads.config1(), workloads.config2()):
+        out = ref.decompress(ref.compress(cfg.grad, cfg.chunk_len, cfg.theta, cfg.bits, nthreads=4),
+                             cfg.grad.size, cfg.chunk_len, cfg.theta, cfg.bits, nthreads=4)
+        alpha = np.linalg.norm(out - cfg.grad) / np.linalg.norm(cfg.grad)
+        assert 0.0 < alpha < 1.0
+
+
+def test_decode_rejects_corruption(ref):
+    L, n = 64, 64
+    g = workloads.small_mixed(n, seed=1)
+    packed = ref.compress(g, L, 0.5, 8)
+    bad = packed.copy()
+    bad[0] = ord("X")
+    with pytest.raises(ref.OracleError):
+        ref.decompress(bad, n, L, 0.5, 8)
+    bad = packed.copy()
+    bad[64 + 16] ^= 0xFF           # bitmap no longer has k bits
+    with pytest.raises(ref.OracleError):
+        ref.decompress(bad, n, L, 0.5, 8)
+    with pytest.raises(ref.OracleError):
+        ref.decompress(packed, n, L, 0.25, 8)     # parameters must match the header
+
+
+def test_threads_do_not_change_bytes(ref):
+    cfg = workloads.config2()
+    a = ref.compress(cfg.grad, cfg.chunk_len, cfg.theta, cfg.bits, nthreads=1)
+    b = ref.compress(cfg.grad, cfg.chunk_len, cfg.theta, cfg.bits, nthreads=5)
+    assert np.array_equal(a, b)
+
+
+def test_segmented_equals_per_tensor_single_chunk(ref):
+    """per-tensor mode = each tensor compressed alone as one chunk of the next power of two (min 32)"""
+    sizes = [10, 64, 100, 257, 1000]
+    offs = np.concatenate([[0], np.cumsum(sizes)])
+    g = workloads.small_mixed(int(offs[-1]), seed=21)
+    theta, bits = 0.3, 6
+    packed = ref.compress_segments(g, offs, theta, bits, nthreads=2)
+    assert packed.size == ref.packed_bytes_segments(offs, theta, bits)
+    h = ref.parse_header(packed)
+    assert (h["L"], h["C"], h["k"], h["S"], h["n"]) == (0, len(sizes), 0, 0, int(offs[-1]))
+    pos = 64
+    for i, s in enumerate(sizes):
+        L = ref.segment_length(s)
+        assert L == max(32, 1 << int(np.ceil(np.log2(s))))
+        one = ref.compress(g[offs[i]:offs[i + 1]], L, theta, bits)
+        S = ref.parse_header(one)["S"]
+        rec = packed[pos:pos + S].copy()
+        assert int(rec[12:16].view("<u4")[0]) == L
+        rec[12:16] = 0
+        assert np.array_equal(rec, one[64:])
+        pos += S
+    assert pos == packed.size
+    out = ref.decompress_segments(packed, offs, theta, bits)
+    for i, s in enumerate(sizes):
+        L = ref.segment_length(s)
+        one = ref.decompress(ref.compress(g[offs[i]:offs[i + 1]], L, theta, bits), s, L, theta, bits)
+        assert np.array_equal(out[offs[i]:offs[i + 1]], one)
+
+
+def test_workload_shapes():
+    assert sum(workloads.resnet20_sizes()) == 269722 and len(workloads.resnet20_sizes()) == 22
+    assert sum(workloads.alexnet_sizes()) == 62378344
+    s50 = workloads.resnet50_sizes()
+    assert len(s50) == 161 and 25.5e6 < sum(s50) < 25.7e6 and min(s50) == 64 and max(s50) == 512 * 512 * 9
+    assert sum(workloads.vgg16_sizes()) == 138357544
+    a, b = workloads.config1().grad, workloads.config1().grad
+    assert np.array_equal(a, b) and a.dtype == np.float32 and abs(a.std() - 1e-3) < 5e-5
