@@ -1,0 +1,128 @@
+/*
+ * fftsp.h -- C ABI of the MI355X (gfx950) FFT-sparsifying gradient codec.
+ *
+ * The codec is the per-worker sender/receiver pair of arXiv 1811.08596, Sec. 3.1
+ * ("The Compression Framework"): linearized gradient -> FFT -> keep the largest
+ * frequency components -> range-based N-bit float -> pack; the receiver applies
+ * the inverse operations in reverse order.
+ *
+ * Conventions shared by every entry point
+ *   - Pointers named d_* are DEVICE pointers (hipMalloc / torch CUDA memory),
+ *     16-byte aligned.  seg_offsets is a HOST pointer.  The caller owns every
+ *     buffer; the library allocates nothing per call (two 16 KiB twiddle tables
+ *     are created once per device on first use and kept until process exit).
+ *   - Calls only enqueue work on `stream` and return; they never synchronise and
+ *     never touch the null stream.  Input buffers are not modified.  Output
+ *     regions are written completely (padding bytes zero), so results are
+ *     byte-comparable.  Two calls that share a workspace must be ordered by
+ *     the caller (same stream, or events).
+ *   - `theta` is the KEPT fraction of frequency bins in [0,1].  The paper's theta
+ *     (Sec. 3.1.1) is the dropped fraction, i.e. 1 - theta of this interface.
+ *   - `chunk_len` L is a power of two in [32, 2^22]; the flat gradient is cut
+ *     into C = ceil(n/L) chunks, the last one zero-padded.  One chunk of length
+ *     n is exactly the paper's whole-vector transform.
+ *   - `bits` N is the code width: 3..16 for the offset-based N-bit float of
+ *     Sec. 3.2.1 / Algorithm 1, or 32 for "quantization off" (raw binary32).
+ *   - Return value: FFTSP_OK or an error; argument errors are detected on the
+ *     host before anything is enqueued.  Non-finite gradient values are not
+ *     detected: the call is memory-safe but its output is unspecified.
+ *
+ * Packed stream (little-endian, all padding zero):
+ *   64-byte header: "FSP1", u32 version=1, u64 n, u32 L (0 = per-segment
+ *   lengths), u32 C, u32 N, u32 m, u32 k, u32 S, f32 theta, zeros;
+ *   then C records of S = align16(16 + 4*W + 4*ceil(2kN/32)) bytes,
+ *   W = ceil(B/32), B = L/2+1:
+ *     +0  u32 pbase, u32 vmax_bits, u32 k, u32 L-if-segmented-else-0
+ *     +16 status bitmap (Sec. 3.2): bit j%32 of word j/32 set = bin j kept
+ *     +16+4W codes: code i in bits [iN, iN+N) of an LSB-first u32 stream,
+ *         order re0, im0, re1, im1, ... by ascending kept bin (the "dense"
+ *         vector of Sec. 3.2; its positions are the prefix sum of the bitmap).
+ */
+#ifndef FFTSP_H
+#define FFTSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ihipStream_t* fftsp_stream_t; /* a hipStream_t */
+
+typedef enum {
+    FFTSP_OK = 0,
+    FFTSP_EINVAL = 1,       /* null/misaligned pointer, n = 0, theta outside [0,1] or NaN, bad bits */
+    FFTSP_ENOSPC = 2,       /* packed_capacity smaller than fftsp_packed_bytes(...) */
+    FFTSP_EWORKSPACE = 3,   /* workspace smaller than fftsp_workspace_bytes(...) */
+    FFTSP_EUNSUPPORTED = 4, /* chunk_len not a power of two in [32, 2^22] */
+    FFTSP_EHIP = 5,         /* a HIP runtime call or launch failed */
+    FFTSP_EFORMAT = 6       /* packed stream does not match the arguments (device status word) */
+} fftsp_status;
+
+/* ---- host-side arithmetic: no device access, pure functions of their arguments ---- */
+
+/* k = clamp(floor((double)theta * B + 1/2), 0, B): kept bins per chunk (selection rule of Sec. 3.1.1). */
+int fftsp_kept_per_chunk(uint32_t chunk_len, float theta, uint32_t* k_out);
+/* default mantissa width m of the N-bit float (Sec. 3.2.1: "m bits left for the mantissa"); -1 if bits invalid. */
+int fftsp_mantissa_bits(int bits);
+/* exact size of the packed stream, 0 on invalid arguments. */
+size_t fftsp_packed_bytes(size_t n, uint32_t chunk_len, float theta, int bits);
+/* bytes of device workspace any entry point below needs for (n, chunk_len, bits); 0 on invalid arguments. */
+size_t fftsp_workspace_bytes(size_t n, uint32_t chunk_len, int bits);
+
+/* ---- the codec (Sec. 3.1 steps 1-4 and their inverses) ---- */
+
+/* Sender.  d_grad: n floats.  d_packed: receives fftsp_packed_bytes(...) bytes. */
+int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits,
+                   void* d_packed, size_t packed_capacity,
+                   void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+
+/* Receiver.  The same (n, chunk_len, theta, bits) as the sender must be passed; a stream whose
+ * header disagrees sets the device status word to FFTSP_EFORMAT and the output is unspecified
+ * (reads stay inside d_packed[0, packed_bytes)).  d_grad_out: exactly n floats are written. */
+int fftsp_decompress(const void* d_packed, size_t packed_bytes,
+                     float* d_grad_out, size_t n, uint32_t chunk_len, float theta, int bits,
+                     void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+
+/* ---- stage-level entry points (the same kernels the codec runs, exposed for parity checks) ---- */
+
+/* Forward real DFT of each chunk (the sum of Sec. 3.1.1, sign -, unnormalised).
+ * d_spec: C*(L+2) floats, chunk c at c*(L+2), bins 0..L/2 as (re,im) pairs; im of bins 0 and L/2 is +0. */
+int fftsp_rfft(const float* d_grad, size_t n, uint32_t chunk_len, float* d_spec,
+               void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+/* Inverse (1/L, Hermitian extension; im of bins 0 and L/2 ignored); writes the first n samples. */
+int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad_out,
+                void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+/* Steps 2-4 of Sec. 3.1 on a given spectrum: magnitude top-k, Algorithm 1, packing (Sec. 3.2). */
+int fftsp_encode_spectrum(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits,
+                          void* d_packed, size_t packed_capacity,
+                          void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+/* Inverse of the above: unpack, Nbit_to_32bit of Algorithm 1, scatter into a zeroed spectrum. */
+int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, uint32_t chunk_len,
+                          float theta, int bits, float* d_spec,
+                          void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+
+/* ---- per-tensor variant: segment i = d_grad[seg_offsets[i] .. seg_offsets[i+1]) is one chunk of
+ *      L_i = max(32, next power of two >= its size); seg_offsets (nseg+1 entries, ascending) is on the HOST
+ *      and is consumed before the call returns.  Sizes above 2^22 are FFTSP_EUNSUPPORTED. ---- */
+size_t fftsp_packed_bytes_segments(const size_t* seg_offsets, int nseg, float theta, int bits);
+size_t fftsp_workspace_bytes_segments(const size_t* seg_offsets, int nseg, int bits);
+int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int nseg, float theta, int bits,
+                            void* d_packed, size_t packed_capacity,
+                            void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* d_grad_out,
+                              const size_t* seg_offsets, int nseg, float theta, int bits,
+                              void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+
+/* Synchronises `stream`'s device and reads the status word the last call on this workspace left
+ * (FFTSP_OK or FFTSP_EFORMAT).  Returns FFTSP_EHIP if the copy fails. */
+int fftsp_device_status(const void* d_workspace, int* status_out);
+
+const char* fftsp_strerror(int status);
+const char* fftsp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FFTSP_H */

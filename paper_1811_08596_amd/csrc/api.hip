@@ -1,0 +1,467 @@
+// C ABI of libfftsp.so (see include/fftsp.h): argument checks, workspace carving, launch order.
+#include "../../include/fftsp.h"
+#include "internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+namespace fftsp {
+
+namespace {
+struct DeviceTables {
+    bool ready = false;
+    Tables t{nullptr, nullptr};
+};
+constexpr int kMaxDevices = 64;
+DeviceTables g_tables[kMaxDevices];
+std::mutex g_mutex;
+}  // namespace
+
+hipError_t get_tables(Tables* out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceTables& d = g_tables[dev];
+    if (!d.ready) {
+        std::vector<float2> hi(2048), lo(2048);
+        const double two_pi = 6.283185307179586476925286766559;
+        for (int i = 0; i < 2048; ++i) {
+            const double a = two_pi * (double)i / 2048.0, b = two_pi * (double)i / 4194304.0;
+            hi[i] = make_float2((float)std::cos(a), (float)-std::sin(a));
+            lo[i] = make_float2((float)std::cos(b), (float)-std::sin(b));
+        }
+        float2* dev_mem = nullptr;
+        e = hipMalloc(reinterpret_cast<void**>(&dev_mem), 2 * 2048 * sizeof(float2));
+        if (e != hipSuccess) return e;
+        e = hipMemcpy(dev_mem, hi.data(), 2048 * sizeof(float2), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemcpy(dev_mem + 2048, lo.data(), 2048 * sizeof(float2), hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipFree(dev_mem);
+            return e;
+        }
+        d.t.hi = dev_mem;
+        d.t.lo = dev_mem + 2048;
+        d.ready = true;
+    }
+    *out = d.t;
+    return hipSuccess;
+}
+
+namespace {
+
+int log2_exact(uint32_t v)
+{
+    if (v == 0 || (v & (v - 1))) return -1;
+    int l = 0;
+    while ((1u << l) < v) ++l;
+    return l;
+}
+
+int check_len(uint32_t L)
+{
+    const int l = log2_exact(L);
+    if (l < kMinLogL || l > kMaxLogL) return -1;
+    return l;
+}
+
+bool theta_ok(float t) { return t >= 0.0f && t <= 1.0f; }  // false for NaN
+
+uint32_t kept(uint32_t L, float theta)
+{
+    const double B = (double)(L / 2 + 1);
+    double k = std::floor((double)theta * B + 0.5);
+    if (k < 0) k = 0;
+    if (k > B) k = B;
+    return (uint32_t)k;
+}
+
+int mantissa(int bits)
+{
+    if (bits == 32) return 23;
+    if (bits < 3 || bits > 16) return -1;
+    const int e = bits <= 6 ? 3 : (bits <= 12 ? 4 : 5);
+    const int m = bits - 1 - e;
+    return m < 1 ? 1 : m;
+}
+
+size_t record_stride(uint32_t L, uint32_t k, int bits)
+{
+    const size_t B = (size_t)L / 2 + 1, W = (B + 31) / 32;
+    const size_t code_words = ((size_t)2 * k * (size_t)bits + 31) / 32;
+    return (16 + 4 * W + 4 * code_words + 15) & ~(size_t)15;
+}
+
+constexpr size_t kStreamHeader = 64;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint32_t segment_length(size_t size)
+{
+    uint32_t L = 32;
+    while ((size_t)L < size && L < (1u << 31)) L <<= 1;
+    return L;
+}
+
+struct Plan {
+    size_t n, C;
+    uint32_t L, k;
+    int logL, bits, m;
+    size_t S;
+    Workspace ws;
+};
+
+// common argument checks for the uniform-chunk entry points; theta/bits optional
+int make_plan(Plan* p, size_t n, uint32_t L, const float* theta, const int* bits)
+{
+    if (n == 0) return FFTSP_EINVAL;
+    p->logL = check_len(L);
+    if (p->logL < 0) return FFTSP_EUNSUPPORTED;
+    p->n = n;
+    p->L = L;
+    p->C = (n + L - 1) / L;
+    p->k = 0;
+    p->bits = 32;
+    p->m = 23;
+    if (theta) {
+        if (!theta_ok(*theta)) return FFTSP_EINVAL;
+        p->k = kept(L, *theta);
+    }
+    if (bits) {
+        p->m = mantissa(*bits);
+        if (p->m < 0) return FFTSP_EINVAL;
+        p->bits = *bits;
+    }
+    p->S = record_stride(L, p->k, p->bits);
+    p->ws = make_workspace(p->C, L);
+    return FFTSP_OK;
+}
+
+CodecArgs codec_args(const Plan& p, float theta)
+{
+    CodecArgs a{};
+    a.C = p.C;
+    a.L = p.L;
+    a.k = p.k;
+    a.bits = p.bits;
+    a.m = p.m;
+    a.S = p.S;
+    a.word3 = 0;
+    a.write_header = 1;
+    a.hdr_n = p.n;
+    a.hdr_L = p.L;
+    a.hdr_C = (uint32_t)p.C;
+    a.hdr_k = p.k;
+    a.hdr_S = (uint32_t)p.S;
+    a.hdr_theta = theta;
+    return a;
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? FFTSP_OK : FFTSP_EHIP; }
+
+}  // namespace
+}  // namespace fftsp
+
+using namespace fftsp;
+
+extern "C" {
+
+int fftsp_kept_per_chunk(uint32_t chunk_len, float theta, uint32_t* k_out)
+{
+    if (!k_out || !theta_ok(theta)) return FFTSP_EINVAL;
+    if (check_len(chunk_len) < 0) return FFTSP_EUNSUPPORTED;
+    *k_out = kept(chunk_len, theta);
+    return FFTSP_OK;
+}
+
+int fftsp_mantissa_bits(int bits) { return mantissa(bits); }
+
+size_t fftsp_packed_bytes(size_t n, uint32_t chunk_len, float theta, int bits)
+{
+    Plan p;
+    if (make_plan(&p, n, chunk_len, &theta, &bits) != FFTSP_OK) return 0;
+    return kStreamHeader + p.C * p.S;
+}
+
+size_t fftsp_workspace_bytes(size_t n, uint32_t chunk_len, int bits)
+{
+    Plan p;
+    if (make_plan(&p, n, chunk_len, nullptr, &bits) != FFTSP_OK) return 0;
+    return p.ws.total;
+}
+
+int fftsp_rfft(const float* d_grad, size_t n, uint32_t chunk_len, float* d_spec, void* d_workspace,
+               size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, nullptr, nullptr);
+    if (rc) return rc;
+    if (!d_grad || !d_spec || !d_workspace || !aligned16(d_grad) || !aligned16(d_spec) || !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    return hip_status(launch_rfft(d_grad, n, p.logL, p.C, d_spec, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+                                  reinterpret_cast<hipStream_t>(stream)));
+}
+
+int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad_out, void* d_workspace,
+                size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, nullptr, nullptr);
+    if (rc) return rc;
+    if (!d_grad_out || !d_spec || !d_workspace || !aligned16(d_grad_out) || !aligned16(d_spec) ||
+        !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    return hip_status(launch_irfft(d_spec, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+                                   reinterpret_cast<hipStream_t>(stream)));
+}
+
+int fftsp_encode_spectrum(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                          size_t packed_capacity, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    if (!d_spec || !d_packed || !d_workspace || !aligned16(d_spec) || !aligned16(d_packed) || !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_capacity < kStreamHeader + p.C * p.S) return FFTSP_ENOSPC;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    uint8_t* out = static_cast<uint8_t*>(d_packed);
+    return hip_status(launch_encode(d_spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws,
+                                    reinterpret_cast<hipStream_t>(stream)));
+}
+
+int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, uint32_t chunk_len, float theta,
+                          int bits, float* d_spec, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    if (!d_spec || !d_packed || !d_workspace || !aligned16(d_spec) || !aligned16(d_packed) || !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_bytes < kStreamHeader + p.C * p.S) return FFTSP_EFORMAT;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    const uint8_t* in = static_cast<const uint8_t*>(d_packed);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipError_t e = launch_zero_status(ws, p.ws, s);
+    if (e == hipSuccess) e = launch_decode(in, in + kStreamHeader, codec_args(p, theta), d_spec, ws, p.ws, 1, s);
+    return hip_status(e);
+}
+
+int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                   size_t packed_capacity, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    if (!d_grad || !d_packed || !d_workspace || !aligned16(d_grad) || !aligned16(d_packed) || !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_capacity < kStreamHeader + p.C * p.S) return FFTSP_ENOSPC;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    uint8_t* out = static_cast<uint8_t*>(d_packed);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
+    hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, reinterpret_cast<float2*>(ws + p.ws.mid), t, s);
+    if (e == hipSuccess) e = launch_encode(spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws, s);
+    return hip_status(e);
+}
+
+int fftsp_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n, uint32_t chunk_len,
+                     float theta, int bits, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    if (!d_grad_out || !d_packed || !d_workspace || !aligned16(d_grad_out) || !aligned16(d_packed) ||
+        !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_bytes < kStreamHeader + p.C * p.S) return FFTSP_EFORMAT;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    const uint8_t* in = static_cast<const uint8_t*>(d_packed);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
+    hipError_t e = launch_zero_status(ws, p.ws, s);
+    if (e == hipSuccess) e = launch_decode(in, in + kStreamHeader, codec_args(p, theta), spec, ws, p.ws, 1, s);
+    if (e == hipSuccess)
+        e = launch_irfft(spec, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t, s);
+    return hip_status(e);
+}
+
+/* ---------------- per-tensor variant: one single-chunk codec per segment ---------------- */
+
+static int segments_ok(const size_t* off, int nseg)
+{
+    if (!off || nseg <= 0) return FFTSP_EINVAL;
+    for (int i = 0; i < nseg; ++i) {
+        if (off[i + 1] <= off[i]) return FFTSP_EINVAL;
+        if (off[i + 1] - off[i] > ((size_t)1 << kMaxLogL)) return FFTSP_EUNSUPPORTED;
+    }
+    return FFTSP_OK;
+}
+
+size_t fftsp_packed_bytes_segments(const size_t* seg_offsets, int nseg, float theta, int bits)
+{
+    if (segments_ok(seg_offsets, nseg) != FFTSP_OK || !theta_ok(theta) || mantissa(bits) < 0) return 0;
+    size_t total = kStreamHeader;
+    for (int i = 0; i < nseg; ++i) {
+        const uint32_t L = segment_length(seg_offsets[i + 1] - seg_offsets[i]);
+        total += record_stride(L, kept(L, theta), bits);
+    }
+    return total;
+}
+
+size_t fftsp_workspace_bytes_segments(const size_t* seg_offsets, int nseg, int bits)
+{
+    if (segments_ok(seg_offsets, nseg) != FFTSP_OK || mantissa(bits) < 0) return 0;
+    size_t best = 0;
+    for (int i = 0; i < nseg; ++i) {
+        const uint32_t L = segment_length(seg_offsets[i + 1] - seg_offsets[i]);
+        const size_t t = make_workspace(1, L).total;
+        best = t > best ? t : best;
+    }
+    return best;
+}
+
+int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int nseg, float theta, int bits,
+                            void* d_packed, size_t packed_capacity, void* d_workspace, size_t workspace_bytes,
+                            fftsp_stream_t stream)
+{
+    int rc = segments_ok(seg_offsets, nseg);
+    if (rc) return rc;
+    const int m = mantissa(bits);
+    if (!theta_ok(theta) || m < 0) return FFTSP_EINVAL;
+    if (!d_grad || !d_packed || !d_workspace || !aligned16(d_grad) || !aligned16(d_packed) || !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_capacity < fftsp_packed_bytes_segments(seg_offsets, nseg, theta, bits)) return FFTSP_ENOSPC;
+    if (workspace_bytes < fftsp_workspace_bytes_segments(seg_offsets, nseg, bits)) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    uint8_t* out = static_cast<uint8_t*>(d_packed);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    size_t rec_off = kStreamHeader;
+    for (int i = 0; i < nseg; ++i) {
+        const size_t size = seg_offsets[i + 1] - seg_offsets[i];
+        const uint32_t L = segment_length(size);
+        const Workspace w = make_workspace(1, L);
+        CodecArgs a{};
+        a.C = 1;
+        a.L = L;
+        a.k = kept(L, theta);
+        a.bits = bits;
+        a.m = m;
+        a.S = record_stride(L, a.k, bits);
+        a.word3 = L;
+        a.write_header = (i == 0);
+        a.hdr_n = seg_offsets[nseg] - seg_offsets[0];
+        a.hdr_L = 0;
+        a.hdr_C = (uint32_t)nseg;
+        a.hdr_k = 0;
+        a.hdr_S = 0;
+        a.hdr_theta = theta;
+        float* spec = reinterpret_cast<float*>(ws + w.spec);
+        hipError_t e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec,
+                                   reinterpret_cast<float2*>(ws + w.mid), t, s);
+        if (e == hipSuccess) e = launch_encode(spec, a, out, out + rec_off, ws, w, s);
+        if (e != hipSuccess) return FFTSP_EHIP;
+        rec_off += a.S;
+    }
+    return FFTSP_OK;
+}
+
+int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* d_grad_out, const size_t* seg_offsets,
+                              int nseg, float theta, int bits, void* d_workspace, size_t workspace_bytes,
+                              fftsp_stream_t stream)
+{
+    int rc = segments_ok(seg_offsets, nseg);
+    if (rc) return rc;
+    const int m = mantissa(bits);
+    if (!theta_ok(theta) || m < 0) return FFTSP_EINVAL;
+    if (!d_grad_out || !d_packed || !d_workspace || !aligned16(d_grad_out) || !aligned16(d_packed) ||
+        !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_bytes < fftsp_packed_bytes_segments(seg_offsets, nseg, theta, bits)) return FFTSP_EFORMAT;
+    if (workspace_bytes < fftsp_workspace_bytes_segments(seg_offsets, nseg, bits)) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    const uint8_t* in = static_cast<const uint8_t*>(d_packed);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    // every segment uses the same status word; it is cleared once, before the first segment
+    if (launch_zero_status(ws, make_workspace(1, 32), s) != hipSuccess) return FFTSP_EHIP;
+    size_t rec_off = kStreamHeader;
+    for (int i = 0; i < nseg; ++i) {
+        const size_t size = seg_offsets[i + 1] - seg_offsets[i];
+        const uint32_t L = segment_length(size);
+        const Workspace w = make_workspace(1, L);
+        CodecArgs a{};
+        a.C = 1;
+        a.L = L;
+        a.k = kept(L, theta);
+        a.bits = bits;
+        a.m = m;
+        a.S = record_stride(L, a.k, bits);
+        a.word3 = L;
+        a.hdr_n = seg_offsets[nseg] - seg_offsets[0];
+        a.hdr_L = 0;
+        a.hdr_C = (uint32_t)nseg;
+        a.hdr_k = 0;
+        a.hdr_S = 0;
+        a.hdr_theta = theta;
+        float* spec = reinterpret_cast<float*>(ws + w.spec);
+        hipError_t e = launch_decode(in, in + rec_off, a, spec, ws, w, i == 0, s);
+        if (e == hipSuccess)
+            e = launch_irfft(spec, size, log2_exact(L), 1, d_grad_out + seg_offsets[i],
+                             reinterpret_cast<float2*>(ws + w.mid), t, s);
+        if (e != hipSuccess) return FFTSP_EHIP;
+        rec_off += a.S;
+    }
+    return FFTSP_OK;
+}
+
+int fftsp_device_status(const void* d_workspace, int* status_out)
+{
+    if (!d_workspace || !status_out) return FFTSP_EINVAL;
+    if (hipDeviceSynchronize() != hipSuccess) return FFTSP_EHIP;
+    uint32_t v = 0;
+    if (hipMemcpy(&v, d_workspace, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return FFTSP_EHIP;
+    *status_out = (int)v;
+    return FFTSP_OK;
+}
+
+const char* fftsp_strerror(int status)
+{
+    switch (status) {
+        case FFTSP_OK: return "ok";
+        case FFTSP_EINVAL: return "invalid argument";
+        case FFTSP_ENOSPC: return "packed buffer too small";
+        case FFTSP_EWORKSPACE: return "workspace too small";
+        case FFTSP_EUNSUPPORTED: return "unsupported chunk length";
+        case FFTSP_EHIP: return "HIP runtime error";
+        case FFTSP_EFORMAT: return "packed stream does not match the arguments";
+        default: return "unknown status";
+    }
+}
+
+const char* fftsp_version(void) { return "fftsp 0.1 (gfx950)"; }
+
+}  // extern "C"

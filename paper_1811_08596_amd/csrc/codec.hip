@@ -1,0 +1,655 @@
+// Selection, quantization, packing and their inverses for gfx950.
+//
+// Follows arXiv 1811.08596: Sec. 3.1.1 (keep the largest-magnitude frequency
+// components, zero the rest), Sec. 3.2 (status bitmap -> prefix sum -> dense
+// vector) and Sec. 3.2.1 / Algorithm 1 (offset-based N-bit float).
+//
+// Selection is an exact radix select on the 31-bit key
+//     key = bits( fma(re, re, im*im) )        (binary32, one product rounded, then one fused step)
+// so it is integer work: a 12-bit histogram of the top key bits per chunk finds
+// the bucket that holds the k-th largest key; bins in higher buckets are kept
+// outright, bins in that bucket ("candidates") are written out tile by tile in
+// bin order, and one workgroup per chunk finishes the select on the candidates
+// (two more digits), resolves ties by lowest bin index, scans the per-tile
+// survivor counts and finds the survivors' largest component, which fixes eps
+// (pbase) of Algorithm 1.  A last pass flags, ranks (wave ballots + popcounts),
+// quantizes and bit-packs.
+#include "internal.h"
+
+namespace fftsp {
+namespace {
+
+constexpr int NT = kTileThreads;     // 256 lanes = 4 waves
+constexpr int ROWS = 8;              // rows of 64 bins per wave
+constexpr int WAVE_BINS = ROWS * 64; // 512
+static_assert(kTile == 4 * WAVE_BINS, "tile geometry");
+
+__device__ __forceinline__ uint32_t key_of(float2 z)
+{
+    return __float_as_uint(__fmaf_rn(z.x, z.x, __fmul_rn(z.y, z.y)));
+}
+__device__ __forceinline__ uint32_t vbits_of(float2 z)
+{
+    const uint32_t a = __float_as_uint(z.x) & 0x7FFFFFFFu, b = __float_as_uint(z.y) & 0x7FFFFFFFu;
+    return a > b ? a : b;
+}
+__device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << (threadIdx.x & 63)) - 1ull; }
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ uint32_t wave_max(uint32_t v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t u = __shfl_xor(v, o, 64);
+        v = u > v ? u : v;
+    }
+    return v;
+}
+
+// 32bit_to_Nbit of Algorithm 1 (value > max clamps to the top code; below eps flushes to the zero code)
+__device__ __forceinline__ uint32_t quantize(uint32_t fbits, uint32_t pbase, int bits, int shift)
+{
+    if (bits == 32) return fbits;
+    const uint32_t Mmax = (1u << (bits - 1)) - 1u;
+    const uint32_t q = (fbits & 0x7FFFFFFFu) >> shift;
+    uint32_t c = 0;
+    if (q >= pbase) {
+        c = q - pbase + 1u;
+        c = c > Mmax ? Mmax : c;
+    }
+    const uint32_t sign = c ? (fbits >> 31) : 0u;
+    return (sign << (bits - 1)) | c;
+}
+// Nbit_to_32bit of Algorithm 1
+__device__ __forceinline__ uint32_t dequantize(uint32_t code, uint32_t pbase, int bits, int shift)
+{
+    if (bits == 32) return code;
+    const uint32_t Mmax = (1u << (bits - 1)) - 1u;
+    const uint32_t c = code & Mmax, sign = (code >> (bits - 1)) & 1u;
+    return c ? (((c - 1u + pbase) << shift) | (sign << 31)) : 0u;
+}
+
+__global__ void k_zero_u32(uint32_t* p, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0u;
+}
+
+// ------------------------------------------------------------- histogram ----
+constexpr int HIST_TILES = 4;  // tiles per workgroup
+
+__global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, uint32_t B, uint32_t groups,
+                                             uint32_t* __restrict__ hist)
+{
+    __shared__ uint32_t h[kHistBins];
+    const int tid = threadIdx.x;
+    const size_t c = blockIdx.x / groups;
+    const uint32_t base = (blockIdx.x % groups) * (HIST_TILES * kTile);
+    for (int i = tid; i < kHistBins; i += NT) h[i] = 0u;
+    __syncthreads();
+    const float2* X = spec + c * (size_t)B;
+#pragma unroll 4
+    for (int i = tid; i < HIST_TILES * kTile; i += NT) {
+        const uint32_t j = base + i;
+        if (j < B) atomicAdd(&h[key_of(X[j]) >> kKeyShift], 1u);
+    }
+    __syncthreads();
+    uint32_t* g = hist + c * kHistBins;
+    for (int i = tid; i < kHistBins; i += NT) {
+        const uint32_t v = h[i];
+        if (v) atomicAdd(&g[i], v);
+    }
+}
+
+// inclusive scan over the 256 lanes of a workgroup; tmp has 4 entries
+__device__ __forceinline__ uint32_t block_scan_incl_256(uint32_t v, uint32_t* tmp)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t u = __shfl_up(x, o, 64);
+        if (lane >= o) x += u;
+    }
+    if (lane == 63) tmp[wave] = x;
+    __syncthreads();
+    uint32_t add = 0;
+    for (int w = 0; w < wave; ++w) add += tmp[w];
+    __syncthreads();
+    return x + add;
+}
+
+// Per chunk: the bucket b* holding the k-th largest key, and how many of its bins are still needed.
+__global__ __launch_bounds__(NT) void k_find_bucket(const uint32_t* __restrict__ hist, uint32_t k,
+                                                    uint32_t* __restrict__ sel)
+{
+    __shared__ uint32_t tmp[4];
+    const int tid = threadIdx.x;
+    const size_t c = blockIdx.x;
+    constexpr int PER = kHistBins / NT;  // 16 buckets per lane, lane t owns the buckets counted from the top
+    uint32_t loc[PER];
+    uint32_t s = 0;
+    const uint32_t top = kHistBins - 1 - tid * PER;  // highest bucket of this lane
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        loc[i] = hist[c * kHistBins + (top - i)];
+        s += loc[i];
+    }
+    const uint32_t incl = block_scan_incl_256(s, tmp);
+    uint32_t run = incl - s;  // bins in buckets above this lane's range
+    if (k == 0) {
+        if (tid == 0) {
+            sel[c * 8 + 0] = kHistBins;  // no bucket qualifies: nothing is kept
+            sel[c * 8 + 1] = 0;
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+        if (run < k && run + loc[i] >= k) {
+            sel[c * 8 + 0] = top - i;
+            sel[c * 8 + 1] = k - run;
+        }
+        run += loc[i];
+    }
+}
+
+// --------------------------------------------------------------- collect ----
+// Per tile: count and range of the bins kept outright, and the candidates in bin order.
+__global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec, uint32_t B, uint32_t Tn,
+                                                const uint32_t* __restrict__ sel, uint32_t* __restrict__ tinfo,
+                                                uint2* __restrict__ cand)
+{
+    __shared__ uint32_t wcnt[4], wdef[4], wvmax[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t c = blockIdx.x / Tn;
+    const uint32_t tile = blockIdx.x % Tn;
+    const uint32_t bstar = sel[c * 8 + 0];
+    const float2* X = spec + c * (size_t)B;
+    const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
+    uint32_t key[ROWS], vb[ROWS];
+    uint64_t cm[ROWS];
+    uint32_t ndef = 0, vmax = 0, ncand = 0;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const uint32_t j = j0 + r * 64;
+        const bool valid = j < B;
+        const float2 z = valid ? X[j] : make_float2(0.f, 0.f);
+        key[r] = key_of(z);
+        vb[r] = vbits_of(z);
+        const uint32_t bucket = key[r] >> kKeyShift;
+        const bool isdef = valid && bucket > bstar;
+        const bool iscand = valid && bucket == bstar;
+        if (isdef) {
+            ++ndef;
+            vmax = vb[r] > vmax ? vb[r] : vmax;
+        }
+        cm[r] = __ballot(iscand);
+        ncand += (uint32_t)__popcll(cm[r]);
+    }
+    ndef = wave_sum(ndef);
+    vmax = wave_max(vmax);
+    if (lane == 0) {
+        wcnt[wave] = ncand;
+        wdef[wave] = ndef;
+        wvmax[wave] = vmax;
+    }
+    __syncthreads();
+    uint32_t off = 0;
+    for (int w = 0; w < wave; ++w) off += wcnt[w];
+    uint2* out = cand + (c * Tn + tile) * (size_t)kTile;
+    const uint64_t lt = lanemask_lt();
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        if ((cm[r] >> lane) & 1ull) out[off + (uint32_t)__popcll(cm[r] & lt)] = make_uint2(key[r], vb[r]);
+        off += (uint32_t)__popcll(cm[r]);
+    }
+    if (tid == 0) {
+        uint32_t* ti = tinfo + (c * Tn + tile) * 4;
+        ti[0] = wdef[0] + wdef[1] + wdef[2] + wdef[3];
+        uint32_t m = wvmax[0];
+        m = wvmax[1] > m ? wvmax[1] : m;
+        m = wvmax[2] > m ? wvmax[2] : m;
+        m = wvmax[3] > m ? wvmax[3] : m;
+        ti[1] = m;
+        ti[2] = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        ti[3] = 0;
+    }
+}
+
+// --------------------------------------------------------------- resolve ----
+constexpr int RT = 1024;           // lanes of the per-chunk workgroup
+constexpr int RW = RT / 64;        // 16 waves
+constexpr int MAX_TILES = ((1 << (kMaxLogL - 1)) + 1 + kTile - 1) / kTile;  // 1025
+
+// inclusive scan over 1024 lanes; tmp has 16 entries
+__device__ __forceinline__ uint32_t block_scan_incl_1024(uint32_t v, uint32_t* tmp)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint32_t x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t u = __shfl_up(x, o, 64);
+        if (lane >= o) x += u;
+    }
+    if (lane == 63) tmp[wave] = x;
+    __syncthreads();
+    uint32_t add = 0;
+    for (int w = 0; w < wave; ++w) add += tmp[w];
+    __syncthreads();
+    return x + add;
+}
+
+struct HeaderInfo {
+    int write;
+    uint64_t n;
+    uint32_t L, C, N, m, k, S;
+    float theta;
+};
+
+// One workgroup per chunk: finish the radix select on the candidates, break ties by bin order,
+// scan the tiles, find the survivors' largest component, write the record header and zero the
+// code words that two tiles will share.
+__global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bits, int m, uint32_t W, size_t S,
+                                                uint32_t word3, uint32_t* __restrict__ sel,
+                                                const uint32_t* __restrict__ tinfo, uint32_t* __restrict__ tscan,
+                                                const uint2* __restrict__ cand, uint8_t* __restrict__ records,
+                                                uint8_t* __restrict__ stream, HeaderInfo hdr)
+{
+    __shared__ uint32_t h[1024];
+    __shared__ uint32_t tmp[RW];
+    __shared__ uint32_t tgt[MAX_TILES], teq[MAX_TILES], ttake[MAX_TILES], trank[MAX_TILES], tsurv[MAX_TILES];
+    __shared__ uint32_t s_digit, s_need, s_vmax, s_carry[2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t c = blockIdx.x;
+    const uint32_t bstar = sel[c * 8 + 0];
+    uint32_t need = sel[c * 8 + 1];
+    const uint32_t* ti = tinfo + c * Tn * 4;
+    const uint2* cd = cand + c * Tn * (size_t)kTile;
+    uint32_t tau = 0xFFFFFFFFu, quota = 0;
+
+    if (need > 0) {
+        uint32_t prefix = bstar << kKeyShift;
+        // two more digits: bits 18..9, then bits 8..0
+        for (int pass = 0; pass < 2; ++pass) {
+            const int shift = pass == 0 ? 9 : 0;
+            const uint32_t dmask = pass == 0 ? 1023u : 511u;
+            const uint32_t pmask = pass == 0 ? (0xFFFFFFFFu << kKeyShift) : (0xFFFFFFFFu << 9);
+            h[tid] = 0u;
+            __syncthreads();
+            for (uint32_t t = wave; t < Tn; t += RW) {
+                const uint32_t nc = ti[t * 4 + 2];
+                for (uint32_t i = lane; i < nc; i += 64) {
+                    const uint32_t key = cd[(size_t)t * kTile + i].x;
+                    if ((key & pmask) == prefix) atomicAdd(&h[(key >> shift) & dmask], 1u);
+                }
+            }
+            __syncthreads();
+            const uint32_t bin = 1023u - (uint32_t)tid;  // scan from the top digit down
+            const uint32_t cnt = h[bin];
+            const uint32_t incl = block_scan_incl_1024(cnt, tmp);
+            const uint32_t excl = incl - cnt;
+            if (excl < need && incl >= need) {
+                s_digit = bin;
+                s_need = need - excl;
+            }
+            __syncthreads();
+            prefix |= s_digit << shift;
+            need = s_need;
+            __syncthreads();
+        }
+        tau = prefix;
+        quota = need;  // bins equal to tau still to take, in bin order
+    }
+
+    // per tile: candidates above tau and equal to tau
+    for (uint32_t t = wave; t < Tn; t += RW) {
+        const uint32_t nc = ti[t * 4 + 2];
+        uint32_t gt = 0, eq = 0;
+        for (uint32_t i = lane; i < nc; i += 64) {
+            const uint32_t key = cd[(size_t)t * kTile + i].x;
+            gt += key > tau;
+            eq += key == tau;
+        }
+        gt = wave_sum(gt);
+        eq = wave_sum(eq);
+        if (lane == 0) {
+            tgt[t] = gt;
+            teq[t] = eq;
+        }
+    }
+    if (tid == 0) {
+        s_carry[0] = 0;
+        s_carry[1] = 0;
+        s_vmax = 0;
+    }
+    __syncthreads();
+
+    // scan over tiles: equal-key prefix decides who gets the tie quota, survivor prefix gives the ranks
+    for (uint32_t base = 0; base < Tn; base += RT) {
+        const uint32_t t = base + tid;
+        const bool in = t < Tn;
+        const uint32_t eq = in ? teq[t] : 0u;
+        const uint32_t ceq = s_carry[0], crk = s_carry[1];
+        const uint32_t eqincl = block_scan_incl_1024(eq, tmp);
+        const uint32_t eqpre = ceq + eqincl - eq;
+        const uint32_t take = eqpre >= quota ? 0u : (eq < quota - eqpre ? eq : quota - eqpre);
+        const uint32_t surv = in ? (ti[t * 4 + 0] + tgt[t] + take) : 0u;
+        const uint32_t rkincl = block_scan_incl_1024(surv, tmp);
+        const uint32_t rank = crk + rkincl - surv;
+        if (in) {
+            ttake[t] = take;
+            trank[t] = rank;
+            tsurv[t] = surv;
+            tscan[(c * Tn + t) * 2 + 0] = rank;
+            tscan[(c * Tn + t) * 2 + 1] = eqpre;
+        }
+        __syncthreads();
+        if (tid == RT - 1) {
+            s_carry[0] = ceq + eqincl;
+            s_carry[1] = crk + rkincl;
+        }
+        __syncthreads();
+    }
+
+    // largest component over the survivors
+    for (uint32_t t = wave; t < Tn; t += RW) {
+        const uint32_t nc = ti[t * 4 + 2], take = ttake[t];
+        uint32_t vm = lane == 0 ? (ti[t * 4 + 0] ? ti[t * 4 + 1] : 0u) : 0u;
+        uint32_t eqrun = 0;
+        for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
+            const uint32_t i = i0 + lane;
+            const bool valid = i < nc;
+            const uint2 e = valid ? cd[(size_t)t * kTile + i] : make_uint2(0u, 0u);
+            const bool iseq = valid && e.x == tau;
+            const uint64_t em = __ballot(iseq);
+            const bool kept = valid && (e.x > tau || (iseq && eqrun + (uint32_t)__popcll(em & lanemask_lt()) < take));
+            if (kept) vm = e.y > vm ? e.y : vm;
+            eqrun += (uint32_t)__popcll(em);
+        }
+        vm = wave_max(vm);
+        if (lane == 0 && vm) atomicMax(&s_vmax, vm);
+    }
+    __syncthreads();
+
+    const uint32_t vmax = s_vmax;
+    uint32_t pbase = 0;
+    if (bits != 32) {
+        const int shift = 23 - m;
+        const int64_t pb = (int64_t)(vmax >> shift) - (int64_t)((1u << (bits - 1)) - 2u);
+        pbase = pb < 1 ? 1u : (uint32_t)pb;
+    }
+    uint32_t* rec = reinterpret_cast<uint32_t*>(records + c * S);
+    if (tid == 0) {
+        sel[c * 8 + 2] = tau;
+        sel[c * 8 + 3] = quota;
+        sel[c * 8 + 4] = pbase;
+        sel[c * 8 + 5] = vmax;
+        rec[0] = pbase;
+        rec[1] = vmax;
+        rec[2] = k;
+        rec[3] = word3;
+    }
+    uint32_t* codes = rec + 4 + W;
+    const uint32_t twoN = 2u * (uint32_t)bits;
+    for (uint32_t t = tid; t < Tn; t += RT) {
+        if (tsurv[t]) {
+            codes[(twoN * trank[t]) >> 5] = 0u;
+            codes[(twoN * (trank[t] + tsurv[t]) - 1u) >> 5] = 0u;
+        }
+    }
+    const uint32_t code_words = (twoN * k + 31u) >> 5;
+    const uint32_t rec_words = (uint32_t)(S / 4) - 4u - W;
+    for (uint32_t w = code_words + tid; w < rec_words; w += RT) codes[w] = 0u;
+
+    if (hdr.write && c == 0 && tid < 16) {
+        uint32_t v = 0;
+        switch (tid) {
+            case 0: v = 0x31505346u; break;  // "FSP1"
+            case 1: v = 1u; break;
+            case 2: v = (uint32_t)hdr.n; break;
+            case 3: v = (uint32_t)(hdr.n >> 32); break;
+            case 4: v = hdr.L; break;
+            case 5: v = hdr.C; break;
+            case 6: v = hdr.N; break;
+            case 7: v = hdr.m; break;
+            case 8: v = hdr.k; break;
+            case 9: v = hdr.S; break;
+            case 10: v = __float_as_uint(hdr.theta); break;
+            default: break;
+        }
+        reinterpret_cast<uint32_t*>(stream)[tid] = v;
+    }
+}
+
+// ------------------------------------------------------------------ emit ----
+// Per tile: flags, ranks, Algorithm 1 codes, bit-packing, bitmap words.
+__global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, uint32_t B, uint32_t Tn, uint32_t W,
+                                             int bits, int m, size_t S, const uint32_t* __restrict__ sel,
+                                             const uint32_t* __restrict__ tscan, uint8_t* __restrict__ records)
+{
+    __shared__ uint32_t cw[kTile * 2 + 2];  // code words of this tile (bits = 32 worst case)
+    __shared__ uint32_t bmw[kTile / 32];
+    __shared__ uint32_t weq[4], wfl[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t c = blockIdx.x / Tn;
+    const uint32_t tile = blockIdx.x % Tn;
+    const uint32_t tau = sel[c * 8 + 2], quota = sel[c * 8 + 3], pbase = sel[c * 8 + 4];
+    const uint32_t rank0 = tscan[(c * Tn + tile) * 2 + 0], eq0 = tscan[(c * Tn + tile) * 2 + 1];
+    const uint32_t twoN = 2u * (uint32_t)bits;
+    const int shift = 23 - m;
+    const uint32_t lds_words = (uint32_t)kTile * twoN / 32u + 2u;
+    for (uint32_t i = tid; i < lds_words; i += NT) cw[i] = 0u;
+
+    const float2* X = spec + c * (size_t)B;
+    const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
+    float2 z[ROWS];
+    uint64_t gm[ROWS], em[ROWS], fm[ROWS];
+    uint32_t neq = 0;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const uint32_t j = j0 + r * 64;
+        const bool valid = j < B;
+        z[r] = valid ? X[j] : make_float2(0.f, 0.f);
+        const uint32_t key = key_of(z[r]);
+        gm[r] = __ballot(valid && key > tau);
+        em[r] = __ballot(valid && key == tau);
+        neq += (uint32_t)__popcll(em[r]);
+    }
+    if (lane == 0) weq[wave] = neq;
+    __syncthreads();  // also orders the zeroing of cw before the atomics below
+    uint32_t eqrun = eq0;
+    for (int w = 0; w < wave; ++w) eqrun += weq[w];
+    const uint64_t lt = lanemask_lt();
+    uint32_t nfl = 0;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const bool gt = (gm[r] >> lane) & 1ull, eq = (em[r] >> lane) & 1ull;
+        const bool flag = gt || (eq && eqrun + (uint32_t)__popcll(em[r] & lt) < quota);
+        fm[r] = __ballot(flag);
+        eqrun += (uint32_t)__popcll(em[r]);
+        nfl += (uint32_t)__popcll(fm[r]);
+    }
+    if (lane == 0) {
+        wfl[wave] = nfl;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            bmw[(wave * ROWS + r) * 2 + 0] = (uint32_t)fm[r];
+            bmw[(wave * ROWS + r) * 2 + 1] = (uint32_t)(fm[r] >> 32);
+        }
+    }
+    __syncthreads();
+    uint32_t rank = rank0;
+    for (int w = 0; w < wave; ++w) rank += wfl[w];
+    const uint32_t total = wfl[0] + wfl[1] + wfl[2] + wfl[3];
+    const uint32_t w0 = (twoN * rank0) >> 5;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        if ((fm[r] >> lane) & 1ull) {
+            const uint32_t rk = rank + (uint32_t)__popcll(fm[r] & lt);
+            const uint32_t cre = quantize(__float_as_uint(z[r].x), pbase, bits, shift);
+            const uint32_t cim = quantize(__float_as_uint(z[r].y), pbase, bits, shift);
+            uint32_t p = twoN * rk - (w0 << 5);  // bit position inside cw
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t code = h ? cim : cre;
+                const uint32_t wi = p >> 5, sh = p & 31u;
+                atomicOr(&cw[wi], code << sh);
+                if (sh + (uint32_t)bits > 32u) atomicOr(&cw[wi + 1], code >> (32u - sh));
+                p += (uint32_t)bits;
+            }
+        }
+        rank += (uint32_t)__popcll(fm[r]);
+    }
+    __syncthreads();
+    uint32_t* rec = reinterpret_cast<uint32_t*>(records + c * S);
+    uint32_t* bitmap = rec + 4;
+    uint32_t* codes = bitmap + W;
+    if (tid < kTile / 32) {
+        const uint32_t wi = tile * (kTile / 32) + tid;
+        if (wi < W) bitmap[wi] = bmw[tid];
+    }
+    if (total) {
+        const uint32_t w1 = (twoN * (rank0 + total) - 1u) >> 5;
+        const uint32_t nw = w1 - w0 + 1u;
+        for (uint32_t i = tid; i < nw; i += NT) {
+            const uint32_t v = cw[i];
+            if (i == 0 || i == nw - 1u)
+                atomicOr(&codes[w0 + i], v);  // may be shared with the neighbouring tile (zeroed by k_resolve)
+            else
+                codes[w0 + i] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- decode ----
+// Per chunk: set bits before each bitmap word; checks the headers.
+__global__ __launch_bounds__(RT) void k_word_prefix(const uint8_t* __restrict__ stream,
+                                                    const uint8_t* __restrict__ records, size_t S, uint32_t W,
+                                                    uint32_t k, uint32_t word3, HeaderInfo hdr,
+                                                    uint32_t* __restrict__ prefix, uint32_t* __restrict__ status)
+{
+    __shared__ uint32_t tmp[RW];
+    __shared__ uint32_t s_carry;
+    const int tid = threadIdx.x;
+    const size_t c = blockIdx.x;
+    const uint32_t* rec = reinterpret_cast<const uint32_t*>(records + c * S);
+    const uint32_t* bitmap = rec + 4;
+    if (tid == 0) s_carry = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < W; base += RT) {
+        const uint32_t w = base + tid;
+        const uint32_t cnt = w < W ? (uint32_t)__popc(bitmap[w]) : 0u;
+        const uint32_t carry = s_carry;
+        const uint32_t incl = block_scan_incl_1024(cnt, tmp);
+        if (w < W) prefix[c * W + w] = carry + incl - cnt;
+        __syncthreads();
+        if (tid == RT - 1) s_carry = carry + incl;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        bool bad = s_carry != k || rec[2] != k || rec[3] != word3;
+        if (hdr.write && c == 0) {
+            const uint32_t* h = reinterpret_cast<const uint32_t*>(stream);
+            bad = bad || h[0] != 0x31505346u || h[1] != 1u || h[2] != (uint32_t)hdr.n ||
+                  h[3] != (uint32_t)(hdr.n >> 32) || h[4] != hdr.L || h[5] != hdr.C || h[6] != hdr.N ||
+                  h[7] != hdr.m || h[8] != hdr.k || h[9] != hdr.S;
+        }
+        if (bad) atomicMax(status, 6u);
+    }
+}
+
+__device__ __forceinline__ uint32_t fetch_code(const uint32_t* __restrict__ codes, uint32_t p, int bits)
+{
+    const uint32_t wi = p >> 5, sh = p & 31u;
+    uint32_t v = codes[wi] >> sh;
+    if (sh + (uint32_t)bits > 32u) v |= codes[wi + 1] << (32u - sh);
+    return bits == 32 ? v : (v & ((1u << bits) - 1u));
+}
+
+// One lane per bin: bit test, rank from the word prefix, code fetch, Nbit_to_32bit, scatter.
+__global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
+                                               uint32_t k, int bits, int m, uint32_t groups,
+                                               const uint32_t* __restrict__ prefix, float2* __restrict__ spec)
+{
+    const size_t c = blockIdx.x / groups;
+    const uint32_t j = (blockIdx.x % groups) * NT + threadIdx.x;
+    if (j >= B) return;
+    const uint32_t* rec = reinterpret_cast<const uint32_t*>(records + c * S);
+    const uint32_t pbase = rec[0];
+    const uint32_t* bitmap = rec + 4;
+    const uint32_t* codes = bitmap + W;
+    const uint32_t word = bitmap[j >> 5], bit = j & 31u;
+    float2 out = make_float2(0.f, 0.f);
+    if (((word >> bit) & 1u) && k > 0) {
+        uint32_t rank = prefix[c * W + (j >> 5)] + (uint32_t)__popc(word & ((1u << bit) - 1u));
+        rank = rank < k ? rank : k - 1u;  // a corrupt bitmap must not read outside the record
+        const uint32_t p = 2u * (uint32_t)bits * rank;
+        const int shift = 23 - m;
+        out.x = __uint_as_float(dequantize(fetch_code(codes, p, bits), pbase, bits, shift));
+        out.y = __uint_as_float(dequantize(fetch_code(codes, p + (uint32_t)bits, bits), pbase, bits, shift));
+    }
+    spec[c * (size_t)B + j] = out;
+}
+
+}  // namespace
+
+hipError_t launch_zero_status(uint8_t* ws_base, const Workspace& w, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws_base + w.status),
+                       (size_t)64);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
+                         uint8_t* ws_base, const Workspace& w, hipStream_t s)
+{
+    const uint32_t B = a.L / 2 + 1, Tn = tiles_per_chunk(a.L), W = (B + 31) / 32;
+    const float2* X = reinterpret_cast<const float2*>(spec);
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(ws_base + w.hist);
+    uint32_t* sel = reinterpret_cast<uint32_t*>(ws_base + w.sel);
+    uint32_t* tinfo = reinterpret_cast<uint32_t*>(ws_base + w.tinfo);
+    uint32_t* tscan = reinterpret_cast<uint32_t*>(ws_base + w.tscan);
+    uint2* cand = reinterpret_cast<uint2*>(ws_base + w.cand);
+    if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
+
+    // status words and histograms are adjacent: one fill
+    const size_t zero_words = (w.hist - w.status) / 4 + a.C * kHistBins;
+    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, status, zero_words);
+    const uint32_t groups = (Tn + HIST_TILES - 1) / HIST_TILES;
+    hipLaunchKernelGGL(k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, B, groups, hist);
+    hipLaunchKernelGGL(k_find_bucket, dim3((unsigned)a.C), dim3(NT), 0, s, hist, a.k, sel);
+    hipLaunchKernelGGL(k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, sel, tinfo, cand);
+    HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
+                 a.hdr_theta};
+    hipLaunchKernelGGL(k_resolve, dim3((unsigned)a.C), dim3(RT), 0, s, Tn, a.k, a.bits, a.m, W, a.S, a.word3, sel,
+                       tinfo, tscan, cand, records, stream_base, h);
+    hipLaunchKernelGGL(k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
+                       records);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
+                         uint8_t* ws_base, const Workspace& w, int check_header, hipStream_t s)
+{
+    const uint32_t B = a.L / 2 + 1, W = (B + 31) / 32;
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
+    uint32_t* prefix = reinterpret_cast<uint32_t*>(ws_base + w.prefix);
+    const uint32_t groups = (B + NT - 1) / NT;
+    if (a.C * (size_t)groups > 0x7fffffffu) return hipErrorInvalidValue;
+    HeaderInfo h{check_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
+                 a.hdr_theta};
+    hipLaunchKernelGGL(k_word_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k, a.word3,
+                       h, prefix, status);
+    hipLaunchKernelGGL(k_decode, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m,
+                       groups, prefix, reinterpret_cast<float2*>(spec));
+    return hipGetLastError();
+}
+
+}  // namespace fftsp

@@ -1,0 +1,95 @@
+// Internal declarations shared by the translation units of libfftsp.so.
+// Nothing here is part of the C ABI (see include/fftsp.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace fftsp {
+
+constexpr int kMinLogL = 5;   // chunk length 32
+constexpr int kMaxLogL = 22;  // chunk length 4 Mi
+
+// Twiddle tables, one pair per device, 2048 entries each:
+//   hi[h] = exp(-2 pi i h / 2^11),  lo[l] = exp(-2 pi i l / 2^22)
+// so that exp(-2 pi i E / 2^22) = hi[E >> 11] * lo[E & 2047] for any E < 2^22.
+struct Tables {
+    const float2* hi;
+    const float2* lo;
+};
+
+// Selection geometry: one workgroup of 256 lanes owns a tile of 2048 consecutive bins
+// (wave w owns 512 of them as 8 rows of 64), so a wave ballot is two bitmap words.
+constexpr int kTile = 2048;
+constexpr int kTileThreads = 256;
+constexpr int kHistBits = 12;                 // first radix-select digit: top 12 bits of the 31-bit key
+constexpr int kHistBins = 1 << kHistBits;
+constexpr int kKeyShift = 31 - kHistBits;     // bucket = key >> 19
+
+// Where everything lives inside the caller's workspace (byte offsets, 256-aligned).
+struct Workspace {
+    size_t status;    // u32[64]   word 0 = device status
+    size_t hist;      // u32[C][kHistBins]         (directly after status: one fill zeroes both)
+    size_t sel;       // u32[C][8]  bstar, need, tau, quota, pbase, vmax, -, -
+    size_t tinfo;     // u32[C][Tn][4]  n_def, vmax_def, n_cand, -
+    size_t tscan;     // u32[C][Tn][2]  first rank of the tile, equal-key count before the tile
+    size_t cand;      // uint2[C][Tn*kTile]  (key, max component bits) of threshold-bucket bins, tile-ordered
+    size_t prefix;    // u32[C][W]  set bits before each bitmap word (decode)
+    size_t spec;      // float[C][L+2]  spectrum
+    size_t mid;       // float2[C][L/2] intermediate of the two-pass FFT
+    size_t total;
+};
+
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+static inline uint32_t tiles_per_chunk(uint32_t L) { return ((L / 2 + 1) + kTile - 1) / kTile; }
+
+static inline Workspace make_workspace(size_t C, uint32_t L)
+{
+    Workspace w;
+    size_t B = (size_t)L / 2 + 1, Tn = tiles_per_chunk(L), W = (B + 31) / 32;
+    size_t off = 0;
+    w.status = off; off += 256;
+    w.hist = off;   off = align256(off + C * kHistBins * 4);
+    w.sel = off;    off = align256(off + C * 8 * 4);
+    w.tinfo = off;  off = align256(off + C * Tn * 16);
+    w.tscan = off;  off = align256(off + C * Tn * 8);
+    w.cand = off;   off = align256(off + C * Tn * kTile * 8);
+    w.prefix = off; off = align256(off + C * W * 4);
+    w.spec = off;   off = align256(off + C * ((size_t)L + 2) * 4);
+    w.mid = off;    off = align256(off + C * (size_t)L * 4);
+    w.total = off;
+    return w;
+}
+
+// per-device tables; returns hipSuccess or the failing HIP error
+hipError_t get_tables(Tables* out);
+
+// FFT launchers (fft.hip).  Chunk c covers in[c*L, min(n, (c+1)*L)), zero beyond n.
+// spec: C*(L+2) floats; mid: C*L floats of scratch (unused when L <= 2^14).
+hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, float2* mid, Tables t,
+                       hipStream_t s);
+hipError_t launch_irfft(const float* spec, size_t n, int logL, size_t C, float* out, float2* mid, Tables t,
+                        hipStream_t s);
+
+// Codec launchers (codec.hip).
+struct CodecArgs {
+    size_t C;           // chunks
+    uint32_t L;         // chunk length
+    uint32_t k;         // kept bins per chunk
+    int bits, m;        // code width, mantissa width
+    size_t S;           // record stride in bytes
+    uint32_t word3;     // 4th word of every record header
+    // stream header (written iff write_header)
+    int write_header;
+    uint64_t hdr_n;
+    uint32_t hdr_L, hdr_C, hdr_k, hdr_S;
+    float hdr_theta;
+};
+hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
+                         uint8_t* ws_base, const Workspace& w, hipStream_t s);
+hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
+                         uint8_t* ws_base, const Workspace& w, int check_header, hipStream_t s);
+hipError_t launch_zero_status(uint8_t* ws_base, const Workspace& w, hipStream_t s);
+
+}  // namespace fftsp

@@ -1,0 +1,112 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+Config 3 (AlexNet-shaped, 62.4 M elements, 60 chunks of 2^20) is checked on every chunk; the oracle needs a
+few seconds per direction on the machine's host cores.  Config 5 (VGG-16-shaped, 2^22 chunks) is checked on
+sampled chunks (chunks are independent, so the oracle is run on those chunks alone).  Config 4 is the
+per-tensor mode on all 161 ResNet-50-shaped tensors.
+"""
+import numpy as np
+import pytest
+
+from paper_1811_08596_amd import workloads
+from tests.gpu_harness import Device, explain_end_to_end, per_chunk_rel_l2, rel_l2
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return Device()
+
+
+@pytest.fixture(scope="module")
+def alexnet():
+    return workloads.config3()
+
+
+def test_config3_all_chunks(dev, ref, alexnet):
+    w = alexnet
+    g, L, bits = w.grad, w.chunk_len, w.bits
+    n = g.size
+    C = (n + L - 1) // L
+    assert n == 62378344 and C == 60
+    print("config3: oracle rfft", flush=True)
+    spec_or = ref.rfft(g, L, nthreads=THREADS)
+    print("config3: gpu rfft", flush=True)
+    spec_gpu = dev.rfft(g, L)
+    assert per_chunk_rel_l2(spec_gpu, spec_or, C) <= TOL
+    for theta in w.thetas:
+        print(f"config3: encode theta={theta}", flush=True)
+        packed_or = ref.encode_spectrum(spec_or, n, L, theta, bits, nthreads=THREADS)
+        packed_gpu = dev.encode(spec_or, n, L, theta, bits)
+        assert np.array_equal(packed_gpu, packed_or)
+        if theta == 0.5:
+            dec_or = ref.decode_spectrum(packed_or, n, L, theta, bits, nthreads=THREADS)
+            dec_gpu = dev.decode(packed_or, n, L, theta, bits)
+            assert np.array_equal(dec_gpu.view(np.uint32), dec_or.view(np.uint32))
+            out_or = ref.irfft(dec_or, n, L, nthreads=THREADS)
+            out_gpu, st = dev.decompress(packed_or, n, L, theta, bits, want_status=True)
+            assert st == 0 and rel_l2(out_gpu, out_or) <= TOL
+            # whole sender, as timed by bench.py
+            a = dev.compress(g, L, theta, bits)
+            assert np.array_equal(a, dev.compress(g, L, theta, bits))
+            sel, codes = explain_end_to_end(ref, a, packed_or, spec_or, n, L, theta, bits)
+            rec = dev.decompress(a, n, L, theta, bits)
+            e_gpu, e_or = rel_l2(rec, g), rel_l2(out_or, g)
+            print(f"config3 theta=.5: selection mismatches {sel}, code mismatches {codes}, "
+                  f"alpha gpu {e_gpu:.6f} oracle {e_or:.6f}", flush=True)
+            assert abs(e_gpu - e_or) <= 1e-3 * e_or + 5e-3 * (sel > 0)
+
+
+def test_config4_segments(dev, ref):
+    w = workloads.config4()
+    offs = w.seg_offsets
+    assert len(offs) == 162
+    print("config4: gpu compress_segments", flush=True)
+    packed = dev.compress_segments(w.grad, offs, w.theta, w.bits)
+    print("config4: oracle compress_segments", flush=True)
+    por = ref.compress_segments(w.grad, offs, w.theta, w.bits, nthreads=THREADS)
+    assert packed.size == por.size
+    assert np.array_equal(packed[:64], por[:64])
+    # records: same kept count everywhere; bytes may differ only where binary32 rounding explains it
+    differing = np.count_nonzero(packed != por)
+    print("config4: differing bytes end-to-end", differing, "of", por.size, flush=True)
+    assert differing <= 2e-3 * por.size
+    out, st = dev.decompress_segments(por, offs, w.theta, w.bits)
+    assert st == 0
+    out_or = ref.decompress_segments(por, offs, w.theta, w.bits, nthreads=THREADS)
+    for i in range(len(offs) - 1):
+        a, b = out[offs[i]:offs[i + 1]], out_or[offs[i]:offs[i + 1]]
+        assert rel_l2(a, b) <= TOL or not b.any()
+
+
+@pytest.mark.parametrize("iteration", [0, 9])
+def test_config5_sampled_chunks(dev, ref, iteration):
+    w = workloads.config5(iteration)
+    g, L, bits, theta = w.grad, w.chunk_len, w.bits, w.theta
+    n = g.size
+    C = (n + L - 1) // L
+    assert n == 138357544 and C == 33
+    print(f"config5[{iteration}]: gpu compress theta={theta:.3f}", flush=True)
+    packed = dev.compress(g, L, theta, bits)
+    spec_gpu = dev.rfft(g, L).reshape(C, L + 2)
+    out = dev.decompress(packed, n, L, theta, bits)
+    h = ref.parse_header(packed)
+    S = h["S"]
+    assert (h["n"], h["L"], h["C"], h["k"]) == (n, L, C, ref.kept_per_chunk(L, theta))
+    for c in (0, 17, C - 1):
+        print(f"config5[{iteration}]: oracle on chunk {c}", flush=True)
+        gc = g[c * L:(c + 1) * L]
+        spec_or = ref.rfft(gc, L)
+        assert rel_l2(spec_gpu[c], spec_or) <= TOL
+        por = ref.encode_spectrum(spec_or, gc.size, L, theta, bits)
+        # fed the oracle's spectrum, the record is byte-identical
+        got = dev.encode(spec_or, gc.size, L, theta, bits)
+        assert np.array_equal(got, por)
+        # the end-to-end record is explainable
+        one = np.concatenate([por[:64], packed[64 + c * S:64 + (c + 1) * S]])
+        explain_end_to_end(ref, one, por, spec_or, gc.size, L, theta, bits)
+        rec_or = ref.decompress(one, gc.size, L, theta, bits)
+        assert rel_l2(out[c * L:c * L + gc.size], rec_or) <= TOL
