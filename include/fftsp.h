@@ -119,6 +119,14 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
  * (FFTSP_OK or FFTSP_EFORMAT).  Returns FFTSP_EHIP if the copy fails. */
 int fftsp_device_status(const void* d_workspace, int* status_out);
 
+/* Per-kernel timing for benchmarks (not part of the method).  While enabled, every kernel the library
+ * launches is bracketed by two HIP events on its stream (do not enable under stream capture).
+ * fftsp_profile_enable(1) also discards earlier records.  fftsp_profile_report synchronises the device and
+ * writes one text line per kernel, "name calls total_ms", NUL-terminated, into buf (HOST memory, cap bytes);
+ * it returns the number of bytes the full report needs. */
+int fftsp_profile_enable(int on);
+size_t fftsp_profile_report(char* buf, size_t cap);
+
 const char* fftsp_strerror(int status);
 const char* fftsp_version(void);
 

@@ -448,6 +448,23 @@ int fftsp_device_status(const void* d_workspace, int* status_out)
     return FFTSP_OK;
 }
 
+int fftsp_profile_enable(int on)
+{
+    prof::enable(on != 0);
+    return FFTSP_OK;
+}
+
+size_t fftsp_profile_report(char* buf, size_t cap)
+{
+    const std::string r = prof::report();
+    if (buf && cap > 0) {
+        const size_t ncopy = r.size() < cap - 1 ? r.size() : cap - 1;
+        std::memcpy(buf, r.data(), ncopy);
+        buf[ncopy] = 0;
+    }
+    return r.size() + 1;
+}
+
 const char* fftsp_strerror(int status)
 {
     switch (status) {

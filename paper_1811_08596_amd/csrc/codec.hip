@@ -601,7 +601,7 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
 
 hipError_t launch_zero_status(uint8_t* ws_base, const Workspace& w, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_zero_u32, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws_base + w.status),
+    FFTSP_LAUNCH("zero_fill", k_zero_u32, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws_base + w.status),
                        (size_t)64);
     return hipGetLastError();
 }
@@ -621,16 +621,16 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
 
     // status words and histograms are adjacent: one fill
     const size_t zero_words = (w.hist - w.status) / 4 + a.C * kHistBins;
-    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, status, zero_words);
+    FFTSP_LAUNCH("zero_fill", k_zero_u32, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, status, zero_words);
     const uint32_t groups = (Tn + HIST_TILES - 1) / HIST_TILES;
-    hipLaunchKernelGGL(k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, B, groups, hist);
-    hipLaunchKernelGGL(k_find_bucket, dim3((unsigned)a.C), dim3(NT), 0, s, hist, a.k, sel);
-    hipLaunchKernelGGL(k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, sel, tinfo, cand);
+    FFTSP_LAUNCH("hist", k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, B, groups, hist);
+    FFTSP_LAUNCH("find_bucket", k_find_bucket, dim3((unsigned)a.C), dim3(NT), 0, s, hist, a.k, sel);
+    FFTSP_LAUNCH("collect", k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, sel, tinfo, cand);
     HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
                  a.hdr_theta};
-    hipLaunchKernelGGL(k_resolve, dim3((unsigned)a.C), dim3(RT), 0, s, Tn, a.k, a.bits, a.m, W, a.S, a.word3, sel,
+    FFTSP_LAUNCH("resolve", k_resolve, dim3((unsigned)a.C), dim3(RT), 0, s, Tn, a.k, a.bits, a.m, W, a.S, a.word3, sel,
                        tinfo, tscan, cand, records, stream_base, h);
-    hipLaunchKernelGGL(k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
+    FFTSP_LAUNCH("emit", k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
                        records);
     return hipGetLastError();
 }
@@ -645,9 +645,9 @@ hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, con
     if (a.C * (size_t)groups > 0x7fffffffu) return hipErrorInvalidValue;
     HeaderInfo h{check_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
                  a.hdr_theta};
-    hipLaunchKernelGGL(k_word_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k, a.word3,
+    FFTSP_LAUNCH("word_prefix", k_word_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k, a.word3,
                        h, prefix, status);
-    hipLaunchKernelGGL(k_decode, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m,
+    FFTSP_LAUNCH("decode", k_decode, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m,
                        groups, prefix, reinterpret_cast<float2*>(spec));
     return hipGetLastError();
 }

@@ -488,7 +488,7 @@ hipError_t small_fwd(const float* in, size_t n, size_t C, float2* spec, Tables t
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
-    hipLaunchKernelGGL(kern, dim3((unsigned)((C + per - 1) / per)), dim3(kNT), lds, s, in, n, C, spec, t, aligned);
+    FFTSP_LAUNCH("rfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kNT), lds, s, in, n, C, spec, t, aligned);
     return hipGetLastError();
 }
 
@@ -501,7 +501,7 @@ hipError_t small_inv(const float2* spec, size_t n, size_t C, float* out, Tables 
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
-    hipLaunchKernelGGL(kern, dim3((unsigned)((C + per - 1) / per)), dim3(kNT), lds, s, spec, n, C, out, t, aligned);
+    FFTSP_LAUNCH("irfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kNT), lds, s, spec, n, C, out, t, aligned);
     return hipGetLastError();
 }
 
@@ -515,7 +515,7 @@ hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tab
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t tiles = ((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, in, n, logM, mid, t, aligned);
+    FFTSP_LAUNCH("rfft_pass_a", kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, in, n, logM, mid, t, aligned);
     return hipGetLastError();
 }
 
@@ -527,7 +527,7 @@ hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, Tables t, 
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t tiles = ((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, mid, logM, spec, t);
+    FFTSP_LAUNCH("rfft_pass_b", kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, mid, logM, spec, t);
     return hipGetLastError();
 }
 
@@ -539,7 +539,7 @@ hipError_t inv_b(const float2* spec, int logM, size_t C, float2* mid, Tables t, 
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t tiles = ((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, spec, logM, mid, t);
+    FFTSP_LAUNCH("irfft_pass_b", kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, spec, logM, mid, t);
     return hipGetLastError();
 }
 
@@ -551,7 +551,7 @@ hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Ta
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t tiles = ((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1);
-    hipLaunchKernelGGL(kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, mid, logM, out, n, t, aligned);
+    FFTSP_LAUNCH("irfft_pass_a", kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, mid, logM, out, n, t, aligned);
     return hipGetLastError();
 }
 

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <string>
 
 namespace fftsp {
 
@@ -61,6 +62,23 @@ static inline Workspace make_workspace(size_t C, uint32_t L)
     w.total = off;
     return w;
 }
+
+// Optional per-kernel event timing (prof.hip).
+namespace prof {
+bool enabled();
+int begin(const char* name, hipStream_t s);
+void end(int id, hipStream_t s);
+void enable(bool on);
+std::string report();
+}  // namespace prof
+
+// Launch `kernel` and, when profiling is on, bracket it with events under `name`.
+#define FFTSP_LAUNCH(name, kernel, grid, block, lds, stream, ...)                    \
+    do {                                                                             \
+        const int fftsp_prof_id_ = ::fftsp::prof::enabled() ? ::fftsp::prof::begin(name, stream) : -1; \
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);           \
+        if (fftsp_prof_id_ >= 0) ::fftsp::prof::end(fftsp_prof_id_, stream);         \
+    } while (0)
 
 // per-device tables; returns hipSuccess or the failing HIP error
 hipError_t get_tables(Tables* out);

@@ -39,6 +39,8 @@ SIGNATURES = {
     "fftsp_decompress_segments": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, _szp, C.c_int, C.c_float, C.c_int,
                                             C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_device_status": (C.c_int, [C.c_void_p, C.POINTER(C.c_int)]),
+    "fftsp_profile_enable": (C.c_int, [C.c_int]),
+    "fftsp_profile_report": (C.c_size_t, [C.c_char_p, C.c_size_t]),
     "fftsp_strerror": (C.c_char_p, [C.c_int]),
     "fftsp_version": (C.c_char_p, []),
 }
@@ -181,6 +183,22 @@ def device_status(workspace) -> int:
     st = C.c_int()
     _check(load().fftsp_device_status(_ptr(workspace), C.byref(st)), "fftsp_device_status")
     return st.value
+
+
+def profile_enable(on: bool) -> None:
+    _check(load().fftsp_profile_enable(1 if on else 0), "fftsp_profile_enable")
+
+
+def profile_report() -> dict:
+    """{kernel name: (calls, total milliseconds)} of the launches since profile_enable(True)"""
+    need = load().fftsp_profile_report(None, 0)
+    buf = C.create_string_buffer(need + 64)
+    load().fftsp_profile_report(buf, len(buf))
+    out = {}
+    for line in buf.value.decode().splitlines():
+        name, calls, ms = line.split()
+        out[name] = (int(calls), float(ms))
+    return out
 
 
 def version() -> str:
