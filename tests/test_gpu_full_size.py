@@ -70,10 +70,28 @@ def test_config4_segments(dev, ref):
     por = ref.compress_segments(w.grad, offs, w.theta, w.bits, nthreads=THREADS)
     assert packed.size == por.size
     assert np.array_equal(packed[:64], por[:64])
-    # records: same kept count everywhere; bytes may differ only where binary32 rounding explains it
-    differing = np.count_nonzero(packed != por)
-    print("config4: differing bytes end-to-end", differing, "of", por.size, flush=True)
-    assert differing <= 2e-3 * por.size
+    # record by record: the end-to-end stream may differ from the oracle's only where binary32 rounding explains it
+    # (one swapped bin shifts every later code of that record, so bytes are compared through the decoder)
+    pos, sel_total, code_total = 64, 0, 0
+    for i in range(len(offs) - 1):
+        seg = w.grad[offs[i]:offs[i + 1]]
+        L = ref.segment_length(seg.size)
+        spec_or = ref.rfft(seg, L)
+        one_or = ref.encode_spectrum(spec_or, seg.size, L, w.theta, w.bits)
+        S = one_or.size - 64
+        rec_or = por[pos:pos + S].copy()
+        rec_gpu = packed[pos:pos + S].copy()
+        assert int(rec_or[12:16].view("<u4")[0]) == L == int(rec_gpu[12:16].view("<u4")[0])
+        rec_or[12:16] = 0
+        rec_gpu[12:16] = 0
+        assert np.array_equal(rec_or, one_or[64:])
+        sel, codes = explain_end_to_end(ref, np.concatenate([one_or[:64], rec_gpu]), one_or, spec_or, seg.size, L,
+                                        w.theta, w.bits)
+        sel_total += sel
+        code_total += codes
+        pos += S
+    assert pos == por.size
+    print("config4: end-to-end selection mismatches", sel_total, "code mismatches", code_total, flush=True)
     out, st = dev.decompress_segments(por, offs, w.theta, w.bits)
     assert st == 0
     out_or = ref.decompress_segments(por, offs, w.theta, w.bits, nthreads=THREADS)
