@@ -207,7 +207,7 @@ int fftsp_rfft(const float* d_grad, size_t n, uint32_t chunk_len, float* d_spec,
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     return hip_status(launch_rfft(d_grad, n, p.logL, p.C, d_spec, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                                  reinterpret_cast<hipStream_t>(stream)));
+                                  nullptr, nullptr, reinterpret_cast<hipStream_t>(stream)));
 }
 
 int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad_out, void* d_workspace,
@@ -239,7 +239,7 @@ int fftsp_encode_spectrum(const float* d_spec, size_t n, uint32_t chunk_len, flo
     if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     uint8_t* out = static_cast<uint8_t*>(d_packed);
-    return hip_status(launch_encode(d_spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws,
+    return hip_status(launch_encode(d_spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws, 0,
                                     reinterpret_cast<hipStream_t>(stream)));
 }
 
@@ -277,8 +277,13 @@ int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float thet
     uint8_t* out = static_cast<uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
-    hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, reinterpret_cast<float2*>(ws + p.ws.mid), t, s);
-    if (e == hipSuccess) e = launch_encode(spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws, s);
+    int hist_done = 0;
+    hipError_t e = launch_zero_hist(ws, p.ws, p.C, s);
+    if (e == hipSuccess)
+        e = launch_rfft(d_grad, n, p.logL, p.C, spec, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+                        reinterpret_cast<uint32_t*>(ws + p.ws.hist), &hist_done, s);
+    if (e == hipSuccess)
+        e = launch_encode(spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws, hist_done, s);
     return hip_status(e);
 }
 
@@ -379,9 +384,13 @@ int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int 
         a.hdr_S = 0;
         a.hdr_theta = theta;
         float* spec = reinterpret_cast<float*>(ws + w.spec);
-        hipError_t e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec,
-                                   reinterpret_cast<float2*>(ws + w.mid), t, s);
-        if (e == hipSuccess) e = launch_encode(spec, a, out, out + rec_off, ws, w, s);
+        int hist_done = 0;
+        hipError_t e = launch_zero_hist(ws, w, 1, s);
+        if (e == hipSuccess)
+            e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec,
+                            reinterpret_cast<float2*>(ws + w.mid), t, reinterpret_cast<uint32_t*>(ws + w.hist),
+                            &hist_done, s);
+        if (e == hipSuccess) e = launch_encode(spec, a, out, out + rec_off, ws, w, hist_done, s);
         if (e != hipSuccess) return FFTSP_EHIP;
         rec_off += a.S;
     }

@@ -606,12 +606,21 @@ hipError_t launch_zero_status(uint8_t* ws_base, const Workspace& w, hipStream_t 
     return hipGetLastError();
 }
 
+// status words and histograms are adjacent: one fill
+hipError_t launch_zero_hist(uint8_t* ws_base, const Workspace& w, size_t C, hipStream_t s)
+{
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
+    const size_t zero_words = (w.hist - w.status) / 4 + C * kHistBins;
+    FFTSP_LAUNCH("zero_fill", k_zero_u32, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, status,
+                 zero_words);
+    return hipGetLastError();
+}
+
 hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
-                         uint8_t* ws_base, const Workspace& w, hipStream_t s)
+                         uint8_t* ws_base, const Workspace& w, int hist_ready, hipStream_t s)
 {
     const uint32_t B = a.L / 2 + 1, Tn = tiles_per_chunk(a.L), W = (B + 31) / 32;
     const float2* X = reinterpret_cast<const float2*>(spec);
-    uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
     uint32_t* hist = reinterpret_cast<uint32_t*>(ws_base + w.hist);
     uint32_t* sel = reinterpret_cast<uint32_t*>(ws_base + w.sel);
     uint32_t* tinfo = reinterpret_cast<uint32_t*>(ws_base + w.tinfo);
@@ -619,11 +628,12 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     uint2* cand = reinterpret_cast<uint2*>(ws_base + w.cand);
     if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
 
-    // status words and histograms are adjacent: one fill
-    const size_t zero_words = (w.hist - w.status) / 4 + a.C * kHistBins;
-    FFTSP_LAUNCH("zero_fill", k_zero_u32, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, status, zero_words);
-    const uint32_t groups = (Tn + HIST_TILES - 1) / HIST_TILES;
-    FFTSP_LAUNCH("hist", k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, B, groups, hist);
+    if (!hist_ready) {
+        hipError_t e = launch_zero_hist(ws_base, w, a.C, s);
+        if (e != hipSuccess) return e;
+        const uint32_t groups = (Tn + HIST_TILES - 1) / HIST_TILES;
+        FFTSP_LAUNCH("hist", k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, B, groups, hist);
+    }
     FFTSP_LAUNCH("find_bucket", k_find_bucket, dim3((unsigned)a.C), dim3(NT), 0, s, hist, a.k, sel);
     FFTSP_LAUNCH("collect", k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, sel, tinfo, cand);
     HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,

@@ -11,7 +11,7 @@
 // chunks per workgroup when M is tiny).  Larger M is factored M = N1*N2 and done
 // in two LDS-resident passes with a transposed intermediate:
 //   pass A: for a tile of TA adjacent columns n2, N1-point FFTs over n1 (stride N2),
-//           times W_M^(n2 k1), stored as mid[n2*N1 + k1] (contiguous in k1);
+//           times W_M^(n2 k1), stored as runs of N1 values per n2 (row k1 next to row N1-k1);
 //   pass B: for a tile of rows k1 together with the mirrored rows N1-k1, N2-point
 //           FFTs over n2; Z[k1 + N1 k2] and its partner Z[M-k] then sit in the same
 //           workgroup, so the real-FFT split happens in LDS before the only store.
@@ -289,187 +289,356 @@ __global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spe
 }
 
 // --------------------------------------------------------------- two pass ---
-// Forward pass A: N1-point FFTs down the columns of the N1 x N2 view of z.
-template <int LOGN1, int LOGE, int NT>
-__global__ __launch_bounds__(NT) void k_fwd_a(const float* __restrict__ in, size_t n, int logM,
-                                              float2* __restrict__ mid, Tables tb, int aligned)
+// The two-pass kernels are persistent: a workgroup of 512 lanes walks a contiguous run of tiles and, while
+// the LDS FFT of tile i runs, the global loads of tile i+1 are already in flight into registers.
+//
+// Twiddles outside the LDS stages are not gathered per element.  Along the index a lane walks, the exponent
+// grows by a fixed step, so W^(e0 + j*step) = W^e0 * (W^step)^j: one table lookup for the base, one for the
+// ratio, then a short recurrence that is re-anchored from the table every 8 steps; for the even/odd split the
+// step is always 1/32 of a turn, so exact constants are used instead of a recurrence.
+
+// Loop-invariant per-lane addresses (LDS swizzles, global offsets of 16 loads and 16 stores, four stages of
+// butterfly indices) would otherwise be hoisted out of the persistent loop and held in ~100 VGPRs; making the
+// lane id opaque once per iteration has them recomputed (a few integer ops) and keeps two workgroups per CU.
+__device__ __forceinline__ int opaque_lane(int v)
 {
+    asm volatile("" : "+v"(v));
+    return v;
+}
+
+constexpr int kNT = 512;   // lanes per workgroup in the two-pass kernels
+constexpr int kLogE = 13;  // 8192 complex points (64 KiB) per tile
+constexpr int kPer = (1 << kLogE) / kNT;
+constexpr int kSplitStep = (16 * kNT) >> kLogE;  // 32nds of a turn between a lane's consecutive split twiddles
+constexpr int kHistLdsWords = kHistBins / 2;  // 16-bit counters, two per word
+
+// exp(-2 pi i q / 32), q = 0..15
+__device__ constexpr float kW32re[16] = {1.0f, 0.98078528040323043f, 0.92387953251128674f, 0.83146961230254524f,
+                                         0.70710678118654752f, 0.55557023301960223f, 0.38268343236508977f,
+                                         0.19509032201612827f, 0.0f, -0.19509032201612827f, -0.38268343236508977f,
+                                         -0.55557023301960223f, -0.70710678118654752f, -0.83146961230254524f,
+                                         -0.92387953251128674f, -0.98078528040323043f};
+__device__ constexpr float kW32im[16] = {-0.0f, -0.19509032201612827f, -0.38268343236508977f, -0.55557023301960223f,
+                                         -0.70710678118654752f, -0.83146961230254524f, -0.92387953251128674f,
+                                         -0.98078528040323043f, -1.0f, -0.98078528040323043f, -0.92387953251128674f,
+                                         -0.83146961230254524f, -0.70710678118654752f, -0.55557023301960223f,
+                                         -0.38268343236508977f, -0.19509032201612827f};
+
+// The intermediate between the two passes is stored "paired": within each run of N1 values, row k1 and its
+// mirror N1-k1 (the two rows the real-FFT split combines) sit next to each other,
+//     position 2*k1   holds row k1        (k1 < N1/2)
+//     position 2*k1+1 holds row N1-k1     (position 1 holds row N1/2, which like row 0 is its own mirror)
+// so a pass-B tile of TB rows plus their mirrors is one contiguous run of 2*TB positions (128 bytes for TB = 8).
+__device__ __forceinline__ uint32_t row_of_pos(uint32_t p, uint32_t N1)
+{
+    return (p & 1u) ? (p == 1u ? N1 / 2 : N1 - (p >> 1)) : (p >> 1);
+}
+
+// Forward pass A: N1-point FFTs down the columns of the N1 x N2 view of z, for tiles of TA adjacent columns.
+template <int LOGN1>
+__global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, size_t n, int logM,
+                                               float2* __restrict__ mid, Tables tb, int aligned, uint32_t total,
+                                               uint32_t per_wg)
+{
+    constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
+    constexpr int KN = N1 >= NT ? N1 / NT : 1;   // distinct k1 per lane in the store loop
+    constexpr int DC = N1 >= NT ? 1 : NT / N1;   // column step between a lane's consecutive stores
+    constexpr int NCOL = PER / KN;
     extern __shared__ float2 smem[];
     float2* d = smem;
     float2* tw = smem + ELEMS;
-    const int tid = threadIdx.x;
+    const int tid0 = threadIdx.x;
     const uint32_t M = 1u << logM, N2 = M >> LOGN1, tiles = N2 >> LOGT;
-    const size_t c = blockIdx.x / tiles;
-    const uint32_t col0 = (blockIdx.x % tiles) << LOGT;
-    load_stage_twiddles<LOGN1, NT>(tw, tb, tid);
-    const size_t cbase = c * (size_t)(2 * (size_t)M);
+    uint32_t t = blockIdx.x * per_wg;
+    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
+    if (t >= tend) return;
+    load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
+
+    float2 r[PER];
+    auto load_tile = [&](uint32_t tile, int tid) {
+        const size_t cbase = (size_t)(tile / tiles) * (size_t)(2 * (size_t)M);
+        const uint32_t col0 = (tile % tiles) << LOGT;
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-        const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + col);
-        d[sw_idx<LOGT>(n1, col)] = load_pair(in, gi, n, aligned);
-    }
-    __syncthreads();
-    run_fft<LOGN1, LOGT, NT, false>(d, tw, tid);
-    float2* out = mid + c * (size_t)M;
+        for (int q = 0; q < PER; ++q) {
+            const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
+            r[q] = load_pair(in, cbase + 2 * ((size_t)n1 * N2 + col0 + col), n, aligned);
+        }
+    };
+    load_tile(t, tid0);
+    for (;;) {
+        const int tid = opaque_lane(tid0);
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, k1 = w & (N1 - 1), col = w >> LOGN1;
-        const uint32_t n2 = col0 + col;
-        const float2 v = d[sw_idx<LOGT>(k1, col)];
-        out[(size_t)n2 * N1 + k1] = cmul(v, twiddle(tb, (n2 * (uint32_t)k1) << (22 - logM)));
+        for (int q = 0; q < PER; ++q) {
+            const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
+            d[sw_idx<LOGT>(n1, col)] = r[q];
+        }
+        __syncthreads();
+        const bool more = t + 1 < tend;
+        if (more) load_tile(t + 1, tid);
+        run_fft<LOGN1, LOGT, NT, false>(d, tw, tid);
+        float2* out = mid + (size_t)(t / tiles) * (size_t)M;
+        const uint32_t col0 = (t % tiles) << LOGT;
+        const int sh = 22 - logM;
+#pragma unroll
+        for (int kk = 0; kk < KN; ++kk) {
+            const uint32_t pos = (uint32_t)(tid + kk * NT) & (N1 - 1);  // paired position this lane stores to
+            const uint32_t k1 = row_of_pos(pos, N1);
+            const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGN1;
+            const float2 ratio = twiddle(tb, ((uint32_t)DC * k1) << sh);
+            float2 cur = make_float2(1.f, 0.f);
+#pragma unroll
+            for (int j = 0; j < NCOL; ++j) {
+                const uint32_t col = cfirst + j * DC, n2 = col0 + col;
+                if (j % 8 == 0) cur = twiddle(tb, (n2 * k1) << sh);
+                out[(size_t)n2 * N1 + pos] = cmul(d[sw_idx<LOGT>(k1, col)], cur);
+                cur = cmul(cur, ratio);
+            }
+        }
+        if (!more) break;
+        ++t;
+        __syncthreads();
     }
 }
 
-// Row held by LDS slot s of the pass-B tile starting at row r0: slots [0,TB) are rows r0.., slots [TB,2TB)
-// are their mirrors N1-row; row 0's mirror slot holds row N1/2 (both are their own partners).
-template <int TB>
-__device__ __forceinline__ uint32_t row_of_slot(int s, uint32_t r0, uint32_t N1)
+__device__ __forceinline__ uint32_t fft_key_of(float2 z)
 {
-    if (s < TB) return r0 + s;
-    const uint32_t row = N1 - r0 - (uint32_t)(s - TB);
-    return row == N1 ? N1 / 2 : row;
+    return __float_as_uint(__fmaf_rn(z.x, z.x, __fmul_rn(z.y, z.y)));
 }
 
-// Forward pass B: N2-point FFTs along n2 for a tile of rows and their mirrors, then the real-FFT split.
-template <int LOGN2, int LOGE, int NT>
-__global__ __launch_bounds__(NT) void k_fwd_b(const float2* __restrict__ mid, int logM, float2* __restrict__ spec,
-                                              Tables tb)
+// Forward pass B: N2-point FFTs along n2 for a tile of rows and their mirrors, then the real-FFT split and,
+// if hist != nullptr, the first radix-select digit of every bin's key (12-bit histogram per chunk).
+template <int LOGN2>
+__global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, int logM, float2* __restrict__ spec,
+                                               Tables tb, uint32_t* __restrict__ hist, uint32_t total,
+                                               uint32_t per_wg)
 {
+    constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, TB = T2 / 2, ELEMS = 1 << LOGE;
+    static_assert(NT % T2 == 0, "a lane keeps one slot");
     extern __shared__ float2 smem[];
     float2* d = smem;
     float2* tw = smem + ELEMS;
-    const int tid = threadIdx.x;
+    uint32_t* h16 = reinterpret_cast<uint32_t*>(tw + N2);
+    const int tid0 = threadIdx.x;
     const int logN1 = logM - LOGN2;
     const uint32_t M = 1u << logM, N1 = 1u << logN1, tiles = N1 >> LOGT;
-    const size_t c = blockIdx.x / tiles;
-    const uint32_t r0 = (blockIdx.x % tiles) * TB;
-    load_stage_twiddles<LOGN2, NT>(tw, tb, tid);
-    const float2* src = mid + c * (size_t)M;
+    uint32_t t = blockIdx.x * per_wg;
+    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
+    if (t >= tend) return;
+    load_stage_twiddles<LOGN2, NT>(tw, tb, tid0);
+    if (hist)
+        for (int i = tid0; i < kHistLdsWords; i += NT) h16[i] = 0u;
+    constexpr int DK = NT >> LOGT;  // k2 step between a lane's consecutive elements
+
+    float2 r[PER];
+    auto load_tile = [&](uint32_t tile, int tid) {
+        const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
+        const float2* src = mid + (size_t)(tile / tiles) * (size_t)M;
+        const uint32_t pos = (tile % tiles) * T2 + slot;
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, slot = w & (T2 - 1), n2 = w >> LOGT;
-        d[sw_idx<LOGT>(n2, slot)] = src[(size_t)n2 * N1 + row_of_slot<TB>(slot, r0, N1)];
-    }
-    __syncthreads();
-    run_fft<LOGN2, LOGT, NT, false>(d, tw, tid);
-    float2* out = spec + c * (size_t)(M + 1);
+        for (int q = 0; q < PER; ++q) r[q] = src[(size_t)(kq0 + q * DK) * N1 + pos];
+    };
+    load_tile(t, tid0);
+    for (;;) {
+        const int tid = opaque_lane(tid0);
+        const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, slot = w & (T2 - 1), k2 = w >> LOGT;
-        const uint32_t k1 = row_of_slot<TB>(slot, r0, N1);
-        const uint32_t k = k1 + ((uint32_t)k2 << logN1);
-        const float2 a = d[sw_idx<LOGT>(k2, slot)];
-        if (k == 0) {
-            out[0] = make_float2(a.x + a.y, 0.f);
-            out[M] = make_float2(a.x - a.y, 0.f);
-            continue;
-        }
+        for (int q = 0; q < PER; ++q) d[sw_idx<LOGT>(kq0 + q * DK, slot)] = r[q];
+        __syncthreads();
+        const bool more = t + 1 < tend;
+        if (more) load_tile(t + 1, tid);
+        run_fft<LOGN2, LOGT, NT, false>(d, tw, tid);
+        const size_t c = t / tiles;
+        float2* out = spec + c * (size_t)(M + 1);
+        const uint32_t k1 = row_of_pos((t % tiles) * T2 + slot, N1);
         const bool self = (k1 == 0) || (k1 == N1 / 2);
-        const int ps = self ? slot : (slot ^ TB);
-        const int k2p = (k1 == 0) ? ((N2 - k2) & (N2 - 1)) : (N2 - 1 - k2);
-        const float2 b = d[sw_idx<LOGT>(k2p, ps)];
-        out[k] = split_fwd(a, b, twiddle(tb, k << (21 - logM)));
+        const int ps = self ? slot : (slot ^ 1);
+        // W_L^(k1 + N1*k2): k2 advances by DK per step, i.e. by exactly kSplitStep 32nds of a turn
+        const float2 base = twiddle(tb, (k1 + ((uint32_t)kq0 << logN1)) << (21 - logM));
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int k2 = kq0 + q * DK;
+            const uint32_t k = k1 + ((uint32_t)k2 << logN1);
+            const float2 a = d[sw_idx<LOGT>(k2, slot)];
+            float2 x;
+            if (k == 0) {
+                x = make_float2(a.x + a.y, 0.f);
+                const float2 xm = make_float2(a.x - a.y, 0.f);
+                out[M] = xm;
+                if (hist) {
+                    const uint32_t b = fft_key_of(xm) >> kKeyShift;
+                    atomicAdd(&h16[b >> 1], 1u << ((b & 1u) * 16u));
+                }
+            } else {
+                const int k2p = (k1 == 0) ? ((N2 - k2) & (N2 - 1)) : (N2 - 1 - k2);
+                const float2 b = d[sw_idx<LOGT>(k2p, ps)];
+                x = split_fwd(a, b, cmul(base, make_float2(kW32re[q * kSplitStep], kW32im[q * kSplitStep])));
+            }
+            out[k] = x;
+            if (hist) {
+                const uint32_t b = fft_key_of(x) >> kKeyShift;
+                atomicAdd(&h16[b >> 1], 1u << ((b & 1u) * 16u));
+            }
+        }
+        if (hist) {  // at most 8193 bins per tile, so the 16-bit halves cannot carry into each other
+            __syncthreads();
+            uint32_t* g = hist + c * kHistBins;
+            for (int i = tid; i < kHistLdsWords; i += NT) {
+                const uint32_t v = h16[i];
+                if (v) {
+                    if (v & 0xFFFFu) atomicAdd(&g[2 * i], v & 0xFFFFu);
+                    if (v >> 16) atomicAdd(&g[2 * i + 1], v >> 16);
+                    h16[i] = 0u;
+                }
+            }
+        }
+        if (!more) break;
+        ++t;
+        __syncthreads();
     }
 }
 
 // Inverse pass B: undo the split, inverse N2-point FFTs over k2, times conj W_M^(n2 k1).
-template <int LOGN2, int LOGE, int NT>
-__global__ __launch_bounds__(NT) void k_inv_b(const float2* __restrict__ spec, int logM, float2* __restrict__ mid,
-                                              Tables tb)
+template <int LOGN2>
+__global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, int logM, float2* __restrict__ mid,
+                                               Tables tb, uint32_t total, uint32_t per_wg)
 {
+    constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, TB = T2 / 2, ELEMS = 1 << LOGE;
+    static_assert(NT % T2 == 0, "a lane keeps one slot");
     extern __shared__ float2 smem[];
     float2* d = smem;
     float2* tw = smem + ELEMS;
-    const int tid = threadIdx.x;
+    const int tid0 = threadIdx.x;
     const int logN1 = logM - LOGN2;
     const uint32_t M = 1u << logM, N1 = 1u << logN1, tiles = N1 >> LOGT;
-    const size_t c = blockIdx.x / tiles;
-    const uint32_t r0 = (blockIdx.x % tiles) * TB;
-    load_stage_twiddles<LOGN2, NT>(tw, tb, tid);
-    const float2* X = spec + c * (size_t)(M + 1);
+    uint32_t t = blockIdx.x * per_wg;
+    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
+    if (t >= tend) return;
+    load_stage_twiddles<LOGN2, NT>(tw, tb, tid0);
+    constexpr int DK = NT >> LOGT;
+
+    float2 r[PER];
+    float2 xnyq = make_float2(0.f, 0.f);
+    auto load_tile = [&](uint32_t tile, int tid) {
+        const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
+        const float2* X = spec + (size_t)(tile / tiles) * (size_t)(M + 1);
+        const uint32_t row = row_of_pos((tile % tiles) * T2 + slot, N1);
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, slot = w & (T2 - 1), k2 = w >> LOGT;
-        const uint32_t k = row_of_slot<TB>(slot, r0, N1) + ((uint32_t)k2 << logN1);
-        d[sw_idx<LOGT>(k2, slot)] = X[k];
-    }
-    __syncthreads();
-    float2 z[ELEMS / NT];
+        for (int q = 0; q < PER; ++q) r[q] = X[row + ((uint32_t)(kq0 + q * DK) << logN1)];
+        if (row == 0 && kq0 == 0) xnyq = X[M];
+    };
+    load_tile(t, tid0);
+    for (;;) {
+        const int tid = opaque_lane(tid0);
+        const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, slot = w & (T2 - 1), k2 = w >> LOGT;
-        const uint32_t k1 = row_of_slot<TB>(slot, r0, N1);
-        const uint32_t k = k1 + ((uint32_t)k2 << logN1);
-        float2 a = d[sw_idx<LOGT>(k2, slot)], b;
-        if (k == 0) {
-            b = X[M];
-            a.y = 0.f;
-            b.y = 0.f;
-        } else {
-            const bool self = (k1 == 0) || (k1 == N1 / 2);
-            const int ps = self ? slot : (slot ^ TB);
-            const int k2p = (k1 == 0) ? ((N2 - k2) & (N2 - 1)) : (N2 - 1 - k2);
-            b = d[sw_idx<LOGT>(k2p, ps)];
+        for (int q = 0; q < PER; ++q) d[sw_idx<LOGT>(kq0 + q * DK, slot)] = r[q];
+        const float2 xm = xnyq;
+        __syncthreads();
+        const uint32_t pos = (t % tiles) * T2 + slot;
+        const uint32_t k1 = row_of_pos(pos, N1);
+        const bool self = (k1 == 0) || (k1 == N1 / 2);
+        const int ps = self ? slot : (slot ^ 1);
+        const float2 base = twiddle(tb, (k1 + ((uint32_t)kq0 << logN1)) << (21 - logM));
+        float2 z[PER];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int k2 = kq0 + q * DK;
+            const uint32_t k = k1 + ((uint32_t)k2 << logN1);
+            float2 a = r[q], b;
+            if (k == 0) {  // imaginary parts of the DC and Nyquist bins are ignored
+                b = xm;
+                a.y = 0.f;
+                b.y = 0.f;
+            } else {
+                const int k2p = (k1 == 0) ? ((N2 - k2) & (N2 - 1)) : (N2 - 1 - k2);
+                b = d[sw_idx<LOGT>(k2p, ps)];
+            }
+            z[q] = split_inv(a, b, cmul(base, make_float2(kW32re[q * kSplitStep], kW32im[q * kSplitStep])));
         }
-        z[q] = split_inv(a, b, twiddle(tb, k << (21 - logM)));
-    }
-    __syncthreads();
+        __syncthreads();
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, slot = w & (T2 - 1), k2 = w >> LOGT;
-        d[sw_idx<LOGT>(k2, slot)] = z[q];
-    }
-    __syncthreads();
-    run_fft<LOGN2, LOGT, NT, true>(d, tw, tid);
-    float2* dst = mid + c * (size_t)M;
+        for (int q = 0; q < PER; ++q) d[sw_idx<LOGT>(kq0 + q * DK, slot)] = z[q];
+        __syncthreads();
+        const bool more = t + 1 < tend;
+        if (more) load_tile(t + 1, tid);
+        run_fft<LOGN2, LOGT, NT, true>(d, tw, tid);
+        float2* dst = mid + (size_t)(t / tiles) * (size_t)M;
+        const int sh = 22 - logM;
+        const float2 ratio = twiddle(tb, ((uint32_t)DK * k1) << sh);
+        float2 cur = make_float2(1.f, 0.f);
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, slot = w & (T2 - 1), n2 = w >> LOGT;
-        const uint32_t k1 = row_of_slot<TB>(slot, r0, N1);
-        const float2 v = d[sw_idx<LOGT>(n2, slot)];
-        dst[(size_t)n2 * N1 + k1] = cmulc(v, twiddle(tb, ((uint32_t)n2 * k1) << (22 - logM)));
+        for (int q = 0; q < PER; ++q) {
+            const uint32_t n2 = (uint32_t)(kq0 + q * DK);
+            if (q % 8 == 0) cur = twiddle(tb, (n2 * k1) << sh);
+            dst[(size_t)n2 * N1 + pos] = cmulc(d[sw_idx<LOGT>((int)n2, slot)], cur);
+            cur = cmul(cur, ratio);
+        }
+        if (!more) break;
+        ++t;
+        __syncthreads();
     }
 }
 
 // Inverse pass A: inverse N1-point FFTs over k1 for a tile of columns n2; writes the real samples.
-template <int LOGN1, int LOGE, int NT>
-__global__ __launch_bounds__(NT) void k_inv_a(const float2* __restrict__ mid, int logM, float* __restrict__ out,
-                                              size_t n, Tables tb, int aligned)
+template <int LOGN1>
+__global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, int logM, float* __restrict__ out,
+                                               size_t n, Tables tb, int aligned, uint32_t total, uint32_t per_wg)
 {
+    constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
     extern __shared__ float2 smem[];
     float2* d = smem;
     float2* tw = smem + ELEMS;
-    const int tid = threadIdx.x;
+    const int tid0 = threadIdx.x;
     const uint32_t M = 1u << logM, N2 = M >> LOGN1, tiles = N2 >> LOGT;
-    const size_t c = blockIdx.x / tiles;
-    const uint32_t col0 = (blockIdx.x % tiles) << LOGT;
-    load_stage_twiddles<LOGN1, NT>(tw, tb, tid);
-    const float2* src = mid + c * (size_t)M;
+    uint32_t t = blockIdx.x * per_wg;
+    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
+    if (t >= tend) return;
+    load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
+
+    float2 r[PER];
+    auto load_tile = [&](uint32_t tile, int tid) {
+        const float2* src = mid + (size_t)(tile / tiles) * (size_t)M;
+        const uint32_t col0 = (tile % tiles) << LOGT;
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, k1 = w & (N1 - 1), col = w >> LOGN1;
-        d[sw_idx<LOGT>(k1, col)] = src[(size_t)(col0 + col) * N1 + k1];
-    }
-    __syncthreads();
-    run_fft<LOGN1, LOGT, NT, true>(d, tw, tid);
+        for (int q = 0; q < PER; ++q) {
+            const int w = tid + q * NT, pos = w & (N1 - 1), col = w >> LOGN1;
+            r[q] = src[(size_t)(col0 + col) * N1 + pos];
+        }
+    };
+    load_tile(t, tid0);
     const float scale = 1.0f / (float)(2u * M);
-    const size_t cbase = c * (size_t)(2 * (size_t)M);
+    for (;;) {
+        const int tid = opaque_lane(tid0);
 #pragma unroll
-    for (int q = 0; q < ELEMS / NT; ++q) {
-        const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-        const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + col);
-        const float2 v = d[sw_idx<LOGT>(n1, col)];
-        store_pair(out, gi, n, aligned, make_float2(v.x * scale, v.y * scale));
+        for (int q = 0; q < PER; ++q) {
+            const int w = tid + q * NT, col = w >> LOGN1;
+            d[sw_idx<LOGT>((int)row_of_pos((uint32_t)w & (N1 - 1), N1), col)] = r[q];
+        }
+        __syncthreads();
+        const bool more = t + 1 < tend;
+        if (more) load_tile(t + 1, tid);
+        run_fft<LOGN1, LOGT, NT, true>(d, tw, tid);
+        const size_t cbase = (size_t)(t / tiles) * (size_t)(2 * (size_t)M);
+        const uint32_t col0 = (t % tiles) << LOGT;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
+            const float2 v = d[sw_idx<LOGT>(n1, col)];
+            store_pair(out, cbase + 2 * ((size_t)n1 * N2 + col0 + col), n, aligned,
+                       make_float2(v.x * scale, v.y * scale));
+        }
+        if (!more) break;
+        ++t;
+        __syncthreads();
     }
 }
 
 // ---------------------------------------------------------------- launch ----
-constexpr int kNT = 256;
+constexpr int kSmallNT = 256;
 
 template <typename K>
 hipError_t set_lds(K kernel, size_t bytes)
@@ -484,11 +653,12 @@ hipError_t small_fwd(const float* in, size_t n, size_t C, float2* spec, Tables t
 {
     constexpr int LOGE = LOGM >= 12 ? LOGM : 12;
     const size_t lds = ((size_t)(1 << LOGE) + (1 << LOGM)) * sizeof(float2);
-    auto kern = k_fwd_small<LOGM, LOGE, kNT>;
+    auto kern = k_fwd_small<LOGM, LOGE, kSmallNT>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
-    FFTSP_LAUNCH("rfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kNT), lds, s, in, n, C, spec, t, aligned);
+    FFTSP_LAUNCH("rfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, in, n, C, spec, t,
+                 aligned);
     return hipGetLastError();
 }
 
@@ -497,37 +667,53 @@ hipError_t small_inv(const float2* spec, size_t n, size_t C, float* out, Tables 
 {
     constexpr int LOGE = LOGM >= 12 ? LOGM : 12;
     const size_t lds = ((size_t)(1 << LOGE) + (1 << LOGM)) * sizeof(float2);
-    auto kern = k_inv_small<LOGM, LOGE, kNT>;
+    auto kern = k_inv_small<LOGM, LOGE, kSmallNT>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
-    FFTSP_LAUNCH("irfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kNT), lds, s, spec, n, C, out, t, aligned);
+    FFTSP_LAUNCH("irfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, spec, n, C, out,
+                 t, aligned);
     return hipGetLastError();
 }
 
-constexpr int kLogE = 13;  // 8192 complex points (64 KiB) per workgroup in the two-pass kernels
+// persistent grid: at most two workgroups per compute unit, each walking a contiguous run of tiles
+struct Grid {
+    uint32_t wgs, per_wg;
+};
+Grid persistent_grid(size_t total)
+{
+    constexpr uint32_t kMaxWgs = 512;  // 256 compute units x 2 resident workgroups
+    Grid g;
+    g.per_wg = (uint32_t)((total + kMaxWgs - 1) / kMaxWgs);
+    g.wgs = (uint32_t)((total + g.per_wg - 1) / g.per_wg);
+    return g;
+}
 
 template <int LOGN1>
 hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tables t, int aligned, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN1)) * sizeof(float2);
-    auto kern = k_fwd_a<LOGN1, kLogE, kNT>;
+    auto kern = k_fwd_a<LOGN1>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
-    const size_t tiles = ((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1);
-    FFTSP_LAUNCH("rfft_pass_a", kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, in, n, logM, mid, t, aligned);
+    const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
+    const Grid g = persistent_grid(total);
+    FFTSP_LAUNCH("rfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, in, n, logM, mid, t, aligned, (uint32_t)total,
+                 g.per_wg);
     return hipGetLastError();
 }
 
 template <int LOGN2>
-hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, Tables t, hipStream_t s)
+hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, Tables t, uint32_t* hist, hipStream_t s)
 {
-    const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2);
-    auto kern = k_fwd_b<LOGN2, kLogE, kNT>;
+    const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2) + kHistLdsWords * sizeof(uint32_t);
+    auto kern = k_fwd_b<LOGN2>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
-    const size_t tiles = ((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2);
-    FFTSP_LAUNCH("rfft_pass_b", kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, mid, logM, spec, t);
+    const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
+    const Grid g = persistent_grid(total);
+    FFTSP_LAUNCH("rfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, spec, t, hist, (uint32_t)total,
+                 g.per_wg);
     return hipGetLastError();
 }
 
@@ -535,11 +721,12 @@ template <int LOGN2>
 hipError_t inv_b(const float2* spec, int logM, size_t C, float2* mid, Tables t, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2);
-    auto kern = k_inv_b<LOGN2, kLogE, kNT>;
+    auto kern = k_inv_b<LOGN2>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
-    const size_t tiles = ((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2);
-    FFTSP_LAUNCH("irfft_pass_b", kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, spec, logM, mid, t);
+    const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
+    const Grid g = persistent_grid(total);
+    FFTSP_LAUNCH("irfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, spec, logM, mid, t, (uint32_t)total, g.per_wg);
     return hipGetLastError();
 }
 
@@ -547,11 +734,13 @@ template <int LOGN1>
 hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Tables t, int aligned, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN1)) * sizeof(float2);
-    auto kern = k_inv_a<LOGN1, kLogE, kNT>;
+    auto kern = k_inv_a<LOGN1>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
-    const size_t tiles = ((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1);
-    FFTSP_LAUNCH("irfft_pass_a", kern, dim3((unsigned)(C * tiles)), dim3(kNT), lds, s, mid, logM, out, n, t, aligned);
+    const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
+    const Grid g = persistent_grid(total);
+    FFTSP_LAUNCH("irfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, out, n, t, aligned, (uint32_t)total,
+                 g.per_wg);
     return hipGetLastError();
 }
 
@@ -559,12 +748,15 @@ hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Ta
 
 #define FFTSP_SMALL_CASES(X) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
 
+// hist (optional, u32[C][kHistBins], zeroed by the caller): receives the 12-bit histogram of the keys' top
+// bits.  Returns *hist_done = 1 if the FFT filled it (two-pass sizes), 0 if the caller still has to.
 hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, float2* mid, Tables t,
-                       hipStream_t s)
+                       uint32_t* hist, int* hist_done, hipStream_t s)
 {
     const int logM = logL - 1;
     const int aligned = (reinterpret_cast<uintptr_t>(in) & 7u) == 0;
     float2* sp = reinterpret_cast<float2*>(spec);
+    if (hist_done) *hist_done = 0;
     if (C * ((size_t)1 << (logM > 13 ? logM - 13 : 0)) > 0x7fffffffu) return hipErrorInvalidValue;
     switch (logM) {
 #define X(p) \
@@ -584,11 +776,12 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
+    if (hist_done) *hist_done = hist != nullptr;
     switch (logN2) {
-        case 7: return fwd_b<7>(mid, logM, C, sp, t, s);
-        case 8: return fwd_b<8>(mid, logM, C, sp, t, s);
-        case 9: return fwd_b<9>(mid, logM, C, sp, t, s);
-        case 10: return fwd_b<10>(mid, logM, C, sp, t, s);
+        case 7: return fwd_b<7>(mid, logM, C, sp, t, hist, s);
+        case 8: return fwd_b<8>(mid, logM, C, sp, t, hist, s);
+        case 9: return fwd_b<9>(mid, logM, C, sp, t, hist, s);
+        case 10: return fwd_b<10>(mid, logM, C, sp, t, hist, s);
         default: return hipErrorInvalidValue;
     }
 }

@@ -85,8 +85,9 @@ hipError_t get_tables(Tables* out);
 
 // FFT launchers (fft.hip).  Chunk c covers in[c*L, min(n, (c+1)*L)), zero beyond n.
 // spec: C*(L+2) floats; mid: C*L floats of scratch (unused when L <= 2^14).
+// hist (optional): u32[C][kHistBins], zeroed by the caller; if the FFT filled it, *hist_done is set to 1.
 hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, float2* mid, Tables t,
-                       hipStream_t s);
+                       uint32_t* hist, int* hist_done, hipStream_t s);
 hipError_t launch_irfft(const float* spec, size_t n, int logL, size_t C, float* out, float2* mid, Tables t,
                         hipStream_t s);
 
@@ -104,8 +105,10 @@ struct CodecArgs {
     uint32_t hdr_L, hdr_C, hdr_k, hdr_S;
     float hdr_theta;
 };
+// hist_ready != 0: the status words are cleared and the per-chunk histograms already hold the keys' top digit
 hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
-                         uint8_t* ws_base, const Workspace& w, hipStream_t s);
+                         uint8_t* ws_base, const Workspace& w, int hist_ready, hipStream_t s);
+hipError_t launch_zero_hist(uint8_t* ws_base, const Workspace& w, size_t C, hipStream_t s);
 hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
                          uint8_t* ws_base, const Workspace& w, int check_header, hipStream_t s);
 hipError_t launch_zero_status(uint8_t* ws_base, const Workspace& w, hipStream_t s);
