@@ -207,7 +207,7 @@ int fftsp_rfft(const float* d_grad, size_t n, uint32_t chunk_len, float* d_spec,
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     return hip_status(launch_rfft(d_grad, n, p.logL, p.C, d_spec, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                                  nullptr, nullptr, reinterpret_cast<hipStream_t>(stream)));
+                                  nullptr, nullptr, 0, nullptr, reinterpret_cast<hipStream_t>(stream)));
 }
 
 int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad_out, void* d_workspace,
@@ -256,8 +256,7 @@ int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, u
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     const uint8_t* in = static_cast<const uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    hipError_t e = launch_zero_status(ws, p.ws, s);
-    if (e == hipSuccess) e = launch_decode(in, in + kStreamHeader, codec_args(p, theta), d_spec, ws, p.ws, 1, s);
+    hipError_t e = launch_decode(in, in + kStreamHeader, codec_args(p, theta), d_spec, ws, p.ws, 1, 1, s);
     return hip_status(e);
 }
 
@@ -278,10 +277,10 @@ int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float thet
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
     int hist_done = 0;
-    hipError_t e = launch_zero_hist(ws, p.ws, p.C, s);
-    if (e == hipSuccess)
-        e = launch_rfft(d_grad, n, p.logL, p.C, spec, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                        reinterpret_cast<uint32_t*>(ws + p.ws.hist), &hist_done, s);
+    hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+                               reinterpret_cast<uint32_t*>(ws + p.ws.hist),
+                               reinterpret_cast<uint32_t*>(ws + p.ws.status),
+                               (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, &hist_done, s);
     if (e == hipSuccess)
         e = launch_encode(spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws, hist_done, s);
     return hip_status(e);
@@ -304,8 +303,7 @@ int fftsp_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_ou
     const uint8_t* in = static_cast<const uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
-    hipError_t e = launch_zero_status(ws, p.ws, s);
-    if (e == hipSuccess) e = launch_decode(in, in + kStreamHeader, codec_args(p, theta), spec, ws, p.ws, 1, s);
+    hipError_t e = launch_decode(in, in + kStreamHeader, codec_args(p, theta), spec, ws, p.ws, 1, 1, s);
     if (e == hipSuccess)
         e = launch_irfft(spec, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t, s);
     return hip_status(e);
@@ -385,11 +383,10 @@ int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int 
         a.hdr_theta = theta;
         float* spec = reinterpret_cast<float*>(ws + w.spec);
         int hist_done = 0;
-        hipError_t e = launch_zero_hist(ws, w, 1, s);
-        if (e == hipSuccess)
-            e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec,
-                            reinterpret_cast<float2*>(ws + w.mid), t, reinterpret_cast<uint32_t*>(ws + w.hist),
-                            &hist_done, s);
+        hipError_t e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec,
+                                   reinterpret_cast<float2*>(ws + w.mid), t, reinterpret_cast<uint32_t*>(ws + w.hist),
+                                   reinterpret_cast<uint32_t*>(ws + w.status),
+                                   (w.hist - w.status) / 4 + (size_t)kHistBins, &hist_done, s);
         if (e == hipSuccess) e = launch_encode(spec, a, out, out + rec_off, ws, w, hist_done, s);
         if (e != hipSuccess) return FFTSP_EHIP;
         rec_off += a.S;
@@ -415,8 +412,7 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     const uint8_t* in = static_cast<const uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    // every segment uses the same status word; it is cleared once, before the first segment
-    if (launch_zero_status(ws, make_workspace(1, 32), s) != hipSuccess) return FFTSP_EHIP;
+    // every segment uses the same status word; it is cleared once, by the first segment's kernels
     size_t rec_off = kStreamHeader;
     for (int i = 0; i < nseg; ++i) {
         const size_t size = seg_offsets[i + 1] - seg_offsets[i];
@@ -437,7 +433,7 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
         a.hdr_S = 0;
         a.hdr_theta = theta;
         float* spec = reinterpret_cast<float*>(ws + w.spec);
-        hipError_t e = launch_decode(in, in + rec_off, a, spec, ws, w, i == 0, s);
+        hipError_t e = launch_decode(in, in + rec_off, a, spec, ws, w, i == 0, i == 0, s);
         if (e == hipSuccess)
             e = launch_irfft(spec, size, log2_exact(L), 1, d_grad_out + seg_offsets[i],
                              reinterpret_cast<float2*>(ws + w.mid), t, s);

@@ -256,7 +256,7 @@ struct HeaderInfo {
 // scan the tiles, find the survivors' largest component, write the record header and zero the
 // code words that two tiles will share.
 __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bits, int m, uint32_t W, size_t S,
-                                                uint32_t word3, uint32_t* __restrict__ sel,
+                                                uint32_t word3, uint32_t stage_cap, uint32_t* __restrict__ sel,
                                                 const uint32_t* __restrict__ tinfo, uint32_t* __restrict__ tscan,
                                                 const uint2* __restrict__ cand, uint8_t* __restrict__ records,
                                                 uint8_t* __restrict__ stream, HeaderInfo hdr)
@@ -264,6 +264,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     __shared__ uint32_t h[1024];
     __shared__ uint32_t tmp[RW];
     __shared__ uint32_t tgt[MAX_TILES], teq[MAX_TILES], ttake[MAX_TILES], trank[MAX_TILES], tsurv[MAX_TILES];
+    __shared__ uint32_t toff[MAX_TILES], tnc[MAX_TILES], tdef[MAX_TILES], tvd[MAX_TILES];
     __shared__ uint32_t s_digit, s_need, s_vmax, s_carry[2];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t c = blockIdx.x;
@@ -272,6 +273,40 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     const uint32_t* ti = tinfo + c * Tn * 4;
     const uint2* cd = cand + c * Tn * (size_t)kTile;
     uint32_t tau = 0xFFFFFFFFu, quota = 0;
+
+    // Stage the candidates in LDS when they fit (they are read four times below): tile t's candidates go to
+    // stage[toff[t] ..).  Otherwise every pass reads them from global memory.
+    extern __shared__ float2 smem[];
+    uint2* stage = reinterpret_cast<uint2*>(smem);
+    if (tid == 0) s_carry[0] = 0;
+    __syncthreads();
+    for (uint32_t base = 0; base < Tn; base += RT) {
+        const uint32_t t = base + tid;
+        uint32_t nc = 0;
+        if (t < Tn) {  // the per-tile summaries are read once; every later pass takes them from LDS
+            const uint4 info = reinterpret_cast<const uint4*>(ti)[t];
+            tdef[t] = info.x;
+            tvd[t] = info.y;
+            tnc[t] = nc = info.z;
+        }
+        const uint32_t carry = s_carry[0];
+        const uint32_t incl = block_scan_incl_1024(nc, tmp);
+        if (t < Tn) toff[t] = carry + incl - nc;
+        __syncthreads();
+        if (tid == RT - 1) s_carry[0] = carry + incl;
+        __syncthreads();
+    }
+    const bool staged = s_carry[0] <= stage_cap;
+    if (staged) {
+        for (uint32_t t = wave; t < Tn; t += RW) {
+            const uint32_t nc = tnc[t], o = toff[t];
+            for (uint32_t i = lane; i < nc; i += 64) stage[o + i] = cd[(size_t)t * kTile + i];
+        }
+    }
+    __syncthreads();
+    auto cand_at = [&](uint32_t t, uint32_t i) -> uint2 {
+        return staged ? stage[toff[t] + i] : cd[(size_t)t * kTile + i];
+    };
 
     if (need > 0) {
         uint32_t prefix = bstar << kKeyShift;
@@ -282,11 +317,19 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             const uint32_t pmask = pass == 0 ? (0xFFFFFFFFu << kKeyShift) : (0xFFFFFFFFu << 9);
             h[tid] = 0u;
             __syncthreads();
-            for (uint32_t t = wave; t < Tn; t += RW) {
-                const uint32_t nc = ti[t * 4 + 2];
-                for (uint32_t i = lane; i < nc; i += 64) {
-                    const uint32_t key = cd[(size_t)t * kTile + i].x;
+            if (staged) {
+                const uint32_t total = s_carry[0];
+                for (uint32_t i = tid; i < total; i += RT) {
+                    const uint32_t key = stage[i].x;
                     if ((key & pmask) == prefix) atomicAdd(&h[(key >> shift) & dmask], 1u);
+                }
+            } else {
+                for (uint32_t t = wave; t < Tn; t += RW) {
+                    const uint32_t nc = tnc[t];
+                    for (uint32_t i = lane; i < nc; i += 64) {
+                        const uint32_t key = cd[(size_t)t * kTile + i].x;
+                        if ((key & pmask) == prefix) atomicAdd(&h[(key >> shift) & dmask], 1u);
+                    }
                 }
             }
             __syncthreads();
@@ -309,10 +352,10 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
 
     // per tile: candidates above tau and equal to tau
     for (uint32_t t = wave; t < Tn; t += RW) {
-        const uint32_t nc = ti[t * 4 + 2];
+        const uint32_t nc = tnc[t];
         uint32_t gt = 0, eq = 0;
         for (uint32_t i = lane; i < nc; i += 64) {
-            const uint32_t key = cd[(size_t)t * kTile + i].x;
+            const uint32_t key = cand_at(t, i).x;
             gt += key > tau;
             eq += key == tau;
         }
@@ -339,7 +382,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
         const uint32_t eqincl = block_scan_incl_1024(eq, tmp);
         const uint32_t eqpre = ceq + eqincl - eq;
         const uint32_t take = eqpre >= quota ? 0u : (eq < quota - eqpre ? eq : quota - eqpre);
-        const uint32_t surv = in ? (ti[t * 4 + 0] + tgt[t] + take) : 0u;
+        const uint32_t surv = in ? (tdef[t] + tgt[t] + take) : 0u;
         const uint32_t rkincl = block_scan_incl_1024(surv, tmp);
         const uint32_t rank = crk + rkincl - surv;
         if (in) {
@@ -359,13 +402,13 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
 
     // largest component over the survivors
     for (uint32_t t = wave; t < Tn; t += RW) {
-        const uint32_t nc = ti[t * 4 + 2], take = ttake[t];
-        uint32_t vm = lane == 0 ? (ti[t * 4 + 0] ? ti[t * 4 + 1] : 0u) : 0u;
+        const uint32_t nc = tnc[t], take = ttake[t];
+        uint32_t vm = lane == 0 ? (tdef[t] ? tvd[t] : 0u) : 0u;
         uint32_t eqrun = 0;
         for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
             const uint32_t i = i0 + lane;
             const bool valid = i < nc;
-            const uint2 e = valid ? cd[(size_t)t * kTile + i] : make_uint2(0u, 0u);
+            const uint2 e = valid ? cand_at(t, i) : make_uint2(0u, 0u);
             const bool iseq = valid && e.x == tau;
             const uint64_t em = __ballot(iseq);
             const bool kept = valid && (e.x > tau || (iseq && eqrun + (uint32_t)__popcll(em & lanemask_lt()) < take));
@@ -528,11 +571,15 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
 }
 
 // ---------------------------------------------------------------- decode ----
-// Per chunk: set bits before each bitmap word; checks the headers.
-__global__ __launch_bounds__(RT) void k_word_prefix(const uint8_t* __restrict__ stream,
-                                                    const uint8_t* __restrict__ records, size_t S, uint32_t W,
-                                                    uint32_t k, uint32_t word3, HeaderInfo hdr,
-                                                    uint32_t* __restrict__ prefix, uint32_t* __restrict__ status)
+constexpr int GROUP_WORDS = 16;  // one wave of the decode kernel covers 512 bins = 16 bitmap words
+
+// Per chunk: number of set bits before each group of 16 bitmap words (the prefix sum of Sec. 3.2's status
+// vector, kept at the granularity a wave needs); checks the headers and leaves the verdict in sel[c][7].
+__global__ __launch_bounds__(RT) void k_group_prefix(const uint8_t* __restrict__ stream,
+                                                     const uint8_t* __restrict__ records, size_t S, uint32_t W,
+                                                     uint32_t k, uint32_t word3, HeaderInfo hdr,
+                                                     uint32_t* __restrict__ gprefix, uint32_t* __restrict__ sel,
+                                                     uint32_t* __restrict__ status, int reset_status)
 {
     __shared__ uint32_t tmp[RW];
     __shared__ uint32_t s_carry;
@@ -540,14 +587,28 @@ __global__ __launch_bounds__(RT) void k_word_prefix(const uint8_t* __restrict__ 
     const size_t c = blockIdx.x;
     const uint32_t* rec = reinterpret_cast<const uint32_t*>(records + c * S);
     const uint32_t* bitmap = rec + 4;
+    const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
     if (tid == 0) s_carry = 0;
     __syncthreads();
-    for (uint32_t base = 0; base < W; base += RT) {
-        const uint32_t w = base + tid;
-        const uint32_t cnt = w < W ? (uint32_t)__popc(bitmap[w]) : 0u;
+    for (uint32_t base = 0; base < G; base += RT) {
+        const uint32_t g = base + tid;
+        uint32_t cnt = 0;
+        if (g < G) {
+            const uint32_t w0 = g * GROUP_WORDS;
+            if (w0 + GROUP_WORDS <= W) {
+                const uint4* p = reinterpret_cast<const uint4*>(bitmap + w0);  // records and bitmaps are 16-byte aligned
+#pragma unroll
+                for (int i = 0; i < GROUP_WORDS / 4; ++i) {
+                    const uint4 v = p[i];
+                    cnt += (uint32_t)(__popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w));
+                }
+            } else {
+                for (uint32_t w = w0; w < W; ++w) cnt += (uint32_t)__popc(bitmap[w]);
+            }
+        }
         const uint32_t carry = s_carry;
         const uint32_t incl = block_scan_incl_1024(cnt, tmp);
-        if (w < W) prefix[c * W + w] = carry + incl - cnt;
+        if (g < G) gprefix[c * G + g] = carry + incl - cnt;
         __syncthreads();
         if (tid == RT - 1) s_carry = carry + incl;
         __syncthreads();
@@ -560,7 +621,8 @@ __global__ __launch_bounds__(RT) void k_word_prefix(const uint8_t* __restrict__ 
                   h[3] != (uint32_t)(hdr.n >> 32) || h[4] != hdr.L || h[5] != hdr.C || h[6] != hdr.N ||
                   h[7] != hdr.m || h[8] != hdr.k || h[9] != hdr.S;
         }
-        if (bad) atomicMax(status, 6u);
+        sel[c * 8 + 7] = bad ? 6u : 0u;
+        if (reset_status && c == 0) status[0] = 0u;  // raised again by k_decode, which runs after this kernel
     }
 }
 
@@ -572,42 +634,64 @@ __device__ __forceinline__ uint32_t fetch_code(const uint32_t* __restrict__ code
     return bits == 32 ? v : (v & ((1u << bits) - 1u));
 }
 
-// One lane per bin: bit test, rank from the word prefix, code fetch, Nbit_to_32bit, scatter.
+// One workgroup per tile of 2048 bins, one wave per group of 16 bitmap words: ranks from ballots of the
+// bitmap itself, code fetch (consecutive ranks, so consecutive addresses), Nbit_to_32bit, zero elsewhere.
 __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
-                                               uint32_t k, int bits, int m, uint32_t groups,
-                                               const uint32_t* __restrict__ prefix, float2* __restrict__ spec)
+                                               uint32_t k, int bits, int m, uint32_t Tn,
+                                               const uint32_t* __restrict__ gprefix, const uint32_t* __restrict__ sel,
+                                               uint32_t* __restrict__ status, float2* __restrict__ spec)
 {
-    const size_t c = blockIdx.x / groups;
-    const uint32_t j = (blockIdx.x % groups) * NT + threadIdx.x;
-    if (j >= B) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t c = blockIdx.x / Tn;
+    const uint32_t tile = blockIdx.x % Tn;
     const uint32_t* rec = reinterpret_cast<const uint32_t*>(records + c * S);
     const uint32_t pbase = rec[0];
     const uint32_t* bitmap = rec + 4;
     const uint32_t* codes = bitmap + W;
-    const uint32_t word = bitmap[j >> 5], bit = j & 31u;
-    float2 out = make_float2(0.f, 0.f);
-    if (((word >> bit) & 1u) && k > 0) {
-        uint32_t rank = prefix[c * W + (j >> 5)] + (uint32_t)__popc(word & ((1u << bit) - 1u));
-        rank = rank < k ? rank : k - 1u;  // a corrupt bitmap must not read outside the record
-        const uint32_t p = 2u * (uint32_t)bits * rank;
-        const int shift = 23 - m;
-        out.x = __uint_as_float(dequantize(fetch_code(codes, p, bits), pbase, bits, shift));
-        out.y = __uint_as_float(dequantize(fetch_code(codes, p + (uint32_t)bits, bits), pbase, bits, shift));
+    if (tile == 0 && tid == 0) {
+        const uint32_t verdict = sel[c * 8 + 7];
+        if (verdict) atomicMax(status, verdict);
     }
-    spec[c * (size_t)B + j] = out;
+    const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
+    const uint32_t g = tile * (kTile / 32 / GROUP_WORDS) + wave;
+    uint32_t myword = 0;
+    if (lane < GROUP_WORDS && g * GROUP_WORDS + lane < W) myword = bitmap[g * GROUP_WORDS + lane];
+    uint32_t run = g < G ? gprefix[c * G + g] : 0u;
+    const uint64_t lt = lanemask_lt();
+    const int shift = 23 - m;
+    float2* X = spec + c * (size_t)B;
+    const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const uint32_t lo = __shfl(myword, 2 * r, 64), hi = __shfl(myword, 2 * r + 1, 64);
+        const uint64_t mask = (uint64_t)lo | ((uint64_t)hi << 32);
+        const uint32_t j = j0 + r * 64;
+        float2 out = make_float2(0.f, 0.f);
+        if (((mask >> lane) & 1ull) && k > 0) {
+            uint32_t rank = run + (uint32_t)__popcll(mask & lt);
+            rank = rank < k ? rank : k - 1u;  // a corrupt bitmap must not read outside the record
+            uint32_t cre, cim;
+            if (bits == 8) {
+                const uint32_t v = reinterpret_cast<const uint16_t*>(codes)[rank];
+                cre = v & 0xFFu;
+                cim = v >> 8;
+            } else {
+                const uint32_t p = 2u * (uint32_t)bits * rank;
+                cre = fetch_code(codes, p, bits);
+                cim = fetch_code(codes, p + (uint32_t)bits, bits);
+            }
+            out.x = __uint_as_float(dequantize(cre, pbase, bits, shift));
+            out.y = __uint_as_float(dequantize(cim, pbase, bits, shift));
+        }
+        if (j < B) X[j] = out;
+        run += (uint32_t)__popcll(mask);
+    }
 }
 
 }  // namespace
 
-hipError_t launch_zero_status(uint8_t* ws_base, const Workspace& w, hipStream_t s)
-{
-    FFTSP_LAUNCH("zero_fill", k_zero_u32, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws_base + w.status),
-                       (size_t)64);
-    return hipGetLastError();
-}
-
 // status words and histograms are adjacent: one fill
-hipError_t launch_zero_hist(uint8_t* ws_base, const Workspace& w, size_t C, hipStream_t s)
+static hipError_t launch_zero_hist(uint8_t* ws_base, const Workspace& w, size_t C, hipStream_t s)
 {
     uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
     const size_t zero_words = (w.hist - w.status) / 4 + C * kHistBins;
@@ -638,27 +722,36 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     FFTSP_LAUNCH("collect", k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, sel, tinfo, cand);
     HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
                  a.hdr_theta};
-    FFTSP_LAUNCH("resolve", k_resolve, dim3((unsigned)a.C), dim3(RT), 0, s, Tn, a.k, a.bits, a.m, W, a.S, a.word3, sel,
-                       tinfo, tscan, cand, records, stream_base, h);
+    // up to 12 Ki candidates (96 KiB) are staged in LDS by the per-chunk workgroup
+    constexpr uint32_t kStageCap = 12 * 1024;
+    static bool lds_set = false;
+    if (!lds_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_resolve),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kStageCap * sizeof(uint2)));
+        if (e != hipSuccess) return e;
+        lds_set = true;
+    }
+    FFTSP_LAUNCH("resolve", k_resolve, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k, a.bits, a.m,
+                 W, a.S, a.word3, kStageCap, sel, tinfo, tscan, cand, records, stream_base, h);
     FFTSP_LAUNCH("emit", k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
                        records);
     return hipGetLastError();
 }
 
 hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
-                         uint8_t* ws_base, const Workspace& w, int check_header, hipStream_t s)
+                         uint8_t* ws_base, const Workspace& w, int check_header, int reset_status, hipStream_t s)
 {
-    const uint32_t B = a.L / 2 + 1, W = (B + 31) / 32;
+    const uint32_t B = a.L / 2 + 1, W = (B + 31) / 32, Tn = tiles_per_chunk(a.L);
     uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
-    uint32_t* prefix = reinterpret_cast<uint32_t*>(ws_base + w.prefix);
-    const uint32_t groups = (B + NT - 1) / NT;
-    if (a.C * (size_t)groups > 0x7fffffffu) return hipErrorInvalidValue;
+    uint32_t* sel = reinterpret_cast<uint32_t*>(ws_base + w.sel);
+    uint32_t* gprefix = reinterpret_cast<uint32_t*>(ws_base + w.prefix);
+    if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
     HeaderInfo h{check_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
                  a.hdr_theta};
-    FFTSP_LAUNCH("word_prefix", k_word_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k, a.word3,
-                       h, prefix, status);
-    FFTSP_LAUNCH("decode", k_decode, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m,
-                       groups, prefix, reinterpret_cast<float2*>(spec));
+    FFTSP_LAUNCH("group_prefix", k_group_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k,
+                 a.word3, h, gprefix, sel, status, reset_status);
+    FFTSP_LAUNCH("decode", k_decode, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m,
+                 Tn, gprefix, sel, status, reinterpret_cast<float2*>(spec));
     return hipGetLastError();
 }
 

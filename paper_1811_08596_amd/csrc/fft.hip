@@ -338,10 +338,12 @@ __device__ __forceinline__ uint32_t row_of_pos(uint32_t p, uint32_t N1)
 template <int LOGN1>
 __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, size_t n, int logM,
                                                float2* __restrict__ mid, Tables tb, int aligned, uint32_t total,
-                                               uint32_t per_wg)
+                                               uint32_t per_wg, uint32_t* __restrict__ zero_ptr, uint32_t zero_words)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
+    // clears the status words and key histograms the next kernels of the sender accumulate into
+    for (uint32_t i = blockIdx.x * NT + threadIdx.x; i < zero_words; i += gridDim.x * NT) zero_ptr[i] = 0u;
     constexpr int KN = N1 >= NT ? N1 / NT : 1;   // distinct k1 per lane in the store loop
     constexpr int DC = N1 >= NT ? 1 : NT / N1;   // column step between a lane's consecutive stores
     constexpr int NCOL = PER / KN;
@@ -690,7 +692,8 @@ Grid persistent_grid(size_t total)
 }
 
 template <int LOGN1>
-hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tables t, int aligned, hipStream_t s)
+hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tables t, int aligned, uint32_t* zero_ptr,
+                 uint32_t zero_words, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN1)) * sizeof(float2);
     auto kern = k_fwd_a<LOGN1>;
@@ -699,7 +702,7 @@ hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tab
     const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
     const Grid g = persistent_grid(total);
     FFTSP_LAUNCH("rfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, in, n, logM, mid, t, aligned, (uint32_t)total,
-                 g.per_wg);
+                 g.per_wg, zero_ptr, zero_words);
     return hipGetLastError();
 }
 
@@ -748,11 +751,14 @@ hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Ta
 
 #define FFTSP_SMALL_CASES(X) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13)
 
-// hist (optional, u32[C][kHistBins], zeroed by the caller): receives the 12-bit histogram of the keys' top
-// bits.  Returns *hist_done = 1 if the FFT filled it (two-pass sizes), 0 if the caller still has to.
+// hist (optional, u32[C][kHistBins]): receives the 12-bit histogram of the keys' top bits when the two-pass
+// kernels run; they first clear zero_words words at zero_ptr (which must cover hist).  *hist_done = 1 if the
+// FFT filled hist, 0 if the caller still has to clear and fill it (single-workgroup sizes).
 hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, float2* mid, Tables t,
-                       uint32_t* hist, int* hist_done, hipStream_t s)
+                       uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, hipStream_t s)
 {
+    if (zero_words > 0xffffffffu) return hipErrorInvalidValue;
+    if (!hist) zero_words = 0;
     const int logM = logL - 1;
     const int aligned = (reinterpret_cast<uintptr_t>(in) & 7u) == 0;
     float2* sp = reinterpret_cast<float2*>(spec);
@@ -768,11 +774,11 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
     hipError_t e;
     switch (logN1) {
-        case 7: e = fwd_a<7>(in, n, logM, C, mid, t, aligned, s); break;
-        case 8: e = fwd_a<8>(in, n, logM, C, mid, t, aligned, s); break;
-        case 9: e = fwd_a<9>(in, n, logM, C, mid, t, aligned, s); break;
-        case 10: e = fwd_a<10>(in, n, logM, C, mid, t, aligned, s); break;
-        case 11: e = fwd_a<11>(in, n, logM, C, mid, t, aligned, s); break;
+        case 7: e = fwd_a<7>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
+        case 8: e = fwd_a<8>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
+        case 9: e = fwd_a<9>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
+        case 10: e = fwd_a<10>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
+        case 11: e = fwd_a<11>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;

@@ -31,11 +31,11 @@ constexpr int kKeyShift = 31 - kHistBits;     // bucket = key >> 19
 struct Workspace {
     size_t status;    // u32[64]   word 0 = device status
     size_t hist;      // u32[C][kHistBins]         (directly after status: one fill zeroes both)
-    size_t sel;       // u32[C][8]  bstar, need, tau, quota, pbase, vmax, -, -
+    size_t sel;       // u32[C][8]  bstar, need, tau, quota, pbase, vmax, -, decode verdict
     size_t tinfo;     // u32[C][Tn][4]  n_def, vmax_def, n_cand, -
     size_t tscan;     // u32[C][Tn][2]  first rank of the tile, equal-key count before the tile
     size_t cand;      // uint2[C][Tn*kTile]  (key, max component bits) of threshold-bucket bins, tile-ordered
-    size_t prefix;    // u32[C][W]  set bits before each bitmap word (decode)
+    size_t prefix;    // u32[C][ceil(W/16)]  set bits before each group of 16 bitmap words (decode)
     size_t spec;      // float[C][L+2]  spectrum
     size_t mid;       // float2[C][L/2] intermediate of the two-pass FFT
     size_t total;
@@ -85,9 +85,10 @@ hipError_t get_tables(Tables* out);
 
 // FFT launchers (fft.hip).  Chunk c covers in[c*L, min(n, (c+1)*L)), zero beyond n.
 // spec: C*(L+2) floats; mid: C*L floats of scratch (unused when L <= 2^14).
-// hist (optional): u32[C][kHistBins], zeroed by the caller; if the FFT filled it, *hist_done is set to 1.
+// hist (optional): u32[C][kHistBins]; the two-pass kernels clear zero_words words at zero_ptr (covering hist and
+// the status words) and fill hist, setting *hist_done = 1; otherwise the caller clears and fills it.
 hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, float2* mid, Tables t,
-                       uint32_t* hist, int* hist_done, hipStream_t s);
+                       uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, hipStream_t s);
 hipError_t launch_irfft(const float* spec, size_t n, int logL, size_t C, float* out, float2* mid, Tables t,
                         hipStream_t s);
 
@@ -108,9 +109,9 @@ struct CodecArgs {
 // hist_ready != 0: the status words are cleared and the per-chunk histograms already hold the keys' top digit
 hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
                          uint8_t* ws_base, const Workspace& w, int hist_ready, hipStream_t s);
-hipError_t launch_zero_hist(uint8_t* ws_base, const Workspace& w, size_t C, hipStream_t s);
+
+// reset_status != 0: this call also clears the device status word (first record set of a stream)
 hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
-                         uint8_t* ws_base, const Workspace& w, int check_header, hipStream_t s);
-hipError_t launch_zero_status(uint8_t* ws_base, const Workspace& w, hipStream_t s);
+                         uint8_t* ws_base, const Workspace& w, int check_header, int reset_status, hipStream_t s);
 
 }  // namespace fftsp
