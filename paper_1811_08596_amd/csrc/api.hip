@@ -151,6 +151,7 @@ CodecArgs codec_args(const Plan& p, float theta)
     a.m = p.m;
     a.S = p.S;
     a.word3 = 0;
+    a.sstride = p.L / 2 + 1;  // dense layout; the codec's own buffer overrides this
     a.write_header = 1;
     a.hdr_n = p.n;
     a.hdr_L = p.L;
@@ -206,7 +207,7 @@ int fftsp_rfft(const float* d_grad, size_t n, uint32_t chunk_len, float* d_spec,
     Tables t;
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
-    return hip_status(launch_rfft(d_grad, n, p.logL, p.C, d_spec, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+    return hip_status(launch_rfft(d_grad, n, p.logL, p.C, d_spec, p.L / 2 + 1, reinterpret_cast<float2*>(ws + p.ws.mid), t,
                                   nullptr, nullptr, 0, nullptr, reinterpret_cast<hipStream_t>(stream)));
 }
 
@@ -223,7 +224,7 @@ int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad
     Tables t;
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
-    return hip_status(launch_irfft(d_spec, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+    return hip_status(launch_irfft(d_spec, p.L / 2 + 1, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
                                    reinterpret_cast<hipStream_t>(stream)));
 }
 
@@ -277,12 +278,14 @@ int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float thet
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
     int hist_done = 0;
-    hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+    CodecArgs a = codec_args(p, theta);
+    a.sstride = padded_bins(p.L);
+    hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, a.sstride, reinterpret_cast<float2*>(ws + p.ws.mid), t,
                                reinterpret_cast<uint32_t*>(ws + p.ws.hist),
                                reinterpret_cast<uint32_t*>(ws + p.ws.status),
                                (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, &hist_done, s);
     if (e == hipSuccess)
-        e = launch_encode(spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws, hist_done, s);
+        e = launch_encode(spec, a, out, out + kStreamHeader, ws, p.ws, hist_done, s);
     return hip_status(e);
 }
 
@@ -303,9 +306,11 @@ int fftsp_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_ou
     const uint8_t* in = static_cast<const uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
-    hipError_t e = launch_decode(in, in + kStreamHeader, codec_args(p, theta), spec, ws, p.ws, 1, 1, s);
+    CodecArgs a = codec_args(p, theta);
+    a.sstride = padded_bins(p.L);
+    hipError_t e = launch_decode(in, in + kStreamHeader, a, spec, ws, p.ws, 1, 1, s);
     if (e == hipSuccess)
-        e = launch_irfft(spec, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t, s);
+        e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t, s);
     return hip_status(e);
 }
 
@@ -374,6 +379,7 @@ int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int 
         a.m = m;
         a.S = record_stride(L, a.k, bits);
         a.word3 = L;
+        a.sstride = padded_bins(L);
         a.write_header = (i == 0);
         a.hdr_n = seg_offsets[nseg] - seg_offsets[0];
         a.hdr_L = 0;
@@ -383,7 +389,7 @@ int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int 
         a.hdr_theta = theta;
         float* spec = reinterpret_cast<float*>(ws + w.spec);
         int hist_done = 0;
-        hipError_t e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec,
+        hipError_t e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec, a.sstride,
                                    reinterpret_cast<float2*>(ws + w.mid), t, reinterpret_cast<uint32_t*>(ws + w.hist),
                                    reinterpret_cast<uint32_t*>(ws + w.status),
                                    (w.hist - w.status) / 4 + (size_t)kHistBins, &hist_done, s);
@@ -426,6 +432,7 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
         a.m = m;
         a.S = record_stride(L, a.k, bits);
         a.word3 = L;
+        a.sstride = padded_bins(L);
         a.hdr_n = seg_offsets[nseg] - seg_offsets[0];
         a.hdr_L = 0;
         a.hdr_C = (uint32_t)nseg;
@@ -435,7 +442,7 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
         float* spec = reinterpret_cast<float*>(ws + w.spec);
         hipError_t e = launch_decode(in, in + rec_off, a, spec, ws, w, i == 0, i == 0, s);
         if (e == hipSuccess)
-            e = launch_irfft(spec, size, log2_exact(L), 1, d_grad_out + seg_offsets[i],
+            e = launch_irfft(spec, a.sstride, size, log2_exact(L), 1, d_grad_out + seg_offsets[i],
                              reinterpret_cast<float2*>(ws + w.mid), t, s);
         if (e != hipSuccess) return FFTSP_EHIP;
         rec_off += a.S;

@@ -83,7 +83,7 @@ __global__ void k_zero_u32(uint32_t* p, size_t count)
 // ------------------------------------------------------------- histogram ----
 constexpr int HIST_TILES = 4;  // tiles per workgroup
 
-__global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, uint32_t B, uint32_t groups,
+__global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, uint32_t sstride, uint32_t B, uint32_t groups,
                                              uint32_t* __restrict__ hist)
 {
     __shared__ uint32_t h[kHistBins];
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, ui
     const uint32_t base = (blockIdx.x % groups) * (HIST_TILES * kTile);
     for (int i = tid; i < kHistBins; i += NT) h[i] = 0u;
     __syncthreads();
-    const float2* X = spec + c * (size_t)B;
+    const float2* X = spec + c * (size_t)sstride;
 #pragma unroll 4
     for (int i = tid; i < HIST_TILES * kTile; i += NT) {
         const uint32_t j = base + i;
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(NT) void k_find_bucket(const uint32_t* __restrict__
 
 // --------------------------------------------------------------- collect ----
 // Per tile: count and range of the bins kept outright, and the candidates in bin order.
-__global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec, uint32_t B, uint32_t Tn,
+__global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec, uint32_t sstride, uint32_t B, uint32_t Tn,
                                                 const uint32_t* __restrict__ sel, uint32_t* __restrict__ tinfo,
                                                 uint2* __restrict__ cand)
 {
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
     const size_t c = blockIdx.x / Tn;
     const uint32_t tile = blockIdx.x % Tn;
     const uint32_t bstar = sel[c * 8 + 0];
-    const float2* X = spec + c * (size_t)B;
+    const float2* X = spec + c * (size_t)sstride;
     const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
     uint32_t key[ROWS], vb[ROWS];
     uint64_t cm[ROWS];
@@ -472,7 +472,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
 
 // ------------------------------------------------------------------ emit ----
 // Per tile: flags, ranks, Algorithm 1 codes, bit-packing, bitmap words.
-__global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, uint32_t B, uint32_t Tn, uint32_t W,
+__global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, uint32_t sstride, uint32_t B, uint32_t Tn, uint32_t W,
                                              int bits, int m, size_t S, const uint32_t* __restrict__ sel,
                                              const uint32_t* __restrict__ tscan, uint8_t* __restrict__ records)
 {
@@ -489,7 +489,7 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     const uint32_t lds_words = (uint32_t)kTile * twoN / 32u + 2u;
     for (uint32_t i = tid; i < lds_words; i += NT) cw[i] = 0u;
 
-    const float2* X = spec + c * (size_t)B;
+    const float2* X = spec + c * (size_t)sstride;
     const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
     float2 z[ROWS];
     uint64_t gm[ROWS], em[ROWS], fm[ROWS];
@@ -639,7 +639,7 @@ __device__ __forceinline__ uint32_t fetch_code(const uint32_t* __restrict__ code
 __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
                                                uint32_t k, int bits, int m, uint32_t Tn,
                                                const uint32_t* __restrict__ gprefix, const uint32_t* __restrict__ sel,
-                                               uint32_t* __restrict__ status, float2* __restrict__ spec)
+                                               uint32_t* __restrict__ status, float2* __restrict__ spec, uint32_t sstride)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t c = blockIdx.x / Tn;
@@ -659,7 +659,7 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
     uint32_t run = g < G ? gprefix[c * G + g] : 0u;
     const uint64_t lt = lanemask_lt();
     const int shift = 23 - m;
-    float2* X = spec + c * (size_t)B;
+    float2* X = spec + c * (size_t)sstride;
     const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
@@ -716,10 +716,10 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
         hipError_t e = launch_zero_hist(ws_base, w, a.C, s);
         if (e != hipSuccess) return e;
         const uint32_t groups = (Tn + HIST_TILES - 1) / HIST_TILES;
-        FFTSP_LAUNCH("hist", k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, B, groups, hist);
+        FFTSP_LAUNCH("hist", k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, a.sstride, B, groups, hist);
     }
     FFTSP_LAUNCH("find_bucket", k_find_bucket, dim3((unsigned)a.C), dim3(NT), 0, s, hist, a.k, sel);
-    FFTSP_LAUNCH("collect", k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, sel, tinfo, cand);
+    FFTSP_LAUNCH("collect", k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, B, Tn, sel, tinfo, cand);
     HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
                  a.hdr_theta};
     // up to 12 Ki candidates (96 KiB) are staged in LDS by the per-chunk workgroup
@@ -733,7 +733,7 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     }
     FFTSP_LAUNCH("resolve", k_resolve, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k, a.bits, a.m,
                  W, a.S, a.word3, kStageCap, sel, tinfo, tscan, cand, records, stream_base, h);
-    FFTSP_LAUNCH("emit", k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
+    FFTSP_LAUNCH("emit", k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
                        records);
     return hipGetLastError();
 }
@@ -751,7 +751,7 @@ hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, con
     FFTSP_LAUNCH("group_prefix", k_group_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k,
                  a.word3, h, gprefix, sel, status, reset_status);
     FFTSP_LAUNCH("decode", k_decode, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m,
-                 Tn, gprefix, sel, status, reinterpret_cast<float2*>(spec));
+                 Tn, gprefix, sel, status, reinterpret_cast<float2*>(spec), a.sstride);
     return hipGetLastError();
 }
 

@@ -215,7 +215,7 @@ __device__ __forceinline__ float2 split_inv(float2 a, float2 b, float2 w)
 // M = 2^LOGM <= 2^13 complex points per chunk, 2^(LOGE-LOGM) chunks per workgroup.
 template <int LOGM, int LOGE, int NT>
 __global__ __launch_bounds__(NT) void k_fwd_small(const float* __restrict__ in, size_t n, size_t C,
-                                                  float2* __restrict__ spec, Tables tb, int aligned)
+                                                  float2* __restrict__ spec, uint32_t sstride, Tables tb, int aligned)
 {
     constexpr int M = 1 << LOGM, LOGT = LOGE - LOGM, ELEMS = 1 << LOGE;
     extern __shared__ float2 smem[];
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(NT) void k_fwd_small(const float* __restrict__ in, 
         const int w = tid + q * NT, k = w & (M - 1), b = w >> LOGM;
         const size_t c = c0 + b;
         if (c >= C) continue;
-        float2* out = spec + c * (size_t)(M + 1);
+        float2* out = spec + c * (size_t)sstride;
         const float2 a = d[sw_idx<LOGT>(k, b)];
         if (k == 0) {
             out[0] = make_float2(a.x + a.y, 0.f);
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(NT) void k_fwd_small(const float* __restrict__ in, 
 }
 
 template <int LOGM, int LOGE, int NT>
-__global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spec, size_t n, size_t C,
+__global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spec, uint32_t sstride, size_t n, size_t C,
                                                   float* __restrict__ out, Tables tb, int aligned)
 {
     constexpr int M = 1 << LOGM, LOGT = LOGE - LOGM, ELEMS = 1 << LOGE;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spe
         const size_t c = c0 + b;
         float2 z = make_float2(0.f, 0.f);
         if (c < C) {
-            const float2* X = spec + c * (size_t)(M + 1);
+            const float2* X = spec + c * (size_t)sstride;
             float2 a = X[k], bq = X[M - k];
             if (k == 0) {  // imaginary parts of the DC and Nyquist bins are ignored
                 a.y = 0.f;
@@ -412,8 +412,8 @@ __device__ __forceinline__ uint32_t fft_key_of(float2 z)
 // if hist != nullptr, the first radix-select digit of every bin's key (12-bit histogram per chunk).
 template <int LOGN2>
 __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, int logM, float2* __restrict__ spec,
-                                               Tables tb, uint32_t* __restrict__ hist, uint32_t total,
-                                               uint32_t per_wg)
+                                               uint32_t sstride, Tables tb, uint32_t* __restrict__ hist,
+                                               uint32_t total, uint32_t per_wg)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, TB = T2 / 2, ELEMS = 1 << LOGE;
@@ -452,7 +452,7 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
         if (more) load_tile(t + 1, tid);
         run_fft<LOGN2, LOGT, NT, false>(d, tw, tid);
         const size_t c = t / tiles;
-        float2* out = spec + c * (size_t)(M + 1);
+        float2* out = spec + c * (size_t)sstride;
         const uint32_t k1 = row_of_pos((t % tiles) * T2 + slot, N1);
         const bool self = (k1 == 0) || (k1 == N1 / 2);
         const int ps = self ? slot : (slot ^ 1);
@@ -503,8 +503,8 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
 
 // Inverse pass B: undo the split, inverse N2-point FFTs over k2, times conj W_M^(n2 k1).
 template <int LOGN2>
-__global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, int logM, float2* __restrict__ mid,
-                                               Tables tb, uint32_t total, uint32_t per_wg)
+__global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, uint32_t sstride, int logM,
+                                               float2* __restrict__ mid, Tables tb, uint32_t total, uint32_t per_wg)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, TB = T2 / 2, ELEMS = 1 << LOGE;
@@ -525,7 +525,7 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
     float2 xnyq = make_float2(0.f, 0.f);
     auto load_tile = [&](uint32_t tile, int tid) {
         const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
-        const float2* X = spec + (size_t)(tile / tiles) * (size_t)(M + 1);
+        const float2* X = spec + (size_t)(tile / tiles) * (size_t)sstride;
         const uint32_t row = row_of_pos((tile % tiles) * T2 + slot, N1);
 #pragma unroll
         for (int q = 0; q < PER; ++q) r[q] = X[row + ((uint32_t)(kq0 + q * DK) << logN1)];
@@ -651,7 +651,8 @@ hipError_t set_lds(K kernel, size_t bytes)
 }
 
 template <int LOGM>
-hipError_t small_fwd(const float* in, size_t n, size_t C, float2* spec, Tables t, int aligned, hipStream_t s)
+hipError_t small_fwd(const float* in, size_t n, size_t C, float2* spec, uint32_t sstride, Tables t, int aligned,
+                     hipStream_t s)
 {
     constexpr int LOGE = LOGM >= 12 ? LOGM : 12;
     const size_t lds = ((size_t)(1 << LOGE) + (1 << LOGM)) * sizeof(float2);
@@ -659,13 +660,14 @@ hipError_t small_fwd(const float* in, size_t n, size_t C, float2* spec, Tables t
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
-    FFTSP_LAUNCH("rfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, in, n, C, spec, t,
-                 aligned);
+    FFTSP_LAUNCH("rfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, in, n, C, spec, sstride,
+                 t, aligned);
     return hipGetLastError();
 }
 
 template <int LOGM>
-hipError_t small_inv(const float2* spec, size_t n, size_t C, float* out, Tables t, int aligned, hipStream_t s)
+hipError_t small_inv(const float2* spec, uint32_t sstride, size_t n, size_t C, float* out, Tables t, int aligned,
+                     hipStream_t s)
 {
     constexpr int LOGE = LOGM >= 12 ? LOGM : 12;
     const size_t lds = ((size_t)(1 << LOGE) + (1 << LOGM)) * sizeof(float2);
@@ -673,8 +675,8 @@ hipError_t small_inv(const float2* spec, size_t n, size_t C, float* out, Tables 
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
-    FFTSP_LAUNCH("irfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, spec, n, C, out,
-                 t, aligned);
+    FFTSP_LAUNCH("irfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, spec, sstride, n, C,
+                 out, t, aligned);
     return hipGetLastError();
 }
 
@@ -707,7 +709,8 @@ hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tab
 }
 
 template <int LOGN2>
-hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, Tables t, uint32_t* hist, hipStream_t s)
+hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, uint32_t sstride, Tables t, uint32_t* hist,
+                 hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2) + kHistLdsWords * sizeof(uint32_t);
     auto kern = k_fwd_b<LOGN2>;
@@ -715,13 +718,13 @@ hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, Tables t, 
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
     const Grid g = persistent_grid(total);
-    FFTSP_LAUNCH("rfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, spec, t, hist, (uint32_t)total,
-                 g.per_wg);
+    FFTSP_LAUNCH("rfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, spec, sstride, t, hist,
+                 (uint32_t)total, g.per_wg);
     return hipGetLastError();
 }
 
 template <int LOGN2>
-hipError_t inv_b(const float2* spec, int logM, size_t C, float2* mid, Tables t, hipStream_t s)
+hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float2* mid, Tables t, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2);
     auto kern = k_inv_b<LOGN2>;
@@ -729,7 +732,8 @@ hipError_t inv_b(const float2* spec, int logM, size_t C, float2* mid, Tables t, 
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
     const Grid g = persistent_grid(total);
-    FFTSP_LAUNCH("irfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, spec, logM, mid, t, (uint32_t)total, g.per_wg);
+    FFTSP_LAUNCH("irfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, spec, sstride, logM, mid, t, (uint32_t)total,
+                 g.per_wg);
     return hipGetLastError();
 }
 
@@ -754,8 +758,8 @@ hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Ta
 // hist (optional, u32[C][kHistBins]): receives the 12-bit histogram of the keys' top bits when the two-pass
 // kernels run; they first clear zero_words words at zero_ptr (which must cover hist).  *hist_done = 1 if the
 // FFT filled hist, 0 if the caller still has to clear and fill it (single-workgroup sizes).
-hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, float2* mid, Tables t,
-                       uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, hipStream_t s)
+hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, uint32_t sstride, float2* mid,
+                       Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, hipStream_t s)
 {
     if (zero_words > 0xffffffffu) return hipErrorInvalidValue;
     if (!hist) zero_words = 0;
@@ -766,7 +770,7 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     if (C * ((size_t)1 << (logM > 13 ? logM - 13 : 0)) > 0x7fffffffu) return hipErrorInvalidValue;
     switch (logM) {
 #define X(p) \
-    case p: return small_fwd<p>(in, n, C, sp, t, aligned, s);
+    case p: return small_fwd<p>(in, n, C, sp, sstride, t, aligned, s);
         FFTSP_SMALL_CASES(X)
 #undef X
         default: break;
@@ -784,16 +788,16 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     if (e != hipSuccess) return e;
     if (hist_done) *hist_done = hist != nullptr;
     switch (logN2) {
-        case 7: return fwd_b<7>(mid, logM, C, sp, t, hist, s);
-        case 8: return fwd_b<8>(mid, logM, C, sp, t, hist, s);
-        case 9: return fwd_b<9>(mid, logM, C, sp, t, hist, s);
-        case 10: return fwd_b<10>(mid, logM, C, sp, t, hist, s);
+        case 7: return fwd_b<7>(mid, logM, C, sp, sstride, t, hist, s);
+        case 8: return fwd_b<8>(mid, logM, C, sp, sstride, t, hist, s);
+        case 9: return fwd_b<9>(mid, logM, C, sp, sstride, t, hist, s);
+        case 10: return fwd_b<10>(mid, logM, C, sp, sstride, t, hist, s);
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_irfft(const float* spec, size_t n, int logL, size_t C, float* out, float2* mid, Tables t,
-                        hipStream_t s)
+hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
+                        Tables t, hipStream_t s)
 {
     const int logM = logL - 1;
     const int aligned = (reinterpret_cast<uintptr_t>(out) & 7u) == 0;
@@ -801,7 +805,7 @@ hipError_t launch_irfft(const float* spec, size_t n, int logL, size_t C, float* 
     if (C * ((size_t)1 << (logM > 13 ? logM - 13 : 0)) > 0x7fffffffu) return hipErrorInvalidValue;
     switch (logM) {
 #define X(p) \
-    case p: return small_inv<p>(sp, n, C, out, t, aligned, s);
+    case p: return small_inv<p>(sp, sstride, n, C, out, t, aligned, s);
         FFTSP_SMALL_CASES(X)
 #undef X
         default: break;
@@ -809,10 +813,10 @@ hipError_t launch_irfft(const float* spec, size_t n, int logL, size_t C, float* 
     const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
     hipError_t e;
     switch (logN2) {
-        case 7: e = inv_b<7>(sp, logM, C, mid, t, s); break;
-        case 8: e = inv_b<8>(sp, logM, C, mid, t, s); break;
-        case 9: e = inv_b<9>(sp, logM, C, mid, t, s); break;
-        case 10: e = inv_b<10>(sp, logM, C, mid, t, s); break;
+        case 7: e = inv_b<7>(sp, sstride, logM, C, mid, t, s); break;
+        case 8: e = inv_b<8>(sp, sstride, logM, C, mid, t, s); break;
+        case 9: e = inv_b<9>(sp, sstride, logM, C, mid, t, s); break;
+        case 10: e = inv_b<10>(sp, sstride, logM, C, mid, t, s); break;
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;

@@ -36,7 +36,7 @@ struct Workspace {
     size_t tscan;     // u32[C][Tn][2]  first rank of the tile, equal-key count before the tile
     size_t cand;      // uint2[C][Tn*kTile]  (key, max component bits) of threshold-bucket bins, tile-ordered
     size_t prefix;    // u32[C][ceil(W/16)]  set bits before each group of 16 bitmap words (decode)
-    size_t spec;      // float[C][L+2]  spectrum
+    size_t spec;      // float2[C][padded_bins(L)]  spectrum, each chunk on a 128-byte boundary
     size_t mid;       // float2[C][L/2] intermediate of the two-pass FFT
     size_t total;
 };
@@ -44,6 +44,8 @@ struct Workspace {
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 static inline uint32_t tiles_per_chunk(uint32_t L) { return ((L / 2 + 1) + kTile - 1) / kTile; }
+// chunk stride of the codec's own spectrum buffer, in complex bins: L/2+1 rounded up to a 128-byte multiple
+static inline uint32_t padded_bins(uint32_t L) { return (L / 2 + 1 + 15u) & ~15u; }
 
 static inline Workspace make_workspace(size_t C, uint32_t L)
 {
@@ -57,7 +59,7 @@ static inline Workspace make_workspace(size_t C, uint32_t L)
     w.tscan = off;  off = align256(off + C * Tn * 8);
     w.cand = off;   off = align256(off + C * Tn * kTile * 8);
     w.prefix = off; off = align256(off + C * W * 4);
-    w.spec = off;   off = align256(off + C * ((size_t)L + 2) * 4);
+    w.spec = off;   off = align256(off + C * (size_t)padded_bins(L) * 8);
     w.mid = off;    off = align256(off + C * (size_t)L * 4);
     w.total = off;
     return w;
@@ -84,13 +86,15 @@ std::string report();
 hipError_t get_tables(Tables* out);
 
 // FFT launchers (fft.hip).  Chunk c covers in[c*L, min(n, (c+1)*L)), zero beyond n.
-// spec: C*(L+2) floats; mid: C*L floats of scratch (unused when L <= 2^14).
+// spec: chunk c's L/2+1 bins start at spec + 2*c*sstride floats (sstride in complex bins: L/2+1 for the dense
+// layout of the stage-level entry points, a multiple of 16 inside the codec so that every chunk starts on a
+// 128-byte line); mid: C*L floats of scratch (unused when L <= 2^14).
 // hist (optional): u32[C][kHistBins]; the two-pass kernels clear zero_words words at zero_ptr (covering hist and
 // the status words) and fill hist, setting *hist_done = 1; otherwise the caller clears and fills it.
-hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, float2* mid, Tables t,
-                       uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, hipStream_t s);
-hipError_t launch_irfft(const float* spec, size_t n, int logL, size_t C, float* out, float2* mid, Tables t,
-                        hipStream_t s);
+hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, uint32_t sstride, float2* mid,
+                       Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, hipStream_t s);
+hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
+                        Tables t, hipStream_t s);
 
 // Codec launchers (codec.hip).
 struct CodecArgs {
@@ -100,6 +104,7 @@ struct CodecArgs {
     int bits, m;        // code width, mantissa width
     size_t S;           // record stride in bytes
     uint32_t word3;     // 4th word of every record header
+    uint32_t sstride;   // distance between consecutive chunks' spectra, in complex bins
     // stream header (written iff write_header)
     int write_header;
     uint64_t hdr_n;
