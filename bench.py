@@ -44,6 +44,22 @@ def kernel_algorithmic_bytes(name: str, n: int, L: int, theta: float, bits: int)
     return table.get(name, 0.0)
 
 
+def measured_traffic_bytes(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
+    scaled by the plain-copy calibration stated in that file), or None if the summary does not cover it."""
+    names = {"rfft_pass_a": "k_fwd_a", "rfft_pass_b": "k_fwd_b", "irfft_pass_b": "k_inv_b", "irfft_pass_a": "k_inv_a",
+             "collect": "k_collect", "emit": "k_emit", "decode": "k_decode"}
+    path = os.path.join(ROOT, "profiles", "codec_config3_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 8 and f[0] == names.get(kernel):
+                return int((float(f[4]) + float(f[5])) * 1e6)
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -161,7 +177,8 @@ def main() -> int:
         "compression_ratio": round(4.0 * n / nbytes, 3),
         "alpha": round(alpha, 5),
         "roofline": {"bound": "hbm", "kernel": dom_name, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic_bytes(dom_name),
                      "algorithmic_bytes_per_launch": int(dom_bytes), "avg_us": round(dom_avg_s * 1e6, 2)},
         "kernels_avg_us": kernels_us,
         "kernels_algorithmic_GBps": kernels_gbs,
