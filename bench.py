@@ -22,7 +22,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 
 def kernel_algorithmic_bytes(name: str, n: int, L: int, theta: float, bits: int) -> float:
-    """Bytes a kernel has to move for the n-element gradient, per launch ("Kernels")."""
+    """Bytes a kernel has to read plus write once for the n-element gradient, per launch: its inputs and
+    outputs at their stored width (fp32 gradient, float2 bins, float2 intermediate, packed bitmap + codes)."""
     C = (n + L - 1) // L
     bins = C * (L // 2 + 1)
     spec = 8.0 * bins                       # one pass over the spectrum

@@ -33,7 +33,11 @@ __device__ __forceinline__ uint32_t vbits_of(float2 z)
     const uint32_t a = __float_as_uint(z.x) & 0x7FFFFFFFu, b = __float_as_uint(z.y) & 0x7FFFFFFFu;
     return a > b ? a : b;
 }
-__device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << (threadIdx.x & 63)) - 1ull; }
+// number of set bits of a wave-uniform mask below this lane (v_mbcnt_lo/hi: two instructions, no 64-bit math)
+__device__ __forceinline__ uint32_t prefix_popc(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
 
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v)
 {
@@ -174,7 +178,7 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
     const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
     uint32_t key[ROWS], vb[ROWS];
     uint64_t cm[ROWS];
-    uint32_t ndef = 0, vmax = 0, ncand = 0;
+    uint32_t ndef = 0, vmax = 0, ncand = 0, mine = 0;  // mine: bit r set = this lane's bin of row r is a candidate
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
@@ -189,6 +193,7 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
             ++ndef;
             vmax = vb[r] > vmax ? vb[r] : vmax;
         }
+        mine |= (uint32_t)iscand << r;
         cm[r] = __ballot(iscand);
         ncand += (uint32_t)__popcll(cm[r]);
     }
@@ -203,10 +208,9 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
     uint32_t off = 0;
     for (int w = 0; w < wave; ++w) off += wcnt[w];
     uint2* out = cand + (c * Tn + tile) * (size_t)kTile;
-    const uint64_t lt = lanemask_lt();
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        if ((cm[r] >> lane) & 1ull) out[off + (uint32_t)__popcll(cm[r] & lt)] = make_uint2(key[r], vb[r]);
+        if ((mine >> r) & 1u) out[off + prefix_popc(cm[r])] = make_uint2(key[r], vb[r]);
         off += (uint32_t)__popcll(cm[r]);
     }
     if (tid == 0) {
@@ -298,9 +302,15 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     }
     const bool staged = s_carry[0] <= stage_cap;
     if (staged) {
-        for (uint32_t t = wave; t < Tn; t += RW) {
-            const uint32_t nc = tnc[t], o = toff[t];
-            for (uint32_t i = lane; i < nc; i += 64) stage[o + i] = cd[(size_t)t * kTile + i];
+        // flat copy with every lane busy: candidate i belongs to the last tile whose offset is <= i
+        const uint32_t total = s_carry[0];
+        for (uint32_t i = tid; i < total; i += RT) {
+            uint32_t lo = 0, hi = Tn - 1;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi + 1) >> 1;
+                if (toff[mid] <= i) lo = mid; else hi = mid - 1;
+            }
+            stage[i] = cd[(size_t)lo * kTile + (i - toff[lo])];
         }
     }
     __syncthreads();
@@ -411,7 +421,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             const uint2 e = valid ? cand_at(t, i) : make_uint2(0u, 0u);
             const bool iseq = valid && e.x == tau;
             const uint64_t em = __ballot(iseq);
-            const bool kept = valid && (e.x > tau || (iseq && eqrun + (uint32_t)__popcll(em & lanemask_lt()) < take));
+            const bool kept = valid && (e.x > tau || (iseq && eqrun + prefix_popc(em) < take));
             if (kept) vm = e.y > vm ? e.y : vm;
             eqrun += (uint32_t)__popcll(em);
         }
@@ -492,30 +502,34 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     const float2* X = spec + c * (size_t)sstride;
     const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
     float2 z[ROWS];
-    uint64_t gm[ROWS], em[ROWS], fm[ROWS];
-    uint32_t neq = 0;
+    uint64_t em[ROWS], fm[ROWS];
+    uint32_t neq = 0, gtbits = 0, eqbits = 0;  // bit r = this lane's bin of row r is above / equal to the threshold
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
         z[r] = valid ? X[j] : make_float2(0.f, 0.f);
         const uint32_t key = key_of(z[r]);
-        gm[r] = __ballot(valid && key > tau);
-        em[r] = __ballot(valid && key == tau);
+        const bool gt = valid && key > tau, eq = valid && key == tau;
+        gtbits |= (uint32_t)gt << r;
+        eqbits |= (uint32_t)eq << r;
+        em[r] = __ballot(eq);
         neq += (uint32_t)__popcll(em[r]);
     }
     if (lane == 0) weq[wave] = neq;
-    __syncthreads();  // also orders the zeroing of cw before the atomics below
+    __syncthreads();  // also orders the zeroing of cw before the writes below
     uint32_t eqrun = eq0;
     for (int w = 0; w < wave; ++w) eqrun += weq[w];
-    const uint64_t lt = lanemask_lt();
-    uint32_t nfl = 0;
+    uint32_t nfl = 0, flbits = 0;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
-        const bool gt = (gm[r] >> lane) & 1ull, eq = (em[r] >> lane) & 1ull;
-        const bool flag = gt || (eq && eqrun + (uint32_t)__popcll(em[r] & lt) < quota);
+        bool flag = (gtbits >> r) & 1u;
+        if (em[r]) {  // wave-uniform: ties are rare, skip their bookkeeping otherwise
+            flag = flag || (((eqbits >> r) & 1u) && eqrun + prefix_popc(em[r]) < quota);
+            eqrun += (uint32_t)__popcll(em[r]);
+        }
+        flbits |= (uint32_t)flag << r;
         fm[r] = __ballot(flag);
-        eqrun += (uint32_t)__popcll(em[r]);
         nfl += (uint32_t)__popcll(fm[r]);
     }
     if (lane == 0) {
@@ -531,23 +545,39 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     for (int w = 0; w < wave; ++w) rank += wfl[w];
     const uint32_t total = wfl[0] + wfl[1] + wfl[2] + wfl[3];
     const uint32_t w0 = (twoN * rank0) >> 5;
+    if (bits == 8) {
+        // two 8-bit codes per survivor = one aligned 16-bit store, no read-modify-write
+        uint16_t* cw16 = reinterpret_cast<uint16_t*>(cw);
+        const uint32_t base16 = rank0 - 2u * w0;  // first survivor's 16-bit slot inside cw
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        if ((fm[r] >> lane) & 1ull) {
-            const uint32_t rk = rank + (uint32_t)__popcll(fm[r] & lt);
-            const uint32_t cre = quantize(__float_as_uint(z[r].x), pbase, bits, shift);
-            const uint32_t cim = quantize(__float_as_uint(z[r].y), pbase, bits, shift);
-            uint32_t p = twoN * rk - (w0 << 5);  // bit position inside cw
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t code = h ? cim : cre;
-                const uint32_t wi = p >> 5, sh = p & 31u;
-                atomicOr(&cw[wi], code << sh);
-                if (sh + (uint32_t)bits > 32u) atomicOr(&cw[wi + 1], code >> (32u - sh));
-                p += (uint32_t)bits;
+        for (int r = 0; r < ROWS; ++r) {
+            if ((flbits >> r) & 1u) {
+                const uint32_t rk = rank + prefix_popc(fm[r]);
+                const uint32_t cre = quantize(__float_as_uint(z[r].x), pbase, 8, shift);
+                const uint32_t cim = quantize(__float_as_uint(z[r].y), pbase, 8, shift);
+                cw16[base16 + (rk - rank0)] = (uint16_t)(cre | (cim << 8));
             }
+            rank += (uint32_t)__popcll(fm[r]);
         }
-        rank += (uint32_t)__popcll(fm[r]);
+    } else {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if ((flbits >> r) & 1u) {
+                const uint32_t rk = rank + prefix_popc(fm[r]);
+                const uint32_t cre = quantize(__float_as_uint(z[r].x), pbase, bits, shift);
+                const uint32_t cim = quantize(__float_as_uint(z[r].y), pbase, bits, shift);
+                uint32_t p = twoN * rk - (w0 << 5);  // bit position inside cw
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t code = h ? cim : cre;
+                    const uint32_t wi = p >> 5, sh = p & 31u;
+                    atomicOr(&cw[wi], code << sh);
+                    if (sh + (uint32_t)bits > 32u) atomicOr(&cw[wi + 1], code >> (32u - sh));
+                    p += (uint32_t)bits;
+                }
+            }
+            rank += (uint32_t)__popcll(fm[r]);
+        }
     }
     __syncthreads();
     uint32_t* rec = reinterpret_cast<uint32_t*>(records + c * S);
@@ -657,7 +687,6 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
     uint32_t myword = 0;
     if (lane < GROUP_WORDS && g * GROUP_WORDS + lane < W) myword = bitmap[g * GROUP_WORDS + lane];
     uint32_t run = g < G ? gprefix[c * G + g] : 0u;
-    const uint64_t lt = lanemask_lt();
     const int shift = 23 - m;
     float2* X = spec + c * (size_t)sstride;
     const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
@@ -667,8 +696,9 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
         const uint64_t mask = (uint64_t)lo | ((uint64_t)hi << 32);
         const uint32_t j = j0 + r * 64;
         float2 out = make_float2(0.f, 0.f);
-        if (((mask >> lane) & 1ull) && k > 0) {
-            uint32_t rank = run + (uint32_t)__popcll(mask & lt);
+        const uint32_t half = lane < 32 ? lo : hi;
+        if (((half >> (lane & 31)) & 1u) && k > 0) {
+            uint32_t rank = run + prefix_popc(mask);
             rank = rank < k ? rank : k - 1u;  // a corrupt bitmap must not read outside the record
             uint32_t cre, cim;
             if (bits == 8) {

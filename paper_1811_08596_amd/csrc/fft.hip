@@ -361,10 +361,19 @@ __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, siz
     auto load_tile = [&](uint32_t tile, int tid) {
         const size_t cbase = (size_t)(tile / tiles) * (size_t)(2 * (size_t)M);
         const uint32_t col0 = (tile % tiles) << LOGT;
+        if (aligned && cbase + 2 * (size_t)M <= n) {  // whole chunk present: no per-element guards
+            const float2* src = reinterpret_cast<const float2*>(in + cbase) + col0;
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-            r[q] = load_pair(in, cbase + 2 * ((size_t)n1 * N2 + col0 + col), n, aligned);
+            for (int q = 0; q < PER; ++q) {
+                const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
+                r[q] = src[(uint32_t)n1 * N2 + col];
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
+                r[q] = load_pair(in, cbase + 2 * ((size_t)n1 * N2 + col0 + col), n, aligned);
+            }
         }
     };
     load_tile(t, tid0);
@@ -393,7 +402,7 @@ __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, siz
             for (int j = 0; j < NCOL; ++j) {
                 const uint32_t col = cfirst + j * DC, n2 = col0 + col;
                 if (j % 8 == 0) cur = twiddle(tb, (n2 * k1) << sh);
-                out[(size_t)n2 * N1 + pos] = cmul(d[sw_idx<LOGT>(k1, col)], cur);
+                out[n2 * N1 + pos] = cmul(d[sw_idx<LOGT>(k1, col)], cur);
                 cur = cmul(cur, ratio);
             }
         }
@@ -416,7 +425,7 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
                                                uint32_t total, uint32_t per_wg)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
-    constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, TB = T2 / 2, ELEMS = 1 << LOGE;
+    constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, ELEMS = 1 << LOGE;
     static_assert(NT % T2 == 0, "a lane keeps one slot");
     extern __shared__ float2 smem[];
     float2* d = smem;
@@ -439,7 +448,7 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
         const float2* src = mid + (size_t)(tile / tiles) * (size_t)M;
         const uint32_t pos = (tile % tiles) * T2 + slot;
 #pragma unroll
-        for (int q = 0; q < PER; ++q) r[q] = src[(size_t)(kq0 + q * DK) * N1 + pos];
+        for (int q = 0; q < PER; ++q) r[q] = src[(uint32_t)(kq0 + q * DK) * N1 + pos];
     };
     load_tile(t, tid0);
     for (;;) {
@@ -507,7 +516,7 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
                                                float2* __restrict__ mid, Tables tb, uint32_t total, uint32_t per_wg)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
-    constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, TB = T2 / 2, ELEMS = 1 << LOGE;
+    constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, ELEMS = 1 << LOGE;
     static_assert(NT % T2 == 0, "a lane keeps one slot");
     extern __shared__ float2 smem[];
     float2* d = smem;
@@ -575,7 +584,7 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
         for (int q = 0; q < PER; ++q) {
             const uint32_t n2 = (uint32_t)(kq0 + q * DK);
             if (q % 8 == 0) cur = twiddle(tb, (n2 * k1) << sh);
-            dst[(size_t)n2 * N1 + pos] = cmulc(d[sw_idx<LOGT>((int)n2, slot)], cur);
+            dst[n2 * N1 + pos] = cmulc(d[sw_idx<LOGT>((int)n2, slot)], cur);
             cur = cmul(cur, ratio);
         }
         if (!more) break;
@@ -608,7 +617,7 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
             const int w = tid + q * NT, pos = w & (N1 - 1), col = w >> LOGN1;
-            r[q] = src[(size_t)(col0 + col) * N1 + pos];
+            r[q] = src[(uint32_t)(col0 + col) * N1 + pos];
         }
     };
     load_tile(t, tid0);
@@ -626,12 +635,22 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
         run_fft<LOGN1, LOGT, NT, true>(d, tw, tid);
         const size_t cbase = (size_t)(t / tiles) * (size_t)(2 * (size_t)M);
         const uint32_t col0 = (t % tiles) << LOGT;
+        if (aligned && cbase + 2 * (size_t)M <= n) {  // whole chunk inside the output: no per-element guards
+            float2* dst = reinterpret_cast<float2*>(out + cbase) + col0;
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-            const float2 v = d[sw_idx<LOGT>(n1, col)];
-            store_pair(out, cbase + 2 * ((size_t)n1 * N2 + col0 + col), n, aligned,
-                       make_float2(v.x * scale, v.y * scale));
+            for (int q = 0; q < PER; ++q) {
+                const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
+                const float2 v = d[sw_idx<LOGT>(n1, col)];
+                dst[(uint32_t)n1 * N2 + col] = make_float2(v.x * scale, v.y * scale);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
+                const float2 v = d[sw_idx<LOGT>(n1, col)];
+                store_pair(out, cbase + 2 * ((size_t)n1 * N2 + col0 + col), n, aligned,
+                           make_float2(v.x * scale, v.y * scale));
+            }
         }
         if (!more) break;
         ++t;
