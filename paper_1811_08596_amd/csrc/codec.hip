@@ -363,14 +363,14 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     // per tile: candidates above tau and equal to tau
     for (uint32_t t = wave; t < Tn; t += RW) {
         const uint32_t nc = tnc[t];
-        uint32_t gt = 0, eq = 0;
-        for (uint32_t i = lane; i < nc; i += 64) {
-            const uint32_t key = cand_at(t, i).x;
-            gt += key > tau;
-            eq += key == tau;
+        uint32_t gt = 0, eq = 0;  // wave-uniform counts from ballots
+        for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
+            const uint32_t i = i0 + lane;
+            const bool valid = i < nc;
+            const uint32_t key = valid ? cand_at(t, i).x : 0u;
+            gt += (uint32_t)__popcll(__ballot(valid && key > tau));
+            eq += (uint32_t)__popcll(__ballot(valid && key == tau));
         }
-        gt = wave_sum(gt);
-        eq = wave_sum(eq);
         if (lane == 0) {
             tgt[t] = gt;
             teq[t] = eq;
@@ -411,9 +411,10 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     }
 
     // largest component over the survivors
+    uint32_t vm = 0;  // per-lane running maximum over all of this wave's tiles, reduced once at the end
     for (uint32_t t = wave; t < Tn; t += RW) {
         const uint32_t nc = tnc[t], take = ttake[t];
-        uint32_t vm = lane == 0 ? (tdef[t] ? tvd[t] : 0u) : 0u;
+        if (lane == 0 && tdef[t]) vm = tvd[t] > vm ? tvd[t] : vm;
         uint32_t eqrun = 0;
         for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
             const uint32_t i = i0 + lane;
@@ -425,9 +426,9 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             if (kept) vm = e.y > vm ? e.y : vm;
             eqrun += (uint32_t)__popcll(em);
         }
-        vm = wave_max(vm);
-        if (lane == 0 && vm) atomicMax(&s_vmax, vm);
     }
+    vm = wave_max(vm);
+    if (lane == 0 && vm) atomicMax(&s_vmax, vm);
     __syncthreads();
 
     const uint32_t vmax = s_vmax;
