@@ -151,7 +151,8 @@ CodecArgs codec_args(const Plan& p, float theta)
     a.m = p.m;
     a.S = p.S;
     a.word3 = 0;
-    a.sstride = p.L / 2 + 1;  // dense layout; the codec's own buffer overrides this
+    a.sstride = p.L / 2 + 1;  // dense layout, natural bin order; the codec's own buffer overrides both
+    a.pair_log = 0;
     a.write_header = 1;
     a.hdr_n = p.n;
     a.hdr_L = p.L;
@@ -208,7 +209,7 @@ int fftsp_rfft(const float* d_grad, size_t n, uint32_t chunk_len, float* d_spec,
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     return hip_status(launch_rfft(d_grad, n, p.logL, p.C, d_spec, p.L / 2 + 1, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                                  nullptr, nullptr, 0, nullptr, reinterpret_cast<hipStream_t>(stream)));
+                                  nullptr, nullptr, 0, nullptr, 0, nullptr, reinterpret_cast<hipStream_t>(stream)));
 }
 
 int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad_out, void* d_workspace,
@@ -225,7 +226,7 @@ int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     return hip_status(launch_irfft(d_spec, p.L / 2 + 1, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                                   reinterpret_cast<hipStream_t>(stream)));
+                                   0, reinterpret_cast<hipStream_t>(stream)));
 }
 
 int fftsp_encode_spectrum(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
@@ -283,7 +284,7 @@ int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float thet
     hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, a.sstride, reinterpret_cast<float2*>(ws + p.ws.mid), t,
                                reinterpret_cast<uint32_t*>(ws + p.ws.hist),
                                reinterpret_cast<uint32_t*>(ws + p.ws.status),
-                               (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, &hist_done, s);
+                               (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, &hist_done, 1, &a.pair_log, s);
     if (e == hipSuccess)
         e = launch_encode(spec, a, out, out + kStreamHeader, ws, p.ws, hist_done, s);
     return hip_status(e);
@@ -308,9 +309,11 @@ int fftsp_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_ou
     float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
     CodecArgs a = codec_args(p, theta);
     a.sstride = padded_bins(p.L);
+    a.pair_log = fft_pair_log(p.logL);
     hipError_t e = launch_decode(in, in + kStreamHeader, a, spec, ws, p.ws, 1, 1, s);
     if (e == hipSuccess)
-        e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t, s);
+        e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+                         a.pair_log != 0, s);
     return hip_status(e);
 }
 
@@ -392,7 +395,7 @@ int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int 
         hipError_t e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec, a.sstride,
                                    reinterpret_cast<float2*>(ws + w.mid), t, reinterpret_cast<uint32_t*>(ws + w.hist),
                                    reinterpret_cast<uint32_t*>(ws + w.status),
-                                   (w.hist - w.status) / 4 + (size_t)kHistBins, &hist_done, s);
+                                   (w.hist - w.status) / 4 + (size_t)kHistBins, &hist_done, 1, &a.pair_log, s);
         if (e == hipSuccess) e = launch_encode(spec, a, out, out + rec_off, ws, w, hist_done, s);
         if (e != hipSuccess) return FFTSP_EHIP;
         rec_off += a.S;
@@ -433,6 +436,7 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
         a.S = record_stride(L, a.k, bits);
         a.word3 = L;
         a.sstride = padded_bins(L);
+        a.pair_log = fft_pair_log(log2_exact(L));
         a.hdr_n = seg_offsets[nseg] - seg_offsets[0];
         a.hdr_L = 0;
         a.hdr_C = (uint32_t)nseg;
@@ -443,7 +447,7 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
         hipError_t e = launch_decode(in, in + rec_off, a, spec, ws, w, i == 0, i == 0, s);
         if (e == hipSuccess)
             e = launch_irfft(spec, a.sstride, size, log2_exact(L), 1, d_grad_out + seg_offsets[i],
-                             reinterpret_cast<float2*>(ws + w.mid), t, s);
+                             reinterpret_cast<float2*>(ws + w.mid), t, a.pair_log != 0, s);
         if (e != hipSuccess) return FFTSP_EHIP;
         rec_off += a.S;
     }

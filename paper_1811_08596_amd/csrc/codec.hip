@@ -87,7 +87,7 @@ __global__ void k_zero_u32(uint32_t* p, size_t count)
 // ------------------------------------------------------------- histogram ----
 constexpr int HIST_TILES = 4;  // tiles per workgroup
 
-__global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, uint32_t sstride, uint32_t B, uint32_t groups,
+__global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, uint32_t sstride, int pair_log, uint32_t B, uint32_t groups,
                                              uint32_t* __restrict__ hist)
 {
     __shared__ uint32_t h[kHistBins];
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, ui
 #pragma unroll 4
     for (int i = tid; i < HIST_TILES * kTile; i += NT) {
         const uint32_t j = base + i;
-        if (j < B) atomicAdd(&h[key_of(X[j]) >> kKeyShift], 1u);
+        if (j < B) atomicAdd(&h[key_of(X[spec_index(j, pair_log)]) >> kKeyShift], 1u);
     }
     __syncthreads();
     uint32_t* g = hist + c * kHistBins;
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(NT) void k_find_bucket(const uint32_t* __restrict__
 
 // --------------------------------------------------------------- collect ----
 // Per tile: count and range of the bins kept outright, and the candidates in bin order.
-__global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec, uint32_t sstride, uint32_t B, uint32_t Tn,
+__global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec, uint32_t sstride, int pair_log, uint32_t B, uint32_t Tn,
                                                 const uint32_t* __restrict__ sel, uint32_t* __restrict__ tinfo,
                                                 uint2* __restrict__ cand)
 {
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
-        const float2 z = valid ? X[j] : make_float2(0.f, 0.f);
+        const float2 z = valid ? X[spec_index(j, pair_log)] : make_float2(0.f, 0.f);
         key[r] = key_of(z);
         vb[r] = vbits_of(z);
         const uint32_t bucket = key[r] >> kKeyShift;
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
 
 // ------------------------------------------------------------------ emit ----
 // Per tile: flags, ranks, Algorithm 1 codes, bit-packing, bitmap words.
-__global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, uint32_t sstride, uint32_t B, uint32_t Tn, uint32_t W,
+__global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, uint32_t sstride, int pair_log, uint32_t B, uint32_t Tn, uint32_t W,
                                              int bits, int m, size_t S, const uint32_t* __restrict__ sel,
                                              const uint32_t* __restrict__ tscan, uint8_t* __restrict__ records)
 {
@@ -509,7 +509,7 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
-        z[r] = valid ? X[j] : make_float2(0.f, 0.f);
+        z[r] = valid ? X[spec_index(j, pair_log)] : make_float2(0.f, 0.f);
         const uint32_t key = key_of(z[r]);
         const bool gt = valid && key > tau, eq = valid && key == tau;
         gtbits |= (uint32_t)gt << r;
@@ -670,7 +670,7 @@ __device__ __forceinline__ uint32_t fetch_code(const uint32_t* __restrict__ code
 __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
                                                uint32_t k, int bits, int m, uint32_t Tn,
                                                const uint32_t* __restrict__ gprefix, const uint32_t* __restrict__ sel,
-                                               uint32_t* __restrict__ status, float2* __restrict__ spec, uint32_t sstride)
+                                               uint32_t* __restrict__ status, float2* __restrict__ spec, uint32_t sstride, int pair_log)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t c = blockIdx.x / Tn;
@@ -714,7 +714,7 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
             out.x = __uint_as_float(dequantize(cre, pbase, bits, shift));
             out.y = __uint_as_float(dequantize(cim, pbase, bits, shift));
         }
-        if (j < B) X[j] = out;
+        if (j < B) X[spec_index(j, pair_log)] = out;
         run += (uint32_t)__popcll(mask);
     }
 }
@@ -747,10 +747,10 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
         hipError_t e = launch_zero_hist(ws_base, w, a.C, s);
         if (e != hipSuccess) return e;
         const uint32_t groups = (Tn + HIST_TILES - 1) / HIST_TILES;
-        FFTSP_LAUNCH("hist", k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, a.sstride, B, groups, hist);
+        FFTSP_LAUNCH("hist", k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B, groups, hist);
     }
     FFTSP_LAUNCH("find_bucket", k_find_bucket, dim3((unsigned)a.C), dim3(NT), 0, s, hist, a.k, sel);
-    FFTSP_LAUNCH("collect", k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, B, Tn, sel, tinfo, cand);
+    FFTSP_LAUNCH("collect", k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B, Tn, sel, tinfo, cand);
     HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
                  a.hdr_theta};
     // up to 12 Ki candidates (96 KiB) are staged in LDS by the per-chunk workgroup
@@ -764,7 +764,7 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     }
     FFTSP_LAUNCH("resolve", k_resolve, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k, a.bits, a.m,
                  W, a.S, a.word3, kStageCap, sel, tinfo, tscan, cand, records, stream_base, h);
-    FFTSP_LAUNCH("emit", k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
+    FFTSP_LAUNCH("emit", k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
                        records);
     return hipGetLastError();
 }
@@ -782,7 +782,7 @@ hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, con
     FFTSP_LAUNCH("group_prefix", k_group_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k,
                  a.word3, h, gprefix, sel, status, reset_status);
     FFTSP_LAUNCH("decode", k_decode, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m,
-                 Tn, gprefix, sel, status, reinterpret_cast<float2*>(spec), a.sstride);
+                 Tn, gprefix, sel, status, reinterpret_cast<float2*>(spec), a.sstride, a.pair_log);
     return hipGetLastError();
 }
 

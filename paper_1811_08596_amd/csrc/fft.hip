@@ -422,7 +422,7 @@ __device__ __forceinline__ uint32_t fft_key_of(float2 z)
 template <int LOGN2>
 __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, int logM, float2* __restrict__ spec,
                                                uint32_t sstride, Tables tb, uint32_t* __restrict__ hist,
-                                               uint32_t total, uint32_t per_wg)
+                                               uint32_t total, uint32_t per_wg, int pair_spec)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, ELEMS = 1 << LOGE;
@@ -462,7 +462,9 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
         run_fft<LOGN2, LOGT, NT, false>(d, tw, tid);
         const size_t c = t / tiles;
         float2* out = spec + c * (size_t)sstride;
-        const uint32_t k1 = row_of_pos((t % tiles) * T2 + slot, N1);
+        const uint32_t pos = (t % tiles) * T2 + slot;
+        const uint32_t k1 = row_of_pos(pos, N1);
+        const uint32_t col = pair_spec ? pos : k1;  // where this lane's row sits inside each run of N1 bins
         const bool self = (k1 == 0) || (k1 == N1 / 2);
         const int ps = self ? slot : (slot ^ 1);
         // W_L^(k1 + N1*k2): k2 advances by DK per step, i.e. by exactly kSplitStep 32nds of a turn
@@ -486,7 +488,7 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
                 const float2 b = d[sw_idx<LOGT>(k2p, ps)];
                 x = split_fwd(a, b, cmul(base, make_float2(kW32re[q * kSplitStep], kW32im[q * kSplitStep])));
             }
-            out[k] = x;
+            out[col + ((uint32_t)k2 << logN1)] = x;
             if (hist) {
                 const uint32_t b = fft_key_of(x) >> kKeyShift;
                 atomicAdd(&h16[b >> 1], 1u << ((b & 1u) * 16u));
@@ -513,7 +515,8 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
 // Inverse pass B: undo the split, inverse N2-point FFTs over k2, times conj W_M^(n2 k1).
 template <int LOGN2>
 __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, uint32_t sstride, int logM,
-                                               float2* __restrict__ mid, Tables tb, uint32_t total, uint32_t per_wg)
+                                               float2* __restrict__ mid, Tables tb, uint32_t total, uint32_t per_wg,
+                                               int pair_spec)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, ELEMS = 1 << LOGE;
@@ -535,9 +538,10 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
     auto load_tile = [&](uint32_t tile, int tid) {
         const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
         const float2* X = spec + (size_t)(tile / tiles) * (size_t)sstride;
-        const uint32_t row = row_of_pos((tile % tiles) * T2 + slot, N1);
+        const uint32_t pos = (tile % tiles) * T2 + slot, row = row_of_pos(pos, N1);
+        const uint32_t col = pair_spec ? pos : row;
 #pragma unroll
-        for (int q = 0; q < PER; ++q) r[q] = X[row + ((uint32_t)(kq0 + q * DK) << logN1)];
+        for (int q = 0; q < PER; ++q) r[q] = X[col + ((uint32_t)(kq0 + q * DK) << logN1)];
         if (row == 0 && kq0 == 0) xnyq = X[M];
     };
     load_tile(t, tid0);
@@ -729,7 +733,7 @@ hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tab
 
 template <int LOGN2>
 hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, uint32_t sstride, Tables t, uint32_t* hist,
-                 hipStream_t s)
+                 int pair_spec, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2) + kHistLdsWords * sizeof(uint32_t);
     auto kern = k_fwd_b<LOGN2>;
@@ -738,12 +742,13 @@ hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, uint32_t s
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
     const Grid g = persistent_grid(total);
     FFTSP_LAUNCH("rfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, spec, sstride, t, hist,
-                 (uint32_t)total, g.per_wg);
+                 (uint32_t)total, g.per_wg, pair_spec);
     return hipGetLastError();
 }
 
 template <int LOGN2>
-hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float2* mid, Tables t, hipStream_t s)
+hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float2* mid, Tables t, int pair_spec,
+                 hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2);
     auto kern = k_inv_b<LOGN2>;
@@ -752,7 +757,7 @@ hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
     const Grid g = persistent_grid(total);
     FFTSP_LAUNCH("irfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, spec, sstride, logM, mid, t, (uint32_t)total,
-                 g.per_wg);
+                 g.per_wg, pair_spec);
     return hipGetLastError();
 }
 
@@ -777,9 +782,17 @@ hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Ta
 // hist (optional, u32[C][kHistBins]): receives the 12-bit histogram of the keys' top bits when the two-pass
 // kernels run; they first clear zero_words words at zero_ptr (which must cover hist).  *hist_done = 1 if the
 // FFT filled hist, 0 if the caller still has to clear and fill it (single-workgroup sizes).
-hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, uint32_t sstride, float2* mid,
-                       Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, hipStream_t s)
+int fft_pair_log(int logL)
 {
+    const int logM = logL - 1;
+    return logM >= 14 ? (logM + 1) / 2 : 0;
+}
+
+hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, uint32_t sstride, float2* mid,
+                       Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, int pair_spec,
+                       int* pair_log, hipStream_t s)
+{
+    if (pair_log) *pair_log = 0;
     if (zero_words > 0xffffffffu) return hipErrorInvalidValue;
     if (!hist) zero_words = 0;
     const int logM = logL - 1;
@@ -806,17 +819,18 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     }
     if (e != hipSuccess) return e;
     if (hist_done) *hist_done = hist != nullptr;
+    if (pair_log && pair_spec) *pair_log = logN1;
     switch (logN2) {
-        case 7: return fwd_b<7>(mid, logM, C, sp, sstride, t, hist, s);
-        case 8: return fwd_b<8>(mid, logM, C, sp, sstride, t, hist, s);
-        case 9: return fwd_b<9>(mid, logM, C, sp, sstride, t, hist, s);
-        case 10: return fwd_b<10>(mid, logM, C, sp, sstride, t, hist, s);
+        case 7: return fwd_b<7>(mid, logM, C, sp, sstride, t, hist, pair_spec, s);
+        case 8: return fwd_b<8>(mid, logM, C, sp, sstride, t, hist, pair_spec, s);
+        case 9: return fwd_b<9>(mid, logM, C, sp, sstride, t, hist, pair_spec, s);
+        case 10: return fwd_b<10>(mid, logM, C, sp, sstride, t, hist, pair_spec, s);
         default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
-                        Tables t, hipStream_t s)
+                        Tables t, int pair_spec, hipStream_t s)
 {
     const int logM = logL - 1;
     const int aligned = (reinterpret_cast<uintptr_t>(out) & 7u) == 0;
@@ -832,10 +846,10 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
     const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
     hipError_t e;
     switch (logN2) {
-        case 7: e = inv_b<7>(sp, sstride, logM, C, mid, t, s); break;
-        case 8: e = inv_b<8>(sp, sstride, logM, C, mid, t, s); break;
-        case 9: e = inv_b<9>(sp, sstride, logM, C, mid, t, s); break;
-        case 10: e = inv_b<10>(sp, sstride, logM, C, mid, t, s); break;
+        case 7: e = inv_b<7>(sp, sstride, logM, C, mid, t, pair_spec, s); break;
+        case 8: e = inv_b<8>(sp, sstride, logM, C, mid, t, pair_spec, s); break;
+        case 9: e = inv_b<9>(sp, sstride, logM, C, mid, t, pair_spec, s); break;
+        case 10: e = inv_b<10>(sp, sstride, logM, C, mid, t, pair_spec, s); break;
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;

@@ -65,6 +65,18 @@ static inline Workspace make_workspace(size_t C, uint32_t L)
     return w;
 }
 
+// Where bin j of a chunk sits inside the chunk's spectrum.  pair_log = 0: natural order (the layout of the
+// stage-level entry points).  pair_log = log2(N1) > 0: the two-pass FFT's own "paired" order, in which each run
+// of N1 bins stores bin k1 next to bin N1-k1 (position 2*k1 / 2*k1+1; position 1 holds k1 = N1/2), so that the
+// rows the real-FFT split combines are one 128-byte run for the FFT passes.  Bin L/2 keeps index L/2.
+__device__ __forceinline__ uint32_t spec_index(uint32_t j, int pair_log)
+{
+    if (pair_log == 0) return j;
+    const uint32_t N1 = 1u << pair_log, k1 = j & (N1 - 1u), hi = j - k1;
+    const uint32_t pos = k1 < N1 / 2 ? 2u * k1 : (k1 == N1 / 2 ? 1u : 2u * (N1 - k1) + 1u);
+    return hi + pos;
+}
+
 // Optional per-kernel event timing (prof.hip).
 namespace prof {
 bool enabled();
@@ -91,10 +103,16 @@ hipError_t get_tables(Tables* out);
 // 128-byte line); mid: C*L floats of scratch (unused when L <= 2^14).
 // hist (optional): u32[C][kHistBins]; the two-pass kernels clear zero_words words at zero_ptr (covering hist and
 // the status words) and fill hist, setting *hist_done = 1; otherwise the caller clears and fills it.
+// pair_spec != 0 asks the two-pass kernels to write the spectrum in paired order; *pair_log receives log2(N1)
+// if they did, 0 otherwise (single-workgroup sizes always write natural order).
 hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, uint32_t sstride, float2* mid,
-                       Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, hipStream_t s);
+                       Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, int pair_spec,
+                       int* pair_log, hipStream_t s);
+// log2(N1) of the two-pass factorisation for chunk length 2^logL, 0 for single-workgroup sizes
+int fft_pair_log(int logL);
+// pair_spec != 0: the spectrum is in paired order (two-pass sizes only)
 hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
-                        Tables t, hipStream_t s);
+                        Tables t, int pair_spec, hipStream_t s);
 
 // Codec launchers (codec.hip).
 struct CodecArgs {
@@ -105,6 +123,7 @@ struct CodecArgs {
     size_t S;           // record stride in bytes
     uint32_t word3;     // 4th word of every record header
     uint32_t sstride;   // distance between consecutive chunks' spectra, in complex bins
+    int pair_log;       // 0: spectrum in natural bin order; log2(N1): paired order (see spec_index)
     // stream header (written iff write_header)
     int write_header;
     uint64_t hdr_n;
