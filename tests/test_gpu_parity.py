@@ -197,3 +197,47 @@ def test_segments_match_per_tensor_chunks(dev, ref):
     out, st = dev.decompress_segments(por, offs, theta, bits)
     assert st == 0
     assert rel_l2(out, ref.decompress_segments(por, offs, theta, bits, nthreads=8)) <= TOL
+
+
+@pytest.mark.parametrize("logL", list(range(5, 23)))
+def test_every_chunk_length(dev, ref, logL):
+    """one full chunk plus a ragged tail at every supported chunk length (all FFT kernel instantiations)"""
+    L = 1 << logL
+    n = L + max(3, L // 3 + 1)
+    print(f"chunk length 2^{logL}, n={n}", flush=True)
+    g = workloads.small_mixed(n, seed=logL)
+    spec_or = ref.rfft(g, L, nthreads=8)
+    assert per_chunk_rel_l2(dev.rfft(g, L), spec_or, 2) <= TOL
+    theta, bits = 0.3, 8
+    packed_or = ref.encode_spectrum(spec_or, n, L, theta, bits, nthreads=8)
+    assert np.array_equal(dev.encode(spec_or, n, L, theta, bits), packed_or)
+    out_or = ref.decompress(packed_or, n, L, theta, bits, nthreads=8)
+    out, st = dev.decompress(packed_or, n, L, theta, bits, want_status=True)
+    assert st == 0 and rel_l2(out, out_or) <= TOL
+    a = dev.compress(g, L, theta, bits)
+    explain_end_to_end(ref, a, packed_or, spec_or, n, L, theta, bits)
+
+
+def test_unsupported_and_invalid_arguments_on_device(dev):
+    """argument errors are reported before anything is enqueued, also with real device pointers"""
+    f, torch = dev.f, dev.torch
+    g = dev.empty(1000, torch.float32)
+    ws = dev.workspace(f.workspace_bytes(1000, 256, 8))
+    packed = dev.empty(f.packed_bytes(1000, 256, 0.5, 8), torch.uint8)
+    for kwargs, code in (((dict(L=100),), f.EUNSUPPORTED), ((dict(L=1 << 23),), f.EUNSUPPORTED),
+                         ((dict(theta=1.5),), f.EINVAL), ((dict(bits=2),), f.EINVAL)):
+        kw = dict(L=256, theta=0.5, bits=8)
+        kw.update(kwargs[0])
+        with pytest.raises(f.FftspError) as e:
+            f.compress(g, kw["L"], kw["theta"], kw["bits"], packed, ws)
+        assert e.value.code == code
+    with pytest.raises(f.FftspError) as e:
+        f.compress(g, 256, 0.5, 8, packed[:-16], ws)
+    assert e.value.code == f.ENOSPC
+    with pytest.raises(f.FftspError) as e:
+        f.compress(g, 256, 0.5, 8, packed, ws[:1024])
+    assert e.value.code == f.EWORKSPACE
+    with pytest.raises(f.FftspError) as e:
+        f.compress(g[1:], 256, 0.5, 8, packed, ws)          # 4-byte aligned only
+    assert e.value.code == f.EINVAL
+    dev.sync()
