@@ -39,6 +39,22 @@ __device__ __forceinline__ uint32_t prefix_popc(uint64_t mask)
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// Cooperative load of one tile of the spectrum buffer, [tbase, tbase+count), into LDS as whole 16-byte pieces.
+// A tile is contiguous in the buffer in either bin order (paired runs are tile-aligned), so lanes then pick
+// their own bins from LDS at spec_index(j) - tbase instead of issuing half-dense global loads.
+__device__ __forceinline__ void tile_to_lds(const float2* __restrict__ X, uint32_t tbase, uint32_t count,
+                                            uint32_t sstride, float2* stage, int tid)
+{
+    if (count == (uint32_t)kTile && (sstride & 1u) == 0) {  // chunk base and tile base are 16-byte aligned
+        const float4* src = reinterpret_cast<const float4*>(X + tbase);
+        float4* dst = reinterpret_cast<float4*>(stage);
+#pragma unroll
+        for (int i = 0; i < kTile / 2 / kTileThreads; ++i) dst[tid + i * kTileThreads] = src[tid + i * kTileThreads];
+    } else {
+        for (uint32_t i = tid; i < count; i += kTileThreads) stage[i] = X[tbase + i];
+    }
+}
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v)
 {
 #pragma unroll
@@ -170,12 +186,16 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
                                                 uint2* __restrict__ cand)
 {
     __shared__ uint32_t wcnt[4], wdef[4], wvmax[4];
+    __shared__ float2 stage[kTile];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t c = blockIdx.x / Tn;
     const uint32_t tile = blockIdx.x % Tn;
-    const uint32_t bstar = sel[c * 8 + 0];
     const float2* X = spec + c * (size_t)sstride;
-    const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
+    const uint32_t tbase = tile * kTile;
+    tile_to_lds(X, tbase, B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile, sstride, stage, tid);
+    const uint32_t bstar = sel[c * 8 + 0];
+    __syncthreads();
+    const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
     uint32_t key[ROWS], vb[ROWS];
     uint64_t cm[ROWS];
     uint32_t ndef = 0, vmax = 0, ncand = 0, mine = 0;  // mine: bit r set = this lane's bin of row r is a candidate
@@ -183,7 +203,7 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
-        const float2 z = valid ? X[spec_index(j, pair_log)] : make_float2(0.f, 0.f);
+        const float2 z = valid ? stage[spec_index(j, pair_log) - tbase] : make_float2(0.f, 0.f);
         key[r] = key_of(z);
         vb[r] = vbits_of(z);
         const uint32_t bucket = key[r] >> kKeyShift;
@@ -498,10 +518,15 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     const uint32_t twoN = 2u * (uint32_t)bits;
     const int shift = 23 - m;
     const uint32_t lds_words = (uint32_t)kTile * twoN / 32u + 2u;
-    for (uint32_t i = tid; i < lds_words; i += NT) cw[i] = 0u;
 
+    // the spectrum tile is staged in the LDS words that later hold the packed codes
     const float2* X = spec + c * (size_t)sstride;
-    const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
+    float2* stage = reinterpret_cast<float2*>(cw);
+    static_assert(sizeof(cw) >= kTile * sizeof(float2), "the code buffer doubles as the tile staging area");
+    const uint32_t tbase = tile * kTile;
+    tile_to_lds(X, tbase, B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile, sstride, stage, tid);
+    __syncthreads();
+    const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
     float2 z[ROWS];
     uint64_t em[ROWS], fm[ROWS];
     uint32_t neq = 0, gtbits = 0, eqbits = 0;  // bit r = this lane's bin of row r is above / equal to the threshold
@@ -509,7 +534,7 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
-        z[r] = valid ? X[spec_index(j, pair_log)] : make_float2(0.f, 0.f);
+        z[r] = valid ? stage[spec_index(j, pair_log) - tbase] : make_float2(0.f, 0.f);
         const uint32_t key = key_of(z[r]);
         const bool gt = valid && key > tau, eq = valid && key == tau;
         gtbits |= (uint32_t)gt << r;
@@ -518,7 +543,8 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
         neq += (uint32_t)__popcll(em[r]);
     }
     if (lane == 0) weq[wave] = neq;
-    __syncthreads();  // also orders the zeroing of cw before the writes below
+    __syncthreads();  // every lane has taken its bins out of the staging area
+    for (uint32_t i = tid; i < lds_words; i += NT) cw[i] = 0u;  // ordered before the code writes by the next barrier
     uint32_t eqrun = eq0;
     for (int w = 0; w < wave; ++w) eqrun += weq[w];
     uint32_t nfl = 0, flbits = 0;
@@ -690,7 +716,11 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
     uint32_t run = g < G ? gprefix[c * G + g] : 0u;
     const int shift = 23 - m;
     float2* X = spec + c * (size_t)sstride;
-    const uint32_t j0 = tile * kTile + wave * WAVE_BINS + lane;
+    // The tile's bins occupy one contiguous range of the spectrum buffer in either bin order (paired runs are
+    // tile-aligned), so values are placed in LDS at their in-tile position and written out as whole lines.
+    __shared__ float2 stage[kTile];
+    const uint32_t tbase = tile * kTile;
+    const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t lo = __shfl(myword, 2 * r, 64), hi = __shfl(myword, 2 * r + 1, 64);
@@ -714,8 +744,18 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
             out.x = __uint_as_float(dequantize(cre, pbase, bits, shift));
             out.y = __uint_as_float(dequantize(cim, pbase, bits, shift));
         }
-        if (j < B) X[spec_index(j, pair_log)] = out;
+        if (j < B) stage[spec_index(j, pair_log) - tbase] = out;
         run += (uint32_t)__popcll(mask);
+    }
+    __syncthreads();
+    const uint32_t count = B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile;
+    if (count == (uint32_t)kTile && ((sstride & 1u) == 0)) {
+        float4* dst = reinterpret_cast<float4*>(X + tbase);  // chunk base and tile base are 16-byte aligned
+        const float4* src = reinterpret_cast<const float4*>(stage);
+#pragma unroll
+        for (int i = 0; i < kTile / 2 / NT; ++i) dst[tid + i * NT] = src[tid + i * NT];
+    } else {
+        for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = stage[i];
     }
 }
 

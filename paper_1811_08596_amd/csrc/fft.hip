@@ -707,9 +707,8 @@ hipError_t small_inv(const float2* spec, uint32_t sstride, size_t n, size_t C, f
 struct Grid {
     uint32_t wgs, per_wg;
 };
-Grid persistent_grid(size_t total)
+Grid persistent_grid(size_t total, uint32_t kMaxWgs = 512)  // 512 = 256 compute units x 2 resident workgroups
 {
-    constexpr uint32_t kMaxWgs = 512;  // 256 compute units x 2 resident workgroups
     Grid g;
     g.per_wg = (uint32_t)((total + kMaxWgs - 1) / kMaxWgs);
     g.wgs = (uint32_t)((total + g.per_wg - 1) / g.per_wg);
@@ -755,7 +754,7 @@ hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
-    const Grid g = persistent_grid(total);
+    const Grid g = persistent_grid(total, 256);  // measured: one workgroup per CU with longer tile runs is faster here
     FFTSP_LAUNCH("irfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, spec, sstride, logM, mid, t, (uint32_t)total,
                  g.per_wg, pair_spec);
     return hipGetLastError();
