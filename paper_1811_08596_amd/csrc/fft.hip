@@ -334,82 +334,169 @@ __device__ __forceinline__ uint32_t row_of_pos(uint32_t p, uint32_t N1)
     return (p & 1u) ? (p == 1u ? N1 / 2 : N1 - (p >> 1)) : (p >> 1);
 }
 
-// Forward pass A: N1-point FFTs down the columns of the N1 x N2 view of z, for tiles of TA adjacent columns.
-template <int LOGN1>
-__global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, size_t n, int logM,
-                                               float2* __restrict__ mid, Tables tb, int aligned, uint32_t total,
-                                               uint32_t per_wg, uint32_t* __restrict__ zero_ptr, uint32_t zero_words)
-{
-    constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
-    constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
-    // clears the status words and key histograms the next kernels of the sender accumulate into
-    for (uint32_t i = blockIdx.x * NT + threadIdx.x; i < zero_words; i += gridDim.x * NT) zero_ptr[i] = 0u;
-    constexpr int KN = N1 >= NT ? N1 / NT : 1;   // distinct k1 per lane in the store loop
-    constexpr int DC = N1 >= NT ? 1 : NT / N1;   // column step between a lane's consecutive stores
-    constexpr int NCOL = PER / KN;
-    extern __shared__ float2 smem[];
-    float2* d = smem;
-    float2* tw = smem + ELEMS;
-    const int tid0 = threadIdx.x;
-    const uint32_t M = 1u << logM, N2 = M >> LOGN1, tiles = N2 >> LOGT;
-    uint32_t t = blockIdx.x * per_wg;
-    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
-    if (t >= tend) return;
-    load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
+// Two adjacent slots of one LDS row travel as one 16-byte value: the XOR swizzle keeps an even/odd slot pair
+// adjacent (possibly swapped), so a pair is one 128-bit LDS access plus a conditional swap.
+__device__ __forceinline__ float2 lo2(float4 v) { return make_float2(v.x, v.y); }
+__device__ __forceinline__ float2 hi2(float4 v) { return make_float2(v.z, v.w); }
+__device__ __forceinline__ float4 join(float2 a, float2 b) { return make_float4(a.x, a.y, b.x, b.y); }
 
-    float2 r[PER];
-    auto load_tile = [&](uint32_t tile, int tid) {
+template <int LOGT>
+__device__ __forceinline__ void lds_store2(float2* d, int i, int b2, float4 v)
+{
+    static_assert(LOGT >= 1, "needs at least two slots per row");
+    const int idx = sw_idx<LOGT>(i, b2);  // slot b2 (even); slot b2+1 lives at idx^1
+    *reinterpret_cast<float4*>(d + (idx & ~1)) = (idx & 1) ? make_float4(v.z, v.w, v.x, v.y) : v;
+}
+
+template <int LOGT>
+__device__ __forceinline__ float4 lds_load2(const float2* d, int i, int b2)
+{
+    static_assert(LOGT >= 1, "needs at least two slots per row");
+    const int idx = sw_idx<LOGT>(i, b2);
+    const float4 v = *reinterpret_cast<const float4*>(d + (idx & ~1));
+    return (idx & 1) ? make_float4(v.z, v.w, v.x, v.y) : v;
+}
+
+// Which tile of its chunk work item `tile` is.  Workgroups walk runs of consecutive work items in step, so
+// at any moment the chip would touch only every per_wg-th tile position of each chunk: a few fixed byte offsets
+// of every row, i.e. a fraction of the memory channels.  Rotating the order by the chunk index spreads the
+// offsets in flight over the whole row.  (tiles is a power of two.)
+__device__ __forceinline__ uint32_t tile_in_chunk(uint32_t tile, uint32_t tiles)
+{
+    return (tile + tile / tiles) & (tiles - 1);
+}
+
+// rows held by pair kp of a run of N1 paired positions: (kp, N1-kp), and (0, N1/2) for kp = 0
+__device__ __forceinline__ uint32_t mirror_row(uint32_t kp, uint32_t N1) { return kp ? N1 - kp : N1 / 2; }
+
+// Software pipeline of the persistent two-pass kernels.  Vector-memory results return in issue order and are
+// counted by a single counter, so the order of issue decides what a wait really waits for.  Per tile t:
+//     [table lookups for tile t's store loop, lookups for tile t+1's split, loads of tile t+1]   one batch
+//     LDS FFT of tile t
+//     store loop of tile t
+//     barrier, LDS fill from the registers that hold tile t+1, barrier
+// Every load is older than the stores issued after it, so no wait for a load ever waits for a store to be
+// acknowledged.  The loads of the batch are unconditional (on the last tile they read one valid dummy address),
+// which keeps the code between issue and use free of branches that would make the waits conservative.
+
+// Forward pass A: N1-point FFTs down the columns of the N1 x N2 view of z, for tiles of TA adjacent columns.
+// FAST: every tile of this workgroup's run lies in a chunk that is wholly inside the input, and the input is
+// 16-byte aligned: two columns per 16-byte load, no guards.  Otherwise every element is loaded under a guard
+// (ragged last chunk, unaligned tensors); the two variants are separate loops so that the guarded one does
+// not put branches between the fast one's loads and their use.
+template <int LOGN1, bool FAST>
+__device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n, int logM, float2* __restrict__ mid,
+                                          const Tables& tb, int aligned, uint32_t t, uint32_t tend, float2* d,
+                                          const float2* tw, int tid0)
+{
+    constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
+    constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT;
+    constexpr int HP = N1 / 2, LOGHP = LOGN1 - 1;  // row pairs per column
+    static_assert(LOGT >= 2 && (NT % (TA / 2)) == 0, "tile shape");
+    constexpr int KN = HP >= NT ? HP / NT : 1;   // distinct row pairs per lane in the store loop
+    constexpr int DC = HP >= NT ? 1 : NT / HP;   // column step between a lane's consecutive stores
+    constexpr int NCOL = PER2 / KN;
+    static_assert(NCOL <= 8, "twiddle recurrence is anchored once");
+    const uint32_t M = 1u << logM, N2 = M >> LOGN1, tiles = N2 >> LOGT;
+
+    float4 r[PER2];
+    // live = false: the tile does not exist; the fast loads are still issued, all to one valid address
+    auto load_tile = [&](uint32_t tile, int tid, bool live) {
         const size_t cbase = (size_t)(tile / tiles) * (size_t)(2 * (size_t)M);
-        const uint32_t col0 = (tile % tiles) << LOGT;
-        if (aligned && cbase + 2 * (size_t)M <= n) {  // whole chunk present: no per-element guards
-            const float2* src = reinterpret_cast<const float2*>(in + cbase) + col0;
+        const uint32_t col0 = tile_in_chunk(tile, tiles) << LOGT;
+        if constexpr (FAST) {
+            const float4* src = live ? reinterpret_cast<const float4*>(in + cbase) + (col0 >> 1)
+                                     : reinterpret_cast<const float4*>(tb.hi);
 #pragma unroll
-            for (int q = 0; q < PER; ++q) {
-                const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-                r[q] = src[(uint32_t)n1 * N2 + col];
+            for (int q = 0; q < PER2; ++q) {
+                const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
+                r[q] = src[live ? (uint32_t)n1 * (N2 >> 1) + bp : 0u];
             }
         } else {
+            if (!live) return;
 #pragma unroll
-            for (int q = 0; q < PER; ++q) {
-                const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-                r[q] = load_pair(in, cbase + 2 * ((size_t)n1 * N2 + col0 + col), n, aligned);
+            for (int q = 0; q < PER2; ++q) {
+                const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
+                const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
+                r[q] = join(load_pair(in, gi, n, aligned & 1), load_pair(in, gi + 2, n, aligned & 1));
             }
         }
     };
-    load_tile(t, tid0);
+    auto fill = [&](int tid) {
+#pragma unroll
+        for (int q = 0; q < PER2; ++q) {
+            const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
+            lds_store2<LOGT>(d, n1, 2 * bp, r[q]);
+        }
+    };
+    load_tile(t, tid0, true);
+    fill(tid0);
+    __syncthreads();
     for (;;) {
         const int tid = opaque_lane(tid0);
-#pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-            d[sw_idx<LOGT>(n1, col)] = r[q];
-        }
-        __syncthreads();
-        const bool more = t + 1 < tend;
-        if (more) load_tile(t + 1, tid);
-        run_fft<LOGN1, LOGT, NT, false>(d, tw, tid);
-        float2* out = mid + (size_t)(t / tiles) * (size_t)M;
-        const uint32_t col0 = (t % tiles) << LOGT;
+        const uint32_t col0 = tile_in_chunk(t, tiles) << LOGT;
         const int sh = 22 - logM;
+        float2 ratio_a[KN], ratio_b[KN], cur_a[KN], cur_b[KN];
 #pragma unroll
         for (int kk = 0; kk < KN; ++kk) {
-            const uint32_t pos = (uint32_t)(tid + kk * NT) & (N1 - 1);  // paired position this lane stores to
-            const uint32_t k1 = row_of_pos(pos, N1);
-            const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGN1;
-            const float2 ratio = twiddle(tb, ((uint32_t)DC * k1) << sh);
-            float2 cur = make_float2(1.f, 0.f);
+            const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
+            const uint32_t ka = kp, kb = mirror_row(kp, N1);
+            const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
+            ratio_a[kk] = twiddle(tb, ((uint32_t)DC * ka) << sh);
+            ratio_b[kk] = twiddle(tb, ((uint32_t)DC * kb) << sh);
+            cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
+            cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
+        }
+        const bool more = t + 1 < tend;
+        load_tile(more ? t + 1 : t, tid, more);
+        run_fft<LOGN1, LOGT, NT, false>(d, tw, tid);
+        float4* out = reinterpret_cast<float4*>(mid + (size_t)(t / tiles) * (size_t)M);
+#pragma unroll
+        for (int kk = 0; kk < KN; ++kk) {
+            const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);  // pair of paired positions (2kp, 2kp+1)
+            const uint32_t ka = kp, kb = mirror_row(kp, N1);
+            const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
 #pragma unroll
             for (int j = 0; j < NCOL; ++j) {
                 const uint32_t col = cfirst + j * DC, n2 = col0 + col;
-                if (j % 8 == 0) cur = twiddle(tb, (n2 * k1) << sh);
-                out[n2 * N1 + pos] = cmul(d[sw_idx<LOGT>(k1, col)], cur);
-                cur = cmul(cur, ratio);
+                const float2 va = cmul(d[sw_idx<LOGT>((int)ka, (int)col)], cur_a[kk]);
+                const float2 vb = cmul(d[sw_idx<LOGT>((int)kb, (int)col)], cur_b[kk]);
+                out[n2 * (uint32_t)HP + kp] = join(va, vb);
+                cur_a[kk] = cmul(cur_a[kk], ratio_a[kk]);
+                cur_b[kk] = cmul(cur_b[kk], ratio_b[kk]);
             }
         }
         if (!more) break;
         ++t;
         __syncthreads();
+        fill(tid);
+        __syncthreads();
     }
+}
+
+// `aligned`: bit 0 = input is 8-byte aligned, bit 1 = 16-byte aligned.
+template <int LOGN1>
+__global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, size_t n, int logM,
+                                               float2* __restrict__ mid, Tables tb, int aligned, uint32_t total,
+                                               uint32_t per_wg, uint32_t* __restrict__ zero_ptr, uint32_t zero_words)
+{
+    constexpr int NT = kNT, ELEMS = 1 << kLogE;
+    // clears the status words and key histograms the next kernels of the sender accumulate into
+    for (uint32_t i = blockIdx.x * NT + threadIdx.x; i < zero_words; i += gridDim.x * NT) zero_ptr[i] = 0u;
+    extern __shared__ float2 smem[];
+    float2* d = smem;
+    float2* tw = smem + ELEMS;
+    const int tid0 = threadIdx.x;
+    const uint32_t t = blockIdx.x * per_wg;
+    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
+    if (t >= tend) return;
+    load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
+    const uint32_t tiles = (1u << logM) >> kLogE;  // tiles per chunk
+    const size_t last_chunk_end = ((size_t)((tend - 1) / tiles) + 1) << (logM + 1);
+    if ((aligned & 2) && last_chunk_end <= n)
+        fwd_a_run<LOGN1, true>(in, n, logM, mid, tb, aligned, t, tend, d, tw, tid0);
+    else
+        fwd_a_run<LOGN1, false>(in, n, logM, mid, tb, aligned, t, tend, d, tw, tid0);
 }
 
 __device__ __forceinline__ uint32_t fft_key_of(float2 z)
@@ -419,14 +506,16 @@ __device__ __forceinline__ uint32_t fft_key_of(float2 z)
 
 // Forward pass B: N2-point FFTs along n2 for a tile of rows and their mirrors, then the real-FFT split and,
 // if hist != nullptr, the first radix-select digit of every bin's key (12-bit histogram per chunk).
+// A lane owns one pair of slots (row ka and its mirror kb), i.e. 16 bytes of every run it touches.
 template <int LOGN2>
 __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, int logM, float2* __restrict__ spec,
                                                uint32_t sstride, Tables tb, uint32_t* __restrict__ hist,
                                                uint32_t total, uint32_t per_wg, int pair_spec)
 {
-    constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
-    constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, ELEMS = 1 << LOGE;
-    static_assert(NT % T2 == 0, "a lane keeps one slot");
+    constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
+    constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, ELEMS = 1 << LOGE;
+    constexpr int LOGP = LOGT - 1, P = 1 << LOGP;  // slot pairs per tile
+    static_assert(LOGT >= 1 && NT % P == 0, "a lane keeps one slot pair");
     extern __shared__ float2 smem[];
     float2* d = smem;
     float2* tw = smem + ELEMS;
@@ -440,61 +529,78 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
     load_stage_twiddles<LOGN2, NT>(tw, tb, tid0);
     if (hist)
         for (int i = tid0; i < kHistLdsWords; i += NT) h16[i] = 0u;
-    constexpr int DK = NT >> LOGT;  // k2 step between a lane's consecutive elements
+    constexpr int DK = NT >> LOGP;  // k2 step between a lane's consecutive pairs
+    static_assert(2 * kSplitStep * (PER2 - 1) < 16, "split twiddle steps stay inside the 32nd-root table");
+    // the LDS histogram has 16-bit counters and a tile adds at most 2^13 + 1 keys: flush after at most 7 tiles
+    constexpr uint32_t kFlushEvery = 7;
 
-    float2 r[PER];
-    auto load_tile = [&](uint32_t tile, int tid) {
-        const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
-        const float2* src = mid + (size_t)(tile / tiles) * (size_t)M;
-        const uint32_t pos = (tile % tiles) * T2 + slot;
+    float4 r[PER2];
+    auto load_tile = [&](uint32_t tile, int tid, bool live) {
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        const float4* src = reinterpret_cast<const float4*>(mid + (live ? (size_t)(tile / tiles) * (size_t)M : 0));
+        const uint32_t pp = tile_in_chunk(tile, tiles) * P + p;
 #pragma unroll
-        for (int q = 0; q < PER; ++q) r[q] = src[(uint32_t)(kq0 + q * DK) * N1 + pos];
+        for (int q = 0; q < PER2; ++q) r[q] = src[live ? (uint32_t)(kq0 + q * DK) * (N1 >> 1) + pp : 0u];
     };
-    load_tile(t, tid0);
+    auto fill = [&](int tid) {
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+#pragma unroll
+        for (int q = 0; q < PER2; ++q) lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, r[q]);
+    };
+    auto count = [&](float2 x) {
+        const uint32_t b = fft_key_of(x) >> kKeyShift;
+        atomicAdd(&h16[b >> 1], 1u << ((b & 1u) * 16u));
+    };
+    load_tile(t, tid0, true);
+    fill(tid0);
+    __syncthreads();
+    uint32_t unflushed = 0;
     for (;;) {
         const int tid = opaque_lane(tid0);
-        const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
-#pragma unroll
-        for (int q = 0; q < PER; ++q) d[sw_idx<LOGT>(kq0 + q * DK, slot)] = r[q];
-        __syncthreads();
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        const uint32_t pp = tile_in_chunk(t, tiles) * P + p;
+        const uint32_t ka = pp, kb = mirror_row(pp, N1);
+        const bool self = pp == 0;  // rows 0 and N1/2 are their own mirrors
+        // W_L^(k1 + N1*k2): k2 advances by DK per step, i.e. by exactly 2*kSplitStep 32nds of a turn
+        const float2 base_a = twiddle(tb, (ka + ((uint32_t)kq0 << logN1)) << (21 - logM));
+        const float2 base_b = twiddle(tb, (kb + ((uint32_t)kq0 << logN1)) << (21 - logM));
         const bool more = t + 1 < tend;
-        if (more) load_tile(t + 1, tid);
+        load_tile(more ? t + 1 : t, tid, more);
         run_fft<LOGN2, LOGT, NT, false>(d, tw, tid);
         const size_t c = t / tiles;
         float2* out = spec + c * (size_t)sstride;
-        const uint32_t pos = (t % tiles) * T2 + slot;
-        const uint32_t k1 = row_of_pos(pos, N1);
-        const uint32_t col = pair_spec ? pos : k1;  // where this lane's row sits inside each run of N1 bins
-        const bool self = (k1 == 0) || (k1 == N1 / 2);
-        const int ps = self ? slot : (slot ^ 1);
-        // W_L^(k1 + N1*k2): k2 advances by DK per step, i.e. by exactly kSplitStep 32nds of a turn
-        const float2 base = twiddle(tb, (k1 + ((uint32_t)kq0 << logN1)) << (21 - logM));
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
+        for (int q = 0; q < PER2; ++q) {
             const int k2 = kq0 + q * DK;
-            const uint32_t k = k1 + ((uint32_t)k2 << logN1);
-            const float2 a = d[sw_idx<LOGT>(k2, slot)];
-            float2 x;
-            if (k == 0) {
-                x = make_float2(a.x + a.y, 0.f);
-                const float2 xm = make_float2(a.x - a.y, 0.f);
-                out[M] = xm;
-                if (hist) {
-                    const uint32_t b = fft_key_of(xm) >> kKeyShift;
-                    atomicAdd(&h16[b >> 1], 1u << ((b & 1u) * 16u));
-                }
-            } else {
-                const int k2p = (k1 == 0) ? ((N2 - k2) & (N2 - 1)) : (N2 - 1 - k2);
-                const float2 b = d[sw_idx<LOGT>(k2p, ps)];
-                x = split_fwd(a, b, cmul(base, make_float2(kW32re[q * kSplitStep], kW32im[q * kSplitStep])));
+            const float4 own = lds_load2<LOGT>(d, k2, 2 * p);
+            const float4 pr = lds_load2<LOGT>(d, N2 - 1 - k2, 2 * p);
+            const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
+            float2 pa = hi2(pr), pb = lo2(pr);
+            if (self) {
+                pa = d[sw_idx<LOGT>((N2 - k2) & (N2 - 1), 2 * p)];
+                pb = hi2(pr);
             }
-            out[col + ((uint32_t)k2 << logN1)] = x;
+            float2 xa = split_fwd(lo2(own), pa, cmul(base_a, wq));
+            const float2 xb = split_fwd(hi2(own), pb, cmul(base_b, wq));
+            if (self && k2 == 0) {
+                xa = make_float2(own.x + own.y, 0.f);
+                const float2 xm = make_float2(own.x - own.y, 0.f);
+                out[M] = xm;
+                if (hist) count(xm);
+            }
+            if (pair_spec) {
+                reinterpret_cast<float4*>(out)[((uint32_t)k2 << (logN1 - 1)) + pp] = join(xa, xb);
+            } else {
+                out[ka + ((uint32_t)k2 << logN1)] = xa;
+                out[kb + ((uint32_t)k2 << logN1)] = xb;
+            }
             if (hist) {
-                const uint32_t b = fft_key_of(x) >> kKeyShift;
-                atomicAdd(&h16[b >> 1], 1u << ((b & 1u) * 16u));
+                count(xa);
+                count(xb);
             }
         }
-        if (hist) {  // at most 8193 bins per tile, so the 16-bit halves cannot carry into each other
+        ++unflushed;
+        if (hist && (!more || unflushed == kFlushEvery || (t + 1) / tiles != c)) {
             __syncthreads();
             uint32_t* g = hist + c * kHistBins;
             for (int i = tid; i < kHistLdsWords; i += NT) {
@@ -505,9 +611,12 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
                     h16[i] = 0u;
                 }
             }
+            unflushed = 0;
         }
         if (!more) break;
         ++t;
+        __syncthreads();
+        fill(tid);
         __syncthreads();
     }
 }
@@ -518,9 +627,10 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
                                                float2* __restrict__ mid, Tables tb, uint32_t total, uint32_t per_wg,
                                                int pair_spec)
 {
-    constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
-    constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, T2 = 1 << LOGT, ELEMS = 1 << LOGE;
-    static_assert(NT % T2 == 0, "a lane keeps one slot");
+    constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
+    constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, ELEMS = 1 << LOGE;
+    constexpr int LOGP = LOGT - 1, P = 1 << LOGP;
+    static_assert(LOGT >= 1 && NT % P == 0, "a lane keeps one slot pair");
     extern __shared__ float2 smem[];
     float2* d = smem;
     float2* tw = smem + ELEMS;
@@ -531,79 +641,102 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
     const uint32_t tend = t + per_wg < total ? t + per_wg : total;
     if (t >= tend) return;
     load_stage_twiddles<LOGN2, NT>(tw, tb, tid0);
-    constexpr int DK = NT >> LOGT;
+    constexpr int DK = NT >> LOGP;
+    static_assert(PER2 <= 8, "twiddle recurrence is anchored once");
 
-    float2 r[PER];
-    float2 xnyq = make_float2(0.f, 0.f);
-    auto load_tile = [&](uint32_t tile, int tid) {
-        const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
-        const float2* X = spec + (size_t)(tile / tiles) * (size_t)sstride;
-        const uint32_t pos = (tile % tiles) * T2 + slot, row = row_of_pos(pos, N1);
-        const uint32_t col = pair_spec ? pos : row;
+    float4 r[PER2];
+    float2 xnyq, base_a, base_b;  // Nyquist bin and split twiddles of the tile held in r
+    auto load_tile = [&](uint32_t tile, int tid, bool live) {
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        const float2* X = spec + (live ? (size_t)(tile / tiles) * (size_t)sstride : 0);
+        const uint32_t pp = tile_in_chunk(tile, tiles) * P + p;
+        const uint32_t ka = pp, kb = mirror_row(pp, N1);
+        base_a = twiddle(tb, (ka + ((uint32_t)kq0 << logN1)) << (21 - logM));
+        base_b = twiddle(tb, (kb + ((uint32_t)kq0 << logN1)) << (21 - logM));
+        if (pair_spec) {
+            const float4* X4 = reinterpret_cast<const float4*>(X);
 #pragma unroll
-        for (int q = 0; q < PER; ++q) r[q] = X[col + ((uint32_t)(kq0 + q * DK) << logN1)];
-        if (row == 0 && kq0 == 0) xnyq = X[M];
+            for (int q = 0; q < PER2; ++q) r[q] = X4[live ? ((uint32_t)(kq0 + q * DK) << (logN1 - 1)) + pp : 0u];
+        } else {
+#pragma unroll
+            for (int q = 0; q < PER2; ++q) {
+                const uint32_t o = (uint32_t)(kq0 + q * DK) << logN1;
+                r[q] = join(X[live ? ka + o : 0u], X[live ? kb + o : 0u]);
+            }
+        }
+        xnyq = X[live ? M : 0u];
     };
-    load_tile(t, tid0);
+    auto fill = [&](int tid) {
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+#pragma unroll
+        for (int q = 0; q < PER2; ++q) lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, r[q]);
+    };
+    load_tile(t, tid0, true);
+    fill(tid0);
+    __syncthreads();
     for (;;) {
         const int tid = opaque_lane(tid0);
-        const int slot = tid & (T2 - 1), kq0 = tid >> LOGT;
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        const uint32_t pp = tile_in_chunk(t, tiles) * P + p;
+        const uint32_t ka = pp, kb = mirror_row(pp, N1);
+        const bool self = pp == 0;
+        float4 z[PER2];
 #pragma unroll
-        for (int q = 0; q < PER; ++q) d[sw_idx<LOGT>(kq0 + q * DK, slot)] = r[q];
-        const float2 xm = xnyq;
-        __syncthreads();
-        const uint32_t pos = (t % tiles) * T2 + slot;
-        const uint32_t k1 = row_of_pos(pos, N1);
-        const bool self = (k1 == 0) || (k1 == N1 / 2);
-        const int ps = self ? slot : (slot ^ 1);
-        const float2 base = twiddle(tb, (k1 + ((uint32_t)kq0 << logN1)) << (21 - logM));
-        float2 z[PER];
-#pragma unroll
-        for (int q = 0; q < PER; ++q) {
+        for (int q = 0; q < PER2; ++q) {
             const int k2 = kq0 + q * DK;
-            const uint32_t k = k1 + ((uint32_t)k2 << logN1);
-            float2 a = r[q], b;
-            if (k == 0) {  // imaginary parts of the DC and Nyquist bins are ignored
-                b = xm;
-                a.y = 0.f;
-                b.y = 0.f;
-            } else {
-                const int k2p = (k1 == 0) ? ((N2 - k2) & (N2 - 1)) : (N2 - 1 - k2);
-                b = d[sw_idx<LOGT>(k2p, ps)];
+            const float4 pr = lds_load2<LOGT>(d, N2 - 1 - k2, 2 * p);
+            const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
+            float2 a0 = lo2(r[q]), pa = hi2(pr), pb = lo2(pr);
+            if (self) {
+                pa = d[sw_idx<LOGT>((N2 - k2) & (N2 - 1), 2 * p)];
+                pb = hi2(pr);
+                if (k2 == 0) {  // imaginary parts of the DC and Nyquist bins are ignored
+                    pa = make_float2(xnyq.x, 0.f);
+                    a0.y = 0.f;
+                }
             }
-            z[q] = split_inv(a, b, cmul(base, make_float2(kW32re[q * kSplitStep], kW32im[q * kSplitStep])));
+            z[q] = join(split_inv(a0, pa, cmul(base_a, wq)), split_inv(hi2(r[q]), pb, cmul(base_b, wq)));
         }
         __syncthreads();
 #pragma unroll
-        for (int q = 0; q < PER; ++q) d[sw_idx<LOGT>(kq0 + q * DK, slot)] = z[q];
+        for (int q = 0; q < PER2; ++q) lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, z[q]);
         __syncthreads();
-        const bool more = t + 1 < tend;
-        if (more) load_tile(t + 1, tid);
-        run_fft<LOGN2, LOGT, NT, true>(d, tw, tid);
-        float2* dst = mid + (size_t)(t / tiles) * (size_t)M;
+        // store-loop twiddles of this tile, then split twiddles and data of the next one
         const int sh = 22 - logM;
-        const float2 ratio = twiddle(tb, ((uint32_t)DK * k1) << sh);
-        float2 cur = make_float2(1.f, 0.f);
+        const float2 ratio_a = twiddle(tb, ((uint32_t)DK * ka) << sh);
+        const float2 ratio_b = twiddle(tb, ((uint32_t)DK * kb) << sh);
+        float2 cur_a = twiddle(tb, ((uint32_t)kq0 * ka) << sh);
+        float2 cur_b = twiddle(tb, ((uint32_t)kq0 * kb) << sh);
+        const bool more = t + 1 < tend;
+        load_tile(more ? t + 1 : t, tid, more);
+        run_fft<LOGN2, LOGT, NT, true>(d, tw, tid);
+        float4* dst = reinterpret_cast<float4*>(mid + (size_t)(t / tiles) * (size_t)M);
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
+        for (int q = 0; q < PER2; ++q) {
             const uint32_t n2 = (uint32_t)(kq0 + q * DK);
-            if (q % 8 == 0) cur = twiddle(tb, (n2 * k1) << sh);
-            dst[n2 * N1 + pos] = cmulc(d[sw_idx<LOGT>((int)n2, slot)], cur);
-            cur = cmul(cur, ratio);
+            const float4 v = lds_load2<LOGT>(d, (int)n2, 2 * p);
+            dst[n2 * (N1 >> 1) + pp] = join(cmulc(lo2(v), cur_a), cmulc(hi2(v), cur_b));
+            cur_a = cmul(cur_a, ratio_a);
+            cur_b = cmul(cur_b, ratio_b);
         }
         if (!more) break;
         ++t;
+        __syncthreads();
+        fill(tid);
         __syncthreads();
     }
 }
 
 // Inverse pass A: inverse N1-point FFTs over k1 for a tile of columns n2; writes the real samples.
+// `aligned`: bit 0 = output is 8-byte aligned, bit 1 = 16-byte aligned.
 template <int LOGN1>
 __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, int logM, float* __restrict__ out,
                                                size_t n, Tables tb, int aligned, uint32_t total, uint32_t per_wg)
 {
-    constexpr int NT = kNT, LOGE = kLogE, PER = kPer;
+    constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
+    constexpr int HP = N1 / 2, LOGHP = LOGN1 - 1;
+    static_assert(LOGT >= 2 && (NT % (TA / 2)) == 0, "tile shape");
     extern __shared__ float2 smem[];
     float2* d = smem;
     float2* tw = smem + ELEMS;
@@ -614,50 +747,57 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
     if (t >= tend) return;
     load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
 
-    float2 r[PER];
-    auto load_tile = [&](uint32_t tile, int tid) {
-        const float2* src = mid + (size_t)(tile / tiles) * (size_t)M;
-        const uint32_t col0 = (tile % tiles) << LOGT;
+    float4 r[PER2];
+    auto load_tile = [&](uint32_t tile, int tid, bool live) {
+        const float4* src = reinterpret_cast<const float4*>(mid + (live ? (size_t)(tile / tiles) * (size_t)M : 0));
+        const uint32_t col0 = tile_in_chunk(tile, tiles) << LOGT;
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int w = tid + q * NT, pos = w & (N1 - 1), col = w >> LOGN1;
-            r[q] = src[(uint32_t)(col0 + col) * N1 + pos];
+        for (int q = 0; q < PER2; ++q) {
+            const int w = tid + q * NT, kp = w & (HP - 1), col = w >> LOGHP;
+            r[q] = src[live ? (uint32_t)(col0 + col) * HP + kp : 0u];
         }
     };
-    load_tile(t, tid0);
+    auto fill = [&](int tid) {
+#pragma unroll
+        for (int q = 0; q < PER2; ++q) {
+            const int w = tid + q * NT, kp = w & (HP - 1), col = w >> LOGHP;
+            d[sw_idx<LOGT>(kp, col)] = lo2(r[q]);
+            d[sw_idx<LOGT>((int)mirror_row((uint32_t)kp, N1), col)] = hi2(r[q]);
+        }
+    };
+    load_tile(t, tid0, true);
+    fill(tid0);
+    __syncthreads();
     const float scale = 1.0f / (float)(2u * M);
     for (;;) {
         const int tid = opaque_lane(tid0);
-#pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int w = tid + q * NT, col = w >> LOGN1;
-            d[sw_idx<LOGT>((int)row_of_pos((uint32_t)w & (N1 - 1), N1), col)] = r[q];
-        }
-        __syncthreads();
         const bool more = t + 1 < tend;
-        if (more) load_tile(t + 1, tid);
+        load_tile(more ? t + 1 : t, tid, more);
         run_fft<LOGN1, LOGT, NT, true>(d, tw, tid);
         const size_t cbase = (size_t)(t / tiles) * (size_t)(2 * (size_t)M);
-        const uint32_t col0 = (t % tiles) << LOGT;
-        if (aligned && cbase + 2 * (size_t)M <= n) {  // whole chunk inside the output: no per-element guards
-            float2* dst = reinterpret_cast<float2*>(out + cbase) + col0;
+        const uint32_t col0 = tile_in_chunk(t, tiles) << LOGT;
+        if ((aligned & 2) && cbase + 2 * (size_t)M <= n) {  // whole chunk inside the output: no per-element guards
+            float4* dst = reinterpret_cast<float4*>(out + cbase) + (col0 >> 1);
 #pragma unroll
-            for (int q = 0; q < PER; ++q) {
-                const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-                const float2 v = d[sw_idx<LOGT>(n1, col)];
-                dst[(uint32_t)n1 * N2 + col] = make_float2(v.x * scale, v.y * scale);
+            for (int q = 0; q < PER2; ++q) {
+                const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
+                const float4 v = lds_load2<LOGT>(d, n1, 2 * bp);
+                dst[(uint32_t)n1 * (N2 >> 1) + bp] = make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
             }
         } else {
 #pragma unroll
-            for (int q = 0; q < PER; ++q) {
-                const int w = tid + q * NT, col = w & (TA - 1), n1 = w >> LOGT;
-                const float2 v = d[sw_idx<LOGT>(n1, col)];
-                store_pair(out, cbase + 2 * ((size_t)n1 * N2 + col0 + col), n, aligned,
-                           make_float2(v.x * scale, v.y * scale));
+            for (int q = 0; q < PER2; ++q) {
+                const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
+                const float4 v = lds_load2<LOGT>(d, n1, 2 * bp);
+                const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
+                store_pair(out, gi, n, aligned & 1, make_float2(v.x * scale, v.y * scale));
+                store_pair(out, gi + 2, n, aligned & 1, make_float2(v.z * scale, v.w * scale));
             }
         }
         if (!more) break;
         ++t;
+        __syncthreads();
+        fill(tid);
         __syncthreads();
     }
 }
@@ -754,7 +894,7 @@ hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
-    const Grid g = persistent_grid(total, 256);  // measured: one workgroup per CU with longer tile runs is faster here
+    const Grid g = persistent_grid(total);
     FFTSP_LAUNCH("irfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, spec, sstride, logM, mid, t, (uint32_t)total,
                  g.per_wg, pair_spec);
     return hipGetLastError();
@@ -795,13 +935,14 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     if (zero_words > 0xffffffffu) return hipErrorInvalidValue;
     if (!hist) zero_words = 0;
     const int logM = logL - 1;
-    const int aligned = (reinterpret_cast<uintptr_t>(in) & 7u) == 0;
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(in);
+    const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
     float2* sp = reinterpret_cast<float2*>(spec);
     if (hist_done) *hist_done = 0;
     if (C * ((size_t)1 << (logM > 13 ? logM - 13 : 0)) > 0x7fffffffu) return hipErrorInvalidValue;
     switch (logM) {
 #define X(p) \
-    case p: return small_fwd<p>(in, n, C, sp, sstride, t, aligned, s);
+    case p: return small_fwd<p>(in, n, C, sp, sstride, t, aligned & 1, s);
         FFTSP_SMALL_CASES(X)
 #undef X
         default: break;
@@ -832,12 +973,13 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
                         Tables t, int pair_spec, hipStream_t s)
 {
     const int logM = logL - 1;
-    const int aligned = (reinterpret_cast<uintptr_t>(out) & 7u) == 0;
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(out);
+    const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
     const float2* sp = reinterpret_cast<const float2*>(spec);
     if (C * ((size_t)1 << (logM > 13 ? logM - 13 : 0)) > 0x7fffffffu) return hipErrorInvalidValue;
     switch (logM) {
 #define X(p) \
-    case p: return small_inv<p>(sp, sstride, n, C, out, t, aligned, s);
+    case p: return small_inv<p>(sp, sstride, n, C, out, t, aligned & 1, s);
         FFTSP_SMALL_CASES(X)
 #undef X
         default: break;
