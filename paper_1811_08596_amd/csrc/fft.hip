@@ -360,10 +360,28 @@ __device__ __forceinline__ float4 lds_load2(const float2* d, int i, int b2)
 // Which tile of its chunk work item `tile` is.  Workgroups walk runs of consecutive work items in step, so
 // at any moment the chip would touch only every per_wg-th tile position of each chunk: a few fixed byte offsets
 // of every row, i.e. a fraction of the memory channels.  Rotating the order by the chunk index spreads the
-// offsets in flight over the whole row.  (tiles is a power of two.)
+// offsets in flight over the whole row; the rotation is a multiple of 4, so aligned groups of up to 4 tiles stay together.
+// (tiles is a power of two.)
 __device__ __forceinline__ uint32_t tile_in_chunk(uint32_t tile, uint32_t tiles)
 {
-    return (tile + tile / tiles) & (tiles - 1);
+    return (tile + 4 * (tile / tiles)) & (tiles - 1);
+}
+
+// Tile run of a pass-A workgroup.  A pass-A tile is 64 bytes of every row it touches, half a 128-byte line;
+// tiles 2m and 2m+1 share their lines.  Workgroups are dealt to the 8 XCDs round-robin by index, so workgroups
+// b, b+8, ... share an L2: 2^glog of them walk the members of the same run of aligned tile groups in step, and
+// each line crosses the fabric once.  The workgroup's tiles are t, t+2^glog, ... < tend.  Returns false if this
+// workgroup has nothing to do.
+__device__ __forceinline__ bool grouped_run(uint32_t groups, uint32_t per_wg, int glog, uint32_t& t, uint32_t& tend)
+{
+    const uint32_t b = blockIdx.x, x = b & 7u, y = b >> 3, h = y & ((1u << glog) - 1u);
+    const uint32_t rho = ((y >> glog) << 3) + x;  // which group of workgroups
+    const uint32_t p0 = rho * per_wg;
+    if (p0 >= groups) return false;
+    const uint32_t p1 = p0 + per_wg < groups ? p0 + per_wg : groups;
+    t = (p0 << glog) + h;
+    tend = p1 << glog;
+    return true;
 }
 
 // rows held by pair kp of a run of N1 paired positions: (kp, N1-kp), and (0, N1/2) for kp = 0
@@ -386,7 +404,7 @@ __device__ __forceinline__ uint32_t mirror_row(uint32_t kp, uint32_t N1) { retur
 // not put branches between the fast one's loads and their use.
 template <int LOGN1, bool FAST>
 __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n, int logM, float2* __restrict__ mid,
-                                          const Tables& tb, int aligned, uint32_t t, uint32_t tend, float2* d,
+                                          const Tables& tb, int aligned, uint32_t t, uint32_t tend, uint32_t tstep, float2* d,
                                           const float2* tw, int tid0)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
@@ -447,8 +465,8 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
             cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
             cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
         }
-        const bool more = t + 1 < tend;
-        load_tile(more ? t + 1 : t, tid, more);
+        const bool more = t + tstep < tend;
+        load_tile(more ? t + tstep : t, tid, more);
         run_fft<LOGN1, LOGT, NT, false>(d, tw, tid);
         float4* out = reinterpret_cast<float4*>(mid + (size_t)(t / tiles) * (size_t)M);
 #pragma unroll
@@ -467,7 +485,7 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
             }
         }
         if (!more) break;
-        ++t;
+        t += tstep;
         __syncthreads();
         fill(tid);
         __syncthreads();
@@ -478,7 +496,7 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
 template <int LOGN1>
 __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, size_t n, int logM,
                                                float2* __restrict__ mid, Tables tb, int aligned, uint32_t total,
-                                               uint32_t per_wg, uint32_t* __restrict__ zero_ptr, uint32_t zero_words)
+                                               uint32_t per_wg, int glog, uint32_t* __restrict__ zero_ptr, uint32_t zero_words)
 {
     constexpr int NT = kNT, ELEMS = 1 << kLogE;
     // clears the status words and key histograms the next kernels of the sender accumulate into
@@ -487,16 +505,15 @@ __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, siz
     float2* d = smem;
     float2* tw = smem + ELEMS;
     const int tid0 = threadIdx.x;
-    const uint32_t t = blockIdx.x * per_wg;
-    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
-    if (t >= tend) return;
+    uint32_t t, tend;
+    if (!grouped_run(total, per_wg, glog, t, tend)) return;
     load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
     const uint32_t tiles = (1u << logM) >> kLogE;  // tiles per chunk
     const size_t last_chunk_end = ((size_t)((tend - 1) / tiles) + 1) << (logM + 1);
     if ((aligned & 2) && last_chunk_end <= n)
-        fwd_a_run<LOGN1, true>(in, n, logM, mid, tb, aligned, t, tend, d, tw, tid0);
+        fwd_a_run<LOGN1, true>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0);
     else
-        fwd_a_run<LOGN1, false>(in, n, logM, mid, tb, aligned, t, tend, d, tw, tid0);
+        fwd_a_run<LOGN1, false>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0);
 }
 
 __device__ __forceinline__ uint32_t fft_key_of(float2 z)
@@ -731,7 +748,7 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
 // `aligned`: bit 0 = output is 8-byte aligned, bit 1 = 16-byte aligned.
 template <int LOGN1>
 __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, int logM, float* __restrict__ out,
-                                               size_t n, Tables tb, int aligned, uint32_t total, uint32_t per_wg)
+                                               size_t n, Tables tb, int aligned, uint32_t total, uint32_t per_wg, int glog)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
@@ -742,9 +759,9 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
     float2* tw = smem + ELEMS;
     const int tid0 = threadIdx.x;
     const uint32_t M = 1u << logM, N2 = M >> LOGN1, tiles = N2 >> LOGT;
-    uint32_t t = blockIdx.x * per_wg;
-    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
-    if (t >= tend) return;
+    uint32_t t, tend;
+    if (!grouped_run(total, per_wg, glog, t, tend)) return;
+    const uint32_t tstep = 1u << glog;
     load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
 
     float4 r[PER2];
@@ -771,8 +788,8 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
     const float scale = 1.0f / (float)(2u * M);
     for (;;) {
         const int tid = opaque_lane(tid0);
-        const bool more = t + 1 < tend;
-        load_tile(more ? t + 1 : t, tid, more);
+        const bool more = t + tstep < tend;
+        load_tile(more ? t + tstep : t, tid, more);
         run_fft<LOGN1, LOGT, NT, true>(d, tw, tid);
         const size_t cbase = (size_t)(t / tiles) * (size_t)(2 * (size_t)M);
         const uint32_t col0 = tile_in_chunk(t, tiles) << LOGT;
@@ -795,7 +812,7 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
             }
         }
         if (!more) break;
-        ++t;
+        t += tstep;
         __syncthreads();
         fill(tid);
         __syncthreads();
@@ -855,6 +872,20 @@ Grid persistent_grid(size_t total, uint32_t kMaxWgs = 512)  // 512 = 256 compute
     return g;
 }
 
+// pass A: 2^glog workgroups (b, b+8, ...) share a run of aligned tile groups; per_wg counts tile groups and wgs
+// is a multiple of 8 * 2^glog
+constexpr int kGroupLog = 1;
+Grid grouped_grid(size_t groups, int glog, uint32_t kMaxWgs = 512)
+{
+    Grid g;
+    const uint32_t wg_groups = kMaxWgs >> glog;
+    g.per_wg = (uint32_t)((groups + wg_groups - 1) / wg_groups);
+    const uint32_t used = (uint32_t)((groups + g.per_wg - 1) / g.per_wg);
+    const uint32_t unit = 8u << glog;
+    g.wgs = (((used << glog) + unit - 1) / unit) * unit;
+    return g;
+}
+
 template <int LOGN1>
 hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tables t, int aligned, uint32_t* zero_ptr,
                  uint32_t zero_words, hipStream_t s)
@@ -864,9 +895,10 @@ hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tab
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
-    const Grid g = persistent_grid(total);
-    FFTSP_LAUNCH("rfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, in, n, logM, mid, t, aligned, (uint32_t)total,
-                 g.per_wg, zero_ptr, zero_words);
+    const int glog = logM - kLogE >= kGroupLog ? kGroupLog : 1;  // a chunk has 2^(logM-kLogE) >= 2 tiles
+    const Grid g = grouped_grid(total >> glog, glog);
+    FFTSP_LAUNCH("rfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, in, n, logM, mid, t, aligned,
+                 (uint32_t)(total >> glog), g.per_wg, glog, zero_ptr, zero_words);
     return hipGetLastError();
 }
 
@@ -908,9 +940,10 @@ hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Ta
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
-    const Grid g = persistent_grid(total);
-    FFTSP_LAUNCH("irfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, out, n, t, aligned, (uint32_t)total,
-                 g.per_wg);
+    const int glog = logM - kLogE >= kGroupLog ? kGroupLog : 1;
+    const Grid g = grouped_grid(total >> glog, glog);
+    FFTSP_LAUNCH("irfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, out, n, t, aligned,
+                 (uint32_t)(total >> glog), g.per_wg, glog);
     return hipGetLastError();
 }
 
