@@ -36,7 +36,7 @@ def kernel_algorithmic_bytes(name: str, n: int, L: int, theta: float, bits: int)
         "hist": spec,
         "collect": spec,
         "emit": spec + payload,
-        "word_prefix": bins / 8.0 + bins / 8.0,
+        "group_prefix": bins / 8.0 + bins / (8.0 * 16),
         "decode": payload + spec,
         "irfft_pass_b": spec + 4.0 * C * L,
         "irfft_pass_a": 4.0 * C * L + 4.0 * n,
