@@ -683,79 +683,168 @@ __global__ __launch_bounds__(RT) void k_group_prefix(const uint8_t* __restrict__
     }
 }
 
-__device__ __forceinline__ uint32_t fetch_code(const uint32_t* __restrict__ codes, uint32_t p, int bits)
-{
-    const uint32_t wi = p >> 5, sh = p & 31u;
-    uint32_t v = codes[wi] >> sh;
-    if (sh + (uint32_t)bits > 32u) v |= codes[wi + 1] << (32u - sh);
-    return bits == 32 ? v : (v & ((1u << bits) - 1u));
-}
+// Persistent decoder.  A workgroup walks tiles of 2048 bins (blockIdx, blockIdx + grid, ...), one wave per
+// group of 16 bitmap words.  The kept bins of a wave's 512 bins have consecutive ranks, so their codes are one
+// contiguous byte range of the record: the wave fetches that range with 16-byte loads into its own LDS window
+// and picks the codes out of LDS by rank (a per-bin gather from global memory costs one memory instruction per
+// row of 64 bins and was measured at a quarter of the kernel's time).  The work on a tile is a chain of two
+// dependent memory round trips (bitmap word and group prefix, then the codes) before anything can be stored, so
+// the kernel is software-pipelined: while tile t is dequantised and stored, the codes of tile t+1 and the bitmap
+// words of tile t+2 are in flight.  All loads are unconditional (clamped to addresses inside the record).
+struct DecHead {
+    uint32_t word, run, pbase;  // this lane's bitmap word (lanes 0..15), kept bins before the wave's group, record pbase
+};
 
-// One workgroup per tile of 2048 bins, one wave per group of 16 bitmap words: ranks from ballots of the
-// bitmap itself, code fetch (consecutive ranks, so consecutive addresses), Nbit_to_32bit, zero elsewhere.
+// NL = 16-byte loads per lane: 1 for codes of up to 8 bits, 2 up to 16, 3 up to 24, 4 up to 32
+typedef uint32_t u32x4 __attribute__((vector_size(16)));  // a plain 16-byte value the compiler keeps in registers
+
+template <int NL>
+struct DecCodes {
+    u32x4 main[NL];
+    u32x4 tail;  // lane 0: the 16 bytes behind the main window (the window starts on a 16-byte boundary <= the first code)
+};
+
+// VEC: the spectrum buffer is the codec's own (chunks padded to 16 bins, 16-byte aligned): whole-line stores, and
+// the one bin a partial tile may write past the chunk's last bin lands in the padding.
+template <int NL, bool VEC>
 __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
-                                               uint32_t k, int bits, int m, uint32_t Tn,
+                                               uint32_t k, int bits, int m, uint32_t Tn, uint32_t total, size_t C,
                                                const uint32_t* __restrict__ gprefix, const uint32_t* __restrict__ sel,
                                                uint32_t* __restrict__ status, float2* __restrict__ spec, uint32_t sstride, int pair_log)
 {
+    constexpr int kWin = NL * 1024 + 32;  // bytes of LDS per wave: main window, tail, slack for the 3-word read
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const size_t c = blockIdx.x / Tn;
-    const uint32_t tile = blockIdx.x % Tn;
-    const uint32_t* rec = reinterpret_cast<const uint32_t*>(records + c * S);
-    const uint32_t pbase = rec[0];
-    const uint32_t* bitmap = rec + 4;
-    const uint32_t* codes = bitmap + W;
-    if (tile == 0 && tid == 0) {
+    // header verdicts of k_group_prefix raise the status word
+    for (size_t c = (size_t)blockIdx.x * NT + tid; c < C; c += (size_t)gridDim.x * NT) {
         const uint32_t verdict = sel[c * 8 + 7];
         if (verdict) atomicMax(status, verdict);
     }
     const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
-    const uint32_t g = tile * (kTile / 32 / GROUP_WORDS) + wave;
-    uint32_t myword = 0;
-    if (lane < GROUP_WORDS && g * GROUP_WORDS + lane < W) myword = bitmap[g * GROUP_WORDS + lane];
-    uint32_t run = g < G ? gprefix[c * G + g] : 0u;
     const int shift = 23 - m;
-    float2* X = spec + c * (size_t)sstride;
-    // The tile's bins occupy one contiguous range of the spectrum buffer in either bin order (paired runs are
-    // tile-aligned), so values are placed in LDS at their in-tile position and written out as whole lines.
+    const uint32_t code_base = 16u + 4u * W;  // byte offset of the codes inside a record
     __shared__ float2 stage[kTile];
-    const uint32_t tbase = tile * kTile;
-    const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) {
-        const uint32_t lo = __shfl(myword, 2 * r, 64), hi = __shfl(myword, 2 * r + 1, 64);
+    __shared__ __attribute__((aligned(16))) uint8_t cwin_all[4 * kWin];
+    uint8_t* cwin = cwin_all + wave * kWin;
+
+    auto record_of = [&](uint32_t t) __attribute__((always_inline)) { return records + (size_t)(t / Tn) * S; };
+    auto load_head = [&](uint32_t t, bool live) __attribute__((always_inline)) {
+        if (!live) t = 0;
+        const uint32_t* rec = reinterpret_cast<const uint32_t*>(record_of(t));
+        const uint32_t g = (t % Tn) * (kTile / 32 / GROUP_WORDS) + wave;
+        const uint32_t wi = g * GROUP_WORDS + lane;
+        const bool has = live && lane < GROUP_WORDS && wi < W;
+        DecHead h;
+        h.word = rec[4 + (has ? wi : 0u)];
+        h.run = gprefix[(size_t)(t / Tn) * G + (g < G ? g : 0u)];
+        h.pbase = rec[0];
+        if (!has) h.word = 0u;
+        return h;
+    };
+    // rank of this lane's bin in row r if its bit is set; advances run past the row
+    auto row_rank = [&](const DecHead& h, int r, uint32_t& run, bool& set) __attribute__((always_inline)) {
+        const uint32_t lo = __shfl(h.word, 2 * r, 64), hi = __shfl(h.word, 2 * r + 1, 64);
         const uint64_t mask = (uint64_t)lo | ((uint64_t)hi << 32);
-        const uint32_t j = j0 + r * 64;
-        float2 out = make_float2(0.f, 0.f);
         const uint32_t half = lane < 32 ? lo : hi;
-        if (((half >> (lane & 31)) & 1u) && k > 0) {
-            uint32_t rank = run + prefix_popc(mask);
-            rank = rank < k ? rank : k - 1u;  // a corrupt bitmap must not read outside the record
-            uint32_t cre, cim;
-            if (bits == 8) {
-                const uint32_t v = reinterpret_cast<const uint16_t*>(codes)[rank];
-                cre = v & 0xFFu;
-                cim = v >> 8;
-            } else {
-                const uint32_t p = 2u * (uint32_t)bits * rank;
-                cre = fetch_code(codes, p, bits);
-                cim = fetch_code(codes, p + (uint32_t)bits, bits);
-            }
-            out.x = __uint_as_float(dequantize(cre, pbase, bits, shift));
-            out.y = __uint_as_float(dequantize(cim, pbase, bits, shift));
-        }
-        if (j < B) stage[spec_index(j, pair_log) - tbase] = out;
+        set = ((half >> (lane & 31)) & 1u) && k > 0;
+        uint32_t rank = run + prefix_popc(mask);
         run += (uint32_t)__popcll(mask);
-    }
-    __syncthreads();
-    const uint32_t count = B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile;
-    if (count == (uint32_t)kTile && ((sstride & 1u) == 0)) {
-        float4* dst = reinterpret_cast<float4*>(X + tbase);  // chunk base and tile base are 16-byte aligned
-        const float4* src = reinterpret_cast<const float4*>(stage);
+        return rank < k ? rank : (k ? k - 1u : 0u);  // a corrupt bitmap must not point outside the record
+    };
+    // first byte of the wave's LDS window inside the record: the 16-byte boundary at or below its first code
+    auto window_start = [&](const DecHead& h) __attribute__((always_inline)) {
+        const uint32_t first = h.run < k ? h.run : (k ? k - 1u : 0u);
+        return (code_base + ((2u * (uint32_t)bits * first) >> 3)) & ~15u;
+    };
+    auto load_codes = [&](uint32_t t, bool live, const DecHead& h, DecCodes<NL>& cd) __attribute__((always_inline)) {
+        if (!live) t = 0;
+        const uint8_t* rec = record_of(t);
+        const uint32_t start = window_start(h), last = (uint32_t)S - 16u;  // S is a multiple of 16, at least 32
 #pragma unroll
-        for (int i = 0; i < kTile / 2 / NT; ++i) dst[tid + i * NT] = src[tid + i * NT];
-    } else {
-        for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = stage[i];
+        for (int i = 0; i < NL; ++i) {
+            const uint32_t off = start + (uint32_t)(i * 1024 + lane * 16);
+            cd.main[i] = *reinterpret_cast<const u32x4*>(rec + (off < last ? off : last));
+        }
+        const uint32_t off = start + (uint32_t)(NL * 1024);
+        cd.tail = *reinterpret_cast<const u32x4*>(rec + (off < last ? off : last));
+    };
+    auto finish = [&](uint32_t t, const DecHead& h, const DecCodes<NL>& cd) __attribute__((always_inline)) {
+        const uint32_t tile = t % Tn, tbase = tile * kTile;
+        const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) *reinterpret_cast<u32x4*>(cwin + i * 1024 + lane * 16) = cd.main[i];
+        if (lane == 0) *reinterpret_cast<u32x4*>(cwin + NL * 1024) = cd.tail;
+        __syncthreads();  // codes visible to the wave; the previous tile's stage has been read by everyone
+        const uint32_t start = window_start(h);
+        uint32_t run = h.run;
+        // The tile's bins occupy one contiguous range of the spectrum buffer in either bin order (paired runs are
+        // tile-aligned), so values are placed in LDS at their in-tile position and written out as whole lines.
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            bool set;
+            const uint32_t rank = row_rank(h, r, run, set);
+            float2 out = make_float2(0.f, 0.f);
+            if (set) {
+                const uint32_t p = 2u * (uint32_t)bits * rank;                // bit offset of the pair in the codes
+                uint32_t cre, cim;
+                if (bits == 8) {
+                    const uint32_t v = *reinterpret_cast<const uint16_t*>(cwin + (code_base + (p >> 3) - start));
+                    cre = v & 0xFFu;
+                    cim = v >> 8;
+                } else {
+                    const uint32_t* w = reinterpret_cast<const uint32_t*>(cwin + (code_base + 4u * (p >> 5) - start));
+                    const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
+                    const uint32_t sh = p & 31u, q = sh + (uint32_t)bits;
+                    const uint64_t w01 = (uint64_t)w0 | ((uint64_t)w1 << 32), w12 = (uint64_t)w1 | ((uint64_t)w2 << 32);
+                    const uint32_t keep = bits == 32 ? 0xFFFFFFFFu : ((1u << bits) - 1u);
+                    cre = (uint32_t)(w01 >> sh) & keep;
+                    cim = (uint32_t)((q >= 32u ? w12 : w01) >> (q & 31u)) & keep;
+                }
+                out.x = __uint_as_float(dequantize(cre, h.pbase, bits, shift));
+                out.y = __uint_as_float(dequantize(cim, h.pbase, bits, shift));
+            }
+            const uint32_t j = j0 + r * 64;
+            if (j < B) stage[spec_index(j, pair_log) - tbase] = out;
+        }
+        __syncthreads();
+        float2* X = spec + (size_t)(t / Tn) * (size_t)sstride;
+        const uint32_t count = B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile;
+        if constexpr (VEC) {
+            float4* dst = reinterpret_cast<float4*>(X + tbase);
+            const float4* src = reinterpret_cast<const float4*>(stage);
+#pragma unroll
+            for (int i = 0; i < kTile / 2 / NT; ++i) {
+                const uint32_t idx = (uint32_t)(tid + i * NT);
+                if (2u * idx < count) dst[idx] = src[idx];
+            }
+        } else {
+            for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = stage[i];
+        }
+    };
+
+    // Three register sets rotate by name through a loop body written out three times: rotating by assignment
+    // would copy registers that loads are still filling, and a copy waits for its load.
+    uint32_t t = blockIdx.x;
+    const uint32_t step = gridDim.x;
+    if (t >= total) return;
+    DecHead h0, h1, h2;
+    DecCodes<NL> c0, c1, c2;
+    // tile t is in (hc, cc), tile t+1 in (hn, cn); fetches what tiles t+1 and t+2 need, then finishes tile t
+    auto advance = [&](const DecHead& hc, const DecCodes<NL>& cc, const DecHead& hn, DecCodes<NL>& cn, DecHead& hn2) __attribute__((always_inline)) {
+        const bool more = t + step < total;
+        const bool more2 = more && t + 2 * step < total;
+        hn2 = load_head(more2 ? t + 2 * step : 0u, more2);
+        load_codes(more ? t + step : 0u, more, hn, cn);
+        finish(t, hc, cc);
+        t += step;
+        return more;
+    };
+    h0 = load_head(t, true);
+    h1 = load_head(t + step, t + step < total);
+    load_codes(t, true, h0, c0);
+    for (;;) {
+        if (!advance(h0, c0, h1, c1, h2)) break;
+        if (!advance(h1, c1, h2, c2, h0)) break;
+        if (!advance(h2, c2, h0, c0, h1)) break;
     }
 }
 
@@ -821,8 +910,25 @@ hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, con
                  a.hdr_theta};
     FFTSP_LAUNCH("group_prefix", k_group_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k,
                  a.word3, h, gprefix, sel, status, reset_status);
-    FFTSP_LAUNCH("decode", k_decode, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m,
-                 Tn, gprefix, sel, status, reinterpret_cast<float2*>(spec), a.sstride, a.pair_log);
+    // persistent grid: up to seven or eight workgroups of four waves fit a compute unit
+    const uint32_t total = (uint32_t)(a.C * Tn);
+    const uint32_t grid = total < 2048u ? total : 2048u;
+#define FFTSP_DECODE(NL, VEC)                                                                                         \
+    FFTSP_LAUNCH("decode", (k_decode<NL, VEC>), dim3(grid), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m, Tn, \
+                 total, a.C, gprefix, sel, status, reinterpret_cast<float2*>(spec), a.sstride, a.pair_log)
+    const bool vec = a.sstride == padded_bins(a.L) && (reinterpret_cast<uintptr_t>(spec) & 15u) == 0;
+    const int nl = a.bits <= 8 ? 1 : a.bits <= 16 ? 2 : a.bits <= 24 ? 3 : 4;
+    switch (nl * 2 + (vec ? 1 : 0)) {
+        case 2: FFTSP_DECODE(1, false); break;
+        case 3: FFTSP_DECODE(1, true); break;
+        case 4: FFTSP_DECODE(2, false); break;
+        case 5: FFTSP_DECODE(2, true); break;
+        case 6: FFTSP_DECODE(3, false); break;
+        case 7: FFTSP_DECODE(3, true); break;
+        case 8: FFTSP_DECODE(4, false); break;
+        default: FFTSP_DECODE(4, true); break;
+    }
+#undef FFTSP_DECODE
     return hipGetLastError();
 }
 
