@@ -521,13 +521,16 @@ __device__ __forceinline__ uint32_t fft_key_of(float2 z)
     return __float_as_uint(__fmaf_rn(z.x, z.x, __fmul_rn(z.y, z.y)));
 }
 
-// Forward pass B: N2-point FFTs along n2 for a tile of rows and their mirrors, then the real-FFT split and,
-// if hist != nullptr, the first radix-select digit of every bin's key (12-bit histogram per chunk).
+// Forward pass B: N2-point FFTs along n2 for a tile of rows and their mirrors, then the real-FFT split.
 // A lane owns one pair of slots (row ka and its mirror kb), i.e. 16 bytes of every run it touches.
-template <int LOGN2>
+// CODEC: the spectrum is stored in the paired order and the first radix-select digit of every bin's key is
+// counted into the 12-bit histogram of the chunk (hist); otherwise natural bin order and no histogram.
+// The store loop is free of branches (partner addresses and the rare self-mirrored rows are handled with
+// selects) so that its LDS reads can be issued ahead in batches instead of one wait per read.
+template <int LOGN2, bool CODEC>
 __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, int logM, float2* __restrict__ spec,
                                                uint32_t sstride, Tables tb, uint32_t* __restrict__ hist,
-                                               uint32_t total, uint32_t per_wg, int pair_spec)
+                                               uint32_t total, uint32_t per_wg)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, ELEMS = 1 << LOGE;
@@ -544,12 +547,14 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
     const uint32_t tend = t + per_wg < total ? t + per_wg : total;
     if (t >= tend) return;
     load_stage_twiddles<LOGN2, NT>(tw, tb, tid0);
-    if (hist)
+    if (CODEC)
         for (int i = tid0; i < kHistLdsWords; i += NT) h16[i] = 0u;
     constexpr int DK = NT >> LOGP;  // k2 step between a lane's consecutive pairs
     static_assert(2 * kSplitStep * (PER2 - 1) < 16, "split twiddle steps stay inside the 32nd-root table");
     // the LDS histogram has 16-bit counters and a tile adds at most 2^13 + 1 keys: flush after at most 7 tiles
     constexpr uint32_t kFlushEvery = 7;
+    constexpr int BATCH = 4;  // pairs whose LDS reads are issued together
+    static_assert(PER2 % BATCH == 0, "batches divide the store loop");
 
     float4 r[PER2];
     auto load_tile = [&](uint32_t tile, int tid, bool live) {
@@ -564,9 +569,10 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
 #pragma unroll
         for (int q = 0; q < PER2; ++q) lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, r[q]);
     };
-    auto count = [&](float2 x) {
+    // one key into the 16-bit LDS histogram (bucket b: word b/2, half b%2); on = false adds nothing
+    auto count = [&](float2 x, bool on) {
         const uint32_t b = fft_key_of(x) >> kKeyShift;
-        atomicAdd(&h16[b >> 1], 1u << ((b & 1u) * 16u));
+        atomicAdd(&h16[b >> 1], on ? 1u << ((b & 1u) * 16u) : 0u);
     };
     load_tile(t, tid0, true);
     fill(tid0);
@@ -587,37 +593,47 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
         const size_t c = t / tiles;
         float2* out = spec + c * (size_t)sstride;
 #pragma unroll
-        for (int q = 0; q < PER2; ++q) {
-            const int k2 = kq0 + q * DK;
-            const float4 own = lds_load2<LOGT>(d, k2, 2 * p);
-            const float4 pr = lds_load2<LOGT>(d, N2 - 1 - k2, 2 * p);
-            const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
-            float2 pa = hi2(pr), pb = lo2(pr);
-            if (self) {
-                pa = d[sw_idx<LOGT>((N2 - k2) & (N2 - 1), 2 * p)];
-                pb = hi2(pr);
+        for (int q0 = 0; q0 < PER2; q0 += BATCH) {
+            float2 a0[BATCH], a1[BATCH], pa[BATCH], pb[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int k2 = kq0 + (q0 + u) * DK, k2p = N2 - 1 - k2;
+                // X[ka, k2] pairs with Z[kb, N2-1-k2] and X[kb, k2] with Z[ka, N2-1-k2]; row 0 pairs with itself
+                // at (N2-k2) mod N2 and row N1/2 with itself at N2-1-k2
+                const int ia = self ? sw_idx<LOGT>((N2 - k2) & (N2 - 1), 2 * p) : sw_idx<LOGT>(k2p, 2 * p + 1);
+                const int ib = self ? sw_idx<LOGT>(k2p, 2 * p + 1) : sw_idx<LOGT>(k2p, 2 * p);
+                a0[u] = d[sw_idx<LOGT>(k2, 2 * p)];
+                a1[u] = d[sw_idx<LOGT>(k2, 2 * p + 1)];
+                pa[u] = d[ia];
+                pb[u] = d[ib];
             }
-            float2 xa = split_fwd(lo2(own), pa, cmul(base_a, wq));
-            const float2 xb = split_fwd(hi2(own), pb, cmul(base_b, wq));
-            if (self && k2 == 0) {
-                xa = make_float2(own.x + own.y, 0.f);
-                const float2 xm = make_float2(own.x - own.y, 0.f);
-                out[M] = xm;
-                if (hist) count(xm);
-            }
-            if (pair_spec) {
-                reinterpret_cast<float4*>(out)[((uint32_t)k2 << (logN1 - 1)) + pp] = join(xa, xb);
-            } else {
-                out[ka + ((uint32_t)k2 << logN1)] = xa;
-                out[kb + ((uint32_t)k2 << logN1)] = xb;
-            }
-            if (hist) {
-                count(xa);
-                count(xb);
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int q = q0 + u, k2 = kq0 + q * DK;
+                const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
+                float2 xa = split_fwd(a0[u], pa[u], cmul(base_a, wq));
+                const float2 xb = split_fwd(a1[u], pb[u], cmul(base_b, wq));
+                if (q == 0) {  // k2 = 0 only here: bin 0 and the Nyquist bin come from Z[0] alone
+                    const bool dc = self && kq0 == 0;
+                    const float2 xm = make_float2(a0[u].x - a0[u].y, 0.f);
+                    if (dc) {
+                        xa = make_float2(a0[u].x + a0[u].y, 0.f);
+                        out[M] = xm;
+                    }
+                    if (CODEC) count(xm, dc);
+                }
+                if (CODEC) {
+                    reinterpret_cast<float4*>(out)[((uint32_t)k2 << (logN1 - 1)) + pp] = join(xa, xb);
+                    count(xa, true);
+                    count(xb, true);
+                } else {
+                    out[ka + ((uint32_t)k2 << logN1)] = xa;
+                    out[kb + ((uint32_t)k2 << logN1)] = xb;
+                }
             }
         }
         ++unflushed;
-        if (hist && (!more || unflushed == kFlushEvery || (t + 1) / tiles != c)) {
+        if (CODEC && (!more || unflushed == kFlushEvery || (t + 1) / tiles != c)) {
             __syncthreads();
             uint32_t* g = hist + c * kHistBins;
             for (int i = tid; i < kHistLdsWords; i += NT) {
@@ -639,10 +655,10 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
 }
 
 // Inverse pass B: undo the split, inverse N2-point FFTs over k2, times conj W_M^(n2 k1).
-template <int LOGN2>
+// PAIR: the spectrum is read in the paired order (the codec's own buffer), otherwise in natural bin order.
+template <int LOGN2, bool PAIR>
 __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, uint32_t sstride, int logM,
-                                               float2* __restrict__ mid, Tables tb, uint32_t total, uint32_t per_wg,
-                                               int pair_spec)
+                                               float2* __restrict__ mid, Tables tb, uint32_t total, uint32_t per_wg)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, ELEMS = 1 << LOGE;
@@ -670,7 +686,7 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
         const uint32_t ka = pp, kb = mirror_row(pp, N1);
         base_a = twiddle(tb, (ka + ((uint32_t)kq0 << logN1)) << (21 - logM));
         base_b = twiddle(tb, (kb + ((uint32_t)kq0 << logN1)) << (21 - logM));
-        if (pair_spec) {
+        if (PAIR) {
             const float4* X4 = reinterpret_cast<const float4*>(X);
 #pragma unroll
             for (int q = 0; q < PER2; ++q) r[q] = X4[live ? ((uint32_t)(kq0 + q * DK) << (logN1 - 1)) + pp : 0u];
@@ -697,22 +713,27 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
         const uint32_t pp = tile_in_chunk(t, tiles) * P + p;
         const uint32_t ka = pp, kb = mirror_row(pp, N1);
         const bool self = pp == 0;
+        // partners of all pairs first (one batch of LDS reads), then the arithmetic: no branches in between
+        float2 pa[PER2], pb[PER2];
+#pragma unroll
+        for (int q = 0; q < PER2; ++q) {
+            const int k2 = kq0 + q * DK, k2p = N2 - 1 - k2;
+            const int ia = self ? sw_idx<LOGT>((N2 - k2) & (N2 - 1), 2 * p) : sw_idx<LOGT>(k2p, 2 * p + 1);
+            const int ib = self ? sw_idx<LOGT>(k2p, 2 * p + 1) : sw_idx<LOGT>(k2p, 2 * p);
+            pa[q] = d[ia];
+            pb[q] = d[ib];
+        }
         float4 z[PER2];
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
-            const int k2 = kq0 + q * DK;
-            const float4 pr = lds_load2<LOGT>(d, N2 - 1 - k2, 2 * p);
             const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
-            float2 a0 = lo2(r[q]), pa = hi2(pr), pb = lo2(pr);
-            if (self) {
-                pa = d[sw_idx<LOGT>((N2 - k2) & (N2 - 1), 2 * p)];
-                pb = hi2(pr);
-                if (k2 == 0) {  // imaginary parts of the DC and Nyquist bins are ignored
-                    pa = make_float2(xnyq.x, 0.f);
-                    a0.y = 0.f;
-                }
+            float2 a0 = lo2(r[q]), b0 = pa[q];
+            if (q == 0) {  // k2 = 0 only here; imaginary parts of the DC and Nyquist bins are ignored
+                const bool dc = self && kq0 == 0;
+                b0 = dc ? make_float2(xnyq.x, 0.f) : b0;
+                a0.y = dc ? 0.f : a0.y;
             }
-            z[q] = join(split_inv(a0, pa, cmul(base_a, wq)), split_inv(hi2(r[q]), pb, cmul(base_b, wq)));
+            z[q] = join(split_inv(a0, b0, cmul(base_a, wq)), split_inv(hi2(r[q]), pb[q], cmul(base_b, wq)));
         }
         __syncthreads();
 #pragma unroll
@@ -902,33 +923,32 @@ hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tab
     return hipGetLastError();
 }
 
-template <int LOGN2>
+template <int LOGN2, bool CODEC>
 hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, uint32_t sstride, Tables t, uint32_t* hist,
-                 int pair_spec, hipStream_t s)
+                 hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2) + kHistLdsWords * sizeof(uint32_t);
-    auto kern = k_fwd_b<LOGN2>;
+    auto kern = k_fwd_b<LOGN2, CODEC>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
     const Grid g = persistent_grid(total);
     FFTSP_LAUNCH("rfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, spec, sstride, t, hist,
-                 (uint32_t)total, g.per_wg, pair_spec);
+                 (uint32_t)total, g.per_wg);
     return hipGetLastError();
 }
 
-template <int LOGN2>
-hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float2* mid, Tables t, int pair_spec,
-                 hipStream_t s)
+template <int LOGN2, bool PAIR>
+hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float2* mid, Tables t, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2);
-    auto kern = k_inv_b<LOGN2>;
+    auto kern = k_inv_b<LOGN2, PAIR>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
     const Grid g = persistent_grid(total);
     FFTSP_LAUNCH("irfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, spec, sstride, logM, mid, t, (uint32_t)total,
-                 g.per_wg, pair_spec);
+                 g.per_wg);
     return hipGetLastError();
 }
 
@@ -980,6 +1000,9 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
 #undef X
         default: break;
     }
+    // the codec stores its own spectrum in the paired order and wants the histogram; the stage-level entry point
+    // wants neither
+    if ((hist != nullptr) != (pair_spec != 0)) return hipErrorInvalidValue;
     const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
     hipError_t e;
     switch (logN1) {
@@ -993,11 +1016,20 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     if (e != hipSuccess) return e;
     if (hist_done) *hist_done = hist != nullptr;
     if (pair_log && pair_spec) *pair_log = logN1;
+    if (hist) {
+        switch (logN2) {
+            case 7: return fwd_b<7, true>(mid, logM, C, sp, sstride, t, hist, s);
+            case 8: return fwd_b<8, true>(mid, logM, C, sp, sstride, t, hist, s);
+            case 9: return fwd_b<9, true>(mid, logM, C, sp, sstride, t, hist, s);
+            case 10: return fwd_b<10, true>(mid, logM, C, sp, sstride, t, hist, s);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (logN2) {
-        case 7: return fwd_b<7>(mid, logM, C, sp, sstride, t, hist, pair_spec, s);
-        case 8: return fwd_b<8>(mid, logM, C, sp, sstride, t, hist, pair_spec, s);
-        case 9: return fwd_b<9>(mid, logM, C, sp, sstride, t, hist, pair_spec, s);
-        case 10: return fwd_b<10>(mid, logM, C, sp, sstride, t, hist, pair_spec, s);
+        case 7: return fwd_b<7, false>(mid, logM, C, sp, sstride, t, nullptr, s);
+        case 8: return fwd_b<8, false>(mid, logM, C, sp, sstride, t, nullptr, s);
+        case 9: return fwd_b<9, false>(mid, logM, C, sp, sstride, t, nullptr, s);
+        case 10: return fwd_b<10, false>(mid, logM, C, sp, sstride, t, nullptr, s);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1019,12 +1051,22 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
     }
     const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
     hipError_t e;
-    switch (logN2) {
-        case 7: e = inv_b<7>(sp, sstride, logM, C, mid, t, pair_spec, s); break;
-        case 8: e = inv_b<8>(sp, sstride, logM, C, mid, t, pair_spec, s); break;
-        case 9: e = inv_b<9>(sp, sstride, logM, C, mid, t, pair_spec, s); break;
-        case 10: e = inv_b<10>(sp, sstride, logM, C, mid, t, pair_spec, s); break;
-        default: return hipErrorInvalidValue;
+    if (pair_spec) {
+        switch (logN2) {
+            case 7: e = inv_b<7, true>(sp, sstride, logM, C, mid, t, s); break;
+            case 8: e = inv_b<8, true>(sp, sstride, logM, C, mid, t, s); break;
+            case 9: e = inv_b<9, true>(sp, sstride, logM, C, mid, t, s); break;
+            case 10: e = inv_b<10, true>(sp, sstride, logM, C, mid, t, s); break;
+            default: return hipErrorInvalidValue;
+        }
+    } else {
+        switch (logN2) {
+            case 7: e = inv_b<7, false>(sp, sstride, logM, C, mid, t, s); break;
+            case 8: e = inv_b<8, false>(sp, sstride, logM, C, mid, t, s); break;
+            case 9: e = inv_b<9, false>(sp, sstride, logM, C, mid, t, s); break;
+            case 10: e = inv_b<10, false>(sp, sstride, logM, C, mid, t, s); break;
+            default: return hipErrorInvalidValue;
+        }
     }
     if (e != hipSuccess) return e;
     switch (logN1) {
