@@ -269,6 +269,8 @@ __device__ __forceinline__ uint32_t block_scan_incl_1024(uint32_t v, uint32_t* t
     return x + add;
 }
 
+constexpr int kStageBatch = 6;  // candidates per lane fetched in one go by k_resolve
+
 struct HeaderInfo {
     int write;
     uint64_t n;
@@ -323,14 +325,32 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     const bool staged = s_carry[0] <= stage_cap;
     if (staged) {
         // flat copy with every lane busy: candidate i belongs to the last tile whose offset is <= i
+        // All of a lane's loads are issued before the first is used: one memory round trip, not one per candidate.
         const uint32_t total = s_carry[0];
-        for (uint32_t i = tid; i < total; i += RT) {
-            uint32_t lo = 0, hi = Tn - 1;
-            while (lo < hi) {
-                const uint32_t mid = (lo + hi + 1) >> 1;
-                if (toff[mid] <= i) lo = mid; else hi = mid - 1;
+        for (uint32_t base = 0; base < total; base += kStageBatch * RT) {
+            uint2 v[kStageBatch];
+            uint32_t lo[kStageBatch];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) lo[u] = 0;
+            // the searches of a batch advance together, so their LDS reads overlap
+            for (uint32_t bit = 1024u; bit; bit >>= 1) {  // MAX_TILES <= 2047
+#pragma unroll
+                for (int u = 0; u < kStageBatch; ++u) {
+                    const uint32_t i = base + (uint32_t)u * RT + tid, probe = lo[u] + bit;
+                    if (probe < Tn && toff[probe] <= i) lo[u] = probe;
+                }
             }
-            stage[i] = cd[(size_t)lo * kTile + (i - toff[lo])];
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const uint32_t i = base + (uint32_t)u * RT + tid;
+                // lanes past the end read their tile's first slot (always allocated) and drop it
+                v[u] = cd[(size_t)lo[u] * kTile + (i < total ? i - toff[lo[u]] : 0u)];
+            }
+#pragma unroll
+            for (int u = 0; u < kStageBatch; ++u) {
+                const uint32_t i = base + (uint32_t)u * RT + tid;
+                if (i < total) stage[i] = v[u];
+            }
         }
     }
     __syncthreads();
