@@ -55,6 +55,37 @@ __device__ __forceinline__ void tile_to_lds(const float2* __restrict__ X, uint32
     }
 }
 
+// In-tile slot (position in the spectrum buffer minus the tile base) of this lane's bin in each of the wave's
+// rows (bins j0, j0 + 64, ...).  The 512 bins of a wave lie in one half of one paired run when a run has at least
+// 1024 positions, so the slot is linear in the row and costs one add instead of the whole index computation;
+// shorter runs go through spec_index row by row.
+struct RowSlots {
+    uint32_t first;  // row 0 (the run's middle bin N1/2 sits at position 1, off the line of the other rows)
+    uint32_t lin;    // row r >= 1: lin + r * step
+    int step;
+    bool linear;
+};
+__device__ __forceinline__ RowSlots row_slots(uint32_t j0, uint32_t tbase, int pair_log)
+{
+    RowSlots s;
+    s.linear = pair_log == 0 || pair_log >= 10;
+    s.first = s.lin = j0 - tbase;
+    s.step = 64;
+    if (pair_log >= 10) {
+        const uint32_t N1 = 1u << pair_log, k1 = j0 & (N1 - 1u), run = j0 - k1 - tbase;
+        const bool upper = k1 >= N1 / 2;
+        s.lin = run + (upper ? 2u * (N1 - k1) + 1u : 2u * k1);
+        s.first = k1 == N1 / 2 ? run + 1u : s.lin;
+        s.step = upper ? -128 : 128;
+    }
+    return s;
+}
+__device__ __forceinline__ uint32_t slot_of(const RowSlots& s, int r, uint32_t j0, uint32_t tbase, int pair_log)
+{
+    if (s.linear) return r == 0 ? s.first : s.lin + (uint32_t)(r * s.step);
+    return spec_index(j0 + (uint32_t)r * 64u, pair_log) - tbase;
+}
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v)
 {
 #pragma unroll
@@ -196,6 +227,7 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
     const uint32_t bstar = sel[c * 8 + 0];
     __syncthreads();
     const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
+    const RowSlots slots = row_slots(j0, tbase, pair_log);
     uint32_t key[ROWS], vb[ROWS];
     uint64_t cm[ROWS];
     uint32_t ndef = 0, vmax = 0, ncand = 0, mine = 0;  // mine: bit r set = this lane's bin of row r is a candidate
@@ -203,7 +235,7 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
-        const float2 z = valid ? stage[spec_index(j, pair_log) - tbase] : make_float2(0.f, 0.f);
+        const float2 z = valid ? stage[slot_of(slots, r, j0, tbase, pair_log)] : make_float2(0.f, 0.f);
         key[r] = key_of(z);
         vb[r] = vbits_of(z);
         const uint32_t bucket = key[r] >> kKeyShift;
@@ -547,6 +579,7 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     tile_to_lds(X, tbase, B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile, sstride, stage, tid);
     __syncthreads();
     const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
+    const RowSlots slots = row_slots(j0, tbase, pair_log);
     float2 z[ROWS];
     uint64_t em[ROWS], fm[ROWS];
     uint32_t neq = 0, gtbits = 0, eqbits = 0;  // bit r = this lane's bin of row r is above / equal to the threshold
@@ -554,7 +587,7 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
-        z[r] = valid ? stage[spec_index(j, pair_log) - tbase] : make_float2(0.f, 0.f);
+        z[r] = valid ? stage[slot_of(slots, r, j0, tbase, pair_log)] : make_float2(0.f, 0.f);
         const uint32_t key = key_of(z[r]);
         const bool gt = valid && key > tau, eq = valid && key == tau;
         gtbits |= (uint32_t)gt << r;
@@ -790,6 +823,7 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
     auto finish = [&](uint32_t t, const DecHead& h, const DecCodes<NL>& cd) __attribute__((always_inline)) {
         const uint32_t tile = t % Tn, tbase = tile * kTile;
         const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
+        const RowSlots slots = row_slots(j0, tbase, pair_log);
 #pragma unroll
         for (int i = 0; i < NL; ++i) *reinterpret_cast<u32x4*>(cwin + i * 1024 + lane * 16) = cd.main[i];
         if (lane == 0) *reinterpret_cast<u32x4*>(cwin + NL * 1024) = cd.tail;
@@ -823,7 +857,7 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
                 out.y = __uint_as_float(dequantize(cim, h.pbase, bits, shift));
             }
             const uint32_t j = j0 + r * 64;
-            if (j < B) stage[spec_index(j, pair_log) - tbase] = out;
+            if (j < B) stage[slot_of(slots, r, j0, tbase, pair_log)] = out;
         }
         __syncthreads();
         float2* X = spec + (size_t)(t / Tn) * (size_t)sstride;
