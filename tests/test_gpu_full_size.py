@@ -58,6 +58,17 @@ def test_config3_all_chunks(dev, ref, alexnet):
             print(f"config3 theta=.5: selection mismatches {sel}, code mismatches {codes}, "
                   f"alpha gpu {e_gpu:.6f} oracle {e_or:.6f}", flush=True)
             assert abs(e_gpu - e_or) <= 1e-3 * e_or + 5e-3 * (sel > 0)
+    # other code widths at full size: the decoder fetches 1, 2 or 4 sixteen-byte pieces per lane depending on the width,
+    # and only here does a decoding workgroup walk several tiles
+    for wide in (5, 12, 32):
+        print(f"config3: {wide}-bit codes", flush=True)
+        packed_or = ref.encode_spectrum(spec_or, n, L, 0.5, wide, nthreads=THREADS)
+        assert np.array_equal(dev.encode(spec_or, n, L, 0.5, wide), packed_or)
+        dec_or = ref.decode_spectrum(packed_or, n, L, 0.5, wide, nthreads=THREADS)
+        dec_gpu = dev.decode(packed_or, n, L, 0.5, wide)
+        assert np.array_equal(dec_gpu.view(np.uint32), dec_or.view(np.uint32))
+        out_gpu, st = dev.decompress(packed_or, n, L, 0.5, wide, want_status=True)
+        assert st == 0 and rel_l2(out_gpu, ref.irfft(dec_or, n, L, nthreads=THREADS)) <= TOL
 
 
 def test_config4_segments(dev, ref):
