@@ -301,7 +301,7 @@ __device__ __forceinline__ uint32_t block_scan_incl_1024(uint32_t v, uint32_t* t
     return x + add;
 }
 
-constexpr int kStageBatch = 6;  // candidates per lane fetched in one go by k_resolve
+constexpr int kStageBatch = 12;  // candidates per lane fetched in one go by k_resolve (12 Ki staged / 1024 lanes)
 
 struct HeaderInfo {
     int write;
@@ -386,9 +386,6 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
         }
     }
     __syncthreads();
-    auto cand_at = [&](uint32_t t, uint32_t i) -> uint2 {
-        return staged ? stage[toff[t] + i] : cd[(size_t)t * kTile + i];
-    };
 
     if (need > 0) {
         uint32_t prefix = bstar << kKeyShift;
@@ -433,19 +430,35 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     }
 
     // per tile: candidates above tau and equal to tau
-    for (uint32_t t = wave; t < Tn; t += RW) {
-        const uint32_t nc = tnc[t];
-        uint32_t gt = 0, eq = 0;  // wave-uniform counts from ballots
-        for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
-            const uint32_t i = i0 + lane;
-            const bool valid = i < nc;
-            const uint32_t key = valid ? cand_at(t, i).x : 0u;
-            gt += (uint32_t)__popcll(__ballot(valid && key > tau));
-            eq += (uint32_t)__popcll(__ballot(valid && key == tau));
-        }
-        if (lane == 0) {
+    if (staged) {
+        // one lane per tile walks that tile's staged candidates (about 40 for a 2^20 chunk): no ballots, no
+        // wave-serial loop over tiles
+        for (uint32_t t = tid; t < Tn; t += RT) {
+            const uint32_t nc = tnc[t], o = toff[t];
+            uint32_t gt = 0, eq = 0;
+            for (uint32_t i = 0; i < nc; ++i) {
+                const uint32_t key = stage[o + i].x;
+                gt += key > tau;
+                eq += key == tau;
+            }
             tgt[t] = gt;
             teq[t] = eq;
+        }
+    } else {
+        for (uint32_t t = wave; t < Tn; t += RW) {
+            const uint32_t nc = tnc[t];
+            uint32_t gt = 0, eq = 0;  // wave-uniform counts from ballots
+            for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
+                const uint32_t i = i0 + lane;
+                const bool valid = i < nc;
+                const uint32_t key = valid ? cd[(size_t)t * kTile + i].x : 0u;
+                gt += (uint32_t)__popcll(__ballot(valid && key > tau));
+                eq += (uint32_t)__popcll(__ballot(valid && key == tau));
+            }
+            if (lane == 0) {
+                tgt[t] = gt;
+                teq[t] = eq;
+            }
         }
     }
     if (tid == 0) {
@@ -483,20 +496,35 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     }
 
     // largest component over the survivors
-    uint32_t vm = 0;  // per-lane running maximum over all of this wave's tiles, reduced once at the end
-    for (uint32_t t = wave; t < Tn; t += RW) {
-        const uint32_t nc = tnc[t], take = ttake[t];
-        if (lane == 0 && tdef[t]) vm = tvd[t] > vm ? tvd[t] : vm;
-        uint32_t eqrun = 0;
-        for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
-            const uint32_t i = i0 + lane;
-            const bool valid = i < nc;
-            const uint2 e = valid ? cand_at(t, i) : make_uint2(0u, 0u);
-            const bool iseq = valid && e.x == tau;
-            const uint64_t em = __ballot(iseq);
-            const bool kept = valid && (e.x > tau || (iseq && eqrun + prefix_popc(em) < take));
-            if (kept) vm = e.y > vm ? e.y : vm;
-            eqrun += (uint32_t)__popcll(em);
+    uint32_t vm = 0;  // per-lane running maximum, reduced once at the end
+    if (staged) {
+        for (uint32_t t = tid; t < Tn; t += RT) {
+            const uint32_t nc = tnc[t], o = toff[t], take = ttake[t];
+            if (tdef[t]) vm = tvd[t] > vm ? tvd[t] : vm;
+            uint32_t eqrun = 0;  // candidates equal to tau seen so far, in bin order
+            for (uint32_t i = 0; i < nc; ++i) {
+                const uint2 e = stage[o + i];
+                const bool iseq = e.x == tau;
+                const bool kept = e.x > tau || (iseq && eqrun < take);
+                eqrun += iseq;
+                if (kept) vm = e.y > vm ? e.y : vm;
+            }
+        }
+    } else {
+        for (uint32_t t = wave; t < Tn; t += RW) {
+            const uint32_t nc = tnc[t], take = ttake[t];
+            if (lane == 0 && tdef[t]) vm = tvd[t] > vm ? tvd[t] : vm;
+            uint32_t eqrun = 0;
+            for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
+                const uint32_t i = i0 + lane;
+                const bool valid = i < nc;
+                const uint2 e = valid ? cd[(size_t)t * kTile + i] : make_uint2(0u, 0u);
+                const bool iseq = valid && e.x == tau;
+                const uint64_t em = __ballot(iseq);
+                const bool kept = valid && (e.x > tau || (iseq && eqrun + prefix_popc(em) < take));
+                if (kept) vm = e.y > vm ? e.y : vm;
+                eqrun += (uint32_t)__popcll(em);
+            }
         }
     }
     vm = wave_max(vm);
