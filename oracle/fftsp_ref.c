@@ -589,6 +589,54 @@ uint32_t fftsp_ref_segment_length(size_t size)
     return L;
 }
 
+/*
+ * Receiver under an allgather (Sec. 4, "Implementation": every worker collects all peers' packed buffers;
+ * Sec. 3.1, last paragraph: the receiver applies the inverse steps).  The inverse transform is linear, so
+ * instead of reconstructing every peer's gradient and adding them, the peers' sparse spectra are added bin by bin
+ * and ONE inverse transform is taken:   out = scale * iFFT( sum_p D(packed_p) ).
+ *
+ * Readings (the paper leaves the arithmetic open; parity unpinned by the paper): the sum starts from a zero
+ * spectrum and adds the peers in list order in binary32 (one rounding per addition); `scale` (e.g. 1/p for an
+ * average) is applied to the binary32 result of the inverse transform with one binary32 multiplication.
+ * All peers must carry the same (n, L, theta, bits).
+ */
+int fftsp_ref_decode_accumulate_spectrum(const uint8_t* const* packed, int npeers, size_t bytes, size_t n, uint32_t L,
+                                         float theta, int bits, float* spec, int nthreads)
+{
+    if (!packed || npeers <= 0 || !spec || n == 0 || L < 2 || !is_pow2(L)) return REF_EINVAL;
+    size_t C = chunk_count(n, L), len = C * ((size_t)L + 2);
+    float* one = (float*)malloc(sizeof(float) * len);
+    if (!one) return REF_ENOSPC;
+    for (size_t i = 0; i < len; ++i) spec[i] = 0.0f;
+    int e = 0;
+    for (int p = 0; p < npeers && !e; ++p) {
+        if (!packed[p]) {
+            e = REF_EINVAL;
+            break;
+        }
+        e = fftsp_ref_decode_spectrum(packed[p], bytes, n, L, theta, bits, one, nthreads);
+        if (e) break;
+        for (size_t i = 0; i < len; ++i) spec[i] = spec[i] + one[i];
+    }
+    free(one);
+    return e;
+}
+
+int fftsp_ref_decompress_accumulate(const uint8_t* const* packed, int npeers, size_t bytes, float scale, float* out,
+                                    size_t n, uint32_t L, float theta, int bits, int nthreads)
+{
+    if (!out || n == 0 || L < 2 || !is_pow2(L)) return REF_EINVAL;
+    size_t C = chunk_count(n, L);
+    float* spec = (float*)malloc(sizeof(float) * C * ((size_t)L + 2));
+    if (!spec) return REF_ENOSPC;
+    int e = fftsp_ref_decode_accumulate_spectrum(packed, npeers, bytes, n, L, theta, bits, spec, nthreads);
+    if (!e) e = fftsp_ref_irfft(spec, n, L, out, nthreads);
+    if (!e)
+        for (size_t i = 0; i < n; ++i) out[i] = out[i] * scale;
+    free(spec);
+    return e;
+}
+
 size_t fftsp_ref_packed_bytes_segments(const size_t* off, int nseg, float theta, int bits)
 {
     if (!off || nseg <= 0 || fftsp_ref_mantissa_bits(bits) < 0) return 0;

@@ -56,6 +56,8 @@ def lib():
             "fftsp_ref_decode_spectrum": (C.c_int, [u8p, C.c_size_t, C.c_size_t, C.c_uint32, C.c_float, C.c_int, fp, C.c_int]),
             "fftsp_ref_compress": (C.c_int, [fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, u8p, C.c_size_t, C.c_int]),
             "fftsp_ref_decompress": (C.c_int, [u8p, C.c_size_t, fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int]),
+            "fftsp_ref_decode_accumulate_spectrum": (C.c_int, [C.POINTER(u8p), C.c_int, C.c_size_t, C.c_size_t, C.c_uint32, C.c_float, C.c_int, fp, C.c_int]),
+            "fftsp_ref_decompress_accumulate": (C.c_int, [C.POINTER(u8p), C.c_int, C.c_size_t, C.c_float, fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int]),
             "fftsp_ref_segment_length": (C.c_uint32, [C.c_size_t]),
             "fftsp_ref_packed_bytes_segments": (C.c_size_t, [szp, C.c_int, C.c_float, C.c_int]),
             "fftsp_ref_compress_segments": (C.c_int, [fp, szp, C.c_int, C.c_float, C.c_int, u8p, C.c_size_t, C.c_int]),
@@ -210,6 +212,36 @@ def decompress(packed, n, L, theta, bits, nthreads=1):
     out = np.empty(n, dtype=np.float32)
     _chk(lib().fftsp_ref_decompress(pp, packed.size, out.ctypes.data_as(C.POINTER(C.c_float)), n, L,
                                     np.float32(theta), bits, nthreads), "decompress")
+    return out
+
+
+def _peer_list(packed_list):
+    """ctypes array of byte pointers for a list of equally long packed streams (kept alive by the caller)."""
+    arrs = [np.ascontiguousarray(p, dtype=np.uint8) for p in packed_list]
+    if not arrs or any(a.size != arrs[0].size for a in arrs):
+        raise OracleError(EINVAL, "peer streams must be non-empty and equally long")
+    u8p = C.POINTER(C.c_uint8)
+    ptrs = (u8p * len(arrs))(*[a.ctypes.data_as(u8p) for a in arrs])
+    return arrs, ptrs
+
+
+def decode_accumulate_spectrum(packed_list, n, L, theta, bits, nthreads=1):
+    """Bin-wise binary32 sum, in list order, of the peers' decoded spectra (receiver under an allgather)."""
+    arrs, ptrs = _peer_list(packed_list)
+    spec = np.empty(n_chunks(n, L) * (L + 2), dtype=np.float32)
+    _chk(lib().fftsp_ref_decode_accumulate_spectrum(ptrs, len(arrs), arrs[0].size, n, L, np.float32(theta), bits,
+                                                    spec.ctypes.data_as(C.POINTER(C.c_float)), nthreads),
+         "decode_accumulate_spectrum")
+    return spec
+
+
+def decompress_accumulate(packed_list, scale, n, L, theta, bits, nthreads=1):
+    """scale * iFFT(sum of the peers' decoded spectra): one inverse transform for all peers."""
+    arrs, ptrs = _peer_list(packed_list)
+    out = np.empty(n, dtype=np.float32)
+    _chk(lib().fftsp_ref_decompress_accumulate(ptrs, len(arrs), arrs[0].size, np.float32(scale),
+                                               out.ctypes.data_as(C.POINTER(C.c_float)), n, L, np.float32(theta), bits,
+                                               nthreads), "decompress_accumulate")
     return out
 
 
