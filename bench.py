@@ -187,6 +187,34 @@ def main() -> int:
                          "end-to-end training speedup 2.26x on 8x P100 + 56 Gb/s IB (Table 2)",
     }
 
+    # receiver under an allgather: eight peers' streams summed in the spectrum, one inverse transform
+    # (extra keys; the headline above is one compress + one decompress)
+    peers = 8
+    ws_acc = torch.empty(fftsp.workspace_bytes_accumulate(n, L, bits, peers), dtype=torch.uint8, device=dev)
+    peer_packed = []
+    for p in range(peers):
+        gp = torch.roll(gd[0], 1 + 104729 * (p + 1)).contiguous()
+        pk = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        fftsp.compress(gp, L, args.theta, bits, pk, ws, stream)
+        peer_packed.append(pk)
+        del gp
+    torch.cuda.synchronize()
+    acc_steps = max(3, args.steps // 2)
+    for _ in range(2):
+        fftsp.decompress_accumulate(peer_packed, nbytes, 1.0 / peers, out[0], L, args.theta, bits, ws_acc, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(acc_steps):
+        fftsp.decompress_accumulate(peer_packed, nbytes, 1.0 / peers, out[0], L, args.theta, bits, ws_acc, stream)
+    torch.cuda.synchronize()
+    t_acc = (time.perf_counter() - t0) / acc_steps
+    assert fftsp.device_status(ws_acc) == 0
+    result["receiver_accumulate"] = {"peers": peers, "ms": round(t_acc * 1e3, 4),
+                                     "ms_if_decompressed_one_by_one": round(peers * t_d * 1e3, 4),
+                                     "packed_GBps_in": round(peers * nbytes / t_acc / 1e9, 2),
+                                     "gradient_GBps_equivalent": round(peers * 4.0 * n / t_acc / 1e9, 2)}
+    del peer_packed, ws_acc
+
     if args.sweep:
         sweep = {}
         for t in (0.1, 0.3, 0.7, 0.9):

@@ -85,6 +85,30 @@ int fftsp_decompress(const void* d_packed, size_t packed_bytes,
                      float* d_grad_out, size_t n, uint32_t chunk_len, float theta, int bits,
                      void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
 
+/* ---- receiver under an allgather (Sec. 4, "Implementation": every worker collects the packed gradients of all
+ *      peers; Sec. 3.1: the receiver applies the inverse steps) ----
+ *
+ * The inverse transform is linear, so the peers' sparse spectra are added bin by bin and ONE inverse transform is
+ * taken:   d_grad_out = scale * iFFT( sum_p D(d_packed[p]) ),   e.g. scale = 1/npeers for the average.
+ * The sum starts from zero and adds the peers in list order in binary32; scale multiplies the transform's
+ * normalisation 1/L (one binary32 product per output).
+ *
+ * d_packed: HOST array of npeers DEVICE pointers (16-byte aligned), each to a stream of packed_bytes bytes made
+ * with the same (n, chunk_len, theta, bits); the array is read before the call returns.  1 <= npeers <=
+ * FFTSP_MAX_PEERS (more: FFTSP_EUNSUPPORTED; call again on the remainder and add).  A stream whose header or
+ * bitmaps disagree with the arguments sets the device status word to FFTSP_EFORMAT; reads stay inside each
+ * stream.  The workspace must hold fftsp_workspace_bytes_accumulate(...) bytes (0 on invalid arguments). */
+#define FFTSP_MAX_PEERS 32
+size_t fftsp_workspace_bytes_accumulate(size_t n, uint32_t chunk_len, int bits, int npeers);
+int fftsp_decompress_accumulate(const void* const* d_packed, int npeers, size_t packed_bytes, float scale,
+                                float* d_grad_out, size_t n, uint32_t chunk_len, float theta, int bits,
+                                void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+/* Stage-level: only the summed spectrum, C*(L+2) floats in natural bin order, unscaled (bit-exact against the
+ * same binary32 sum on the host). */
+int fftsp_decode_accumulate_spectrum(const void* const* d_packed, int npeers, size_t packed_bytes, size_t n,
+                                     uint32_t chunk_len, float theta, int bits, float* d_spec,
+                                     void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+
 /* ---- stage-level entry points (the same kernels the codec runs, exposed for parity checks) ---- */
 
 /* Forward real DFT of each chunk (the sum of Sec. 3.1.1, sign -, unnormalised).

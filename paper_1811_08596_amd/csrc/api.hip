@@ -226,7 +226,7 @@ int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     return hip_status(launch_irfft(d_spec, p.L / 2 + 1, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                                   0, reinterpret_cast<hipStream_t>(stream)));
+                                   0, 1.0f, reinterpret_cast<hipStream_t>(stream)));
 }
 
 int fftsp_encode_spectrum(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
@@ -313,7 +313,77 @@ int fftsp_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_ou
     hipError_t e = launch_decode(in, in + kStreamHeader, a, spec, ws, p.ws, 1, 1, s);
     if (e == hipSuccess)
         e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                         a.pair_log != 0, s);
+                         a.pair_log != 0, 1.0f, s);
+    return hip_status(e);
+}
+
+/* ---------------- receiver under an allgather: several peers' streams, one inverse transform ---------------- */
+
+static int peer_list(PeerList* out, const void* const* d_packed, int npeers)
+{
+    if (!d_packed || npeers < 1) return FFTSP_EINVAL;
+    if (npeers > kMaxPeers) return FFTSP_EUNSUPPORTED;
+    for (int i = 0; i < kMaxPeers; ++i) out->p[i] = nullptr;
+    for (int i = 0; i < npeers; ++i) {
+        if (!d_packed[i] || !aligned16(d_packed[i])) return FFTSP_EINVAL;
+        out->p[i] = static_cast<const uint8_t*>(d_packed[i]);
+    }
+    return FFTSP_OK;
+}
+
+size_t fftsp_workspace_bytes_accumulate(size_t n, uint32_t chunk_len, int bits, int npeers)
+{
+    Plan p;
+    if (npeers < 1 || npeers > kMaxPeers || make_plan(&p, n, chunk_len, nullptr, &bits) != FFTSP_OK) return 0;
+    return make_peer_workspace(p.ws, p.C, p.L, npeers).total;
+}
+
+int fftsp_decode_accumulate_spectrum(const void* const* d_packed, int npeers, size_t packed_bytes, size_t n,
+                                     uint32_t chunk_len, float theta, int bits, float* d_spec, void* d_workspace,
+                                     size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    PeerList peers;
+    rc = peer_list(&peers, d_packed, npeers);
+    if (rc) return rc;
+    if (!d_spec || !d_workspace || !aligned16(d_spec) || !aligned16(d_workspace)) return FFTSP_EINVAL;
+    if (packed_bytes < kStreamHeader + p.C * p.S) return FFTSP_EFORMAT;
+    const PeerWorkspace pw = make_peer_workspace(p.ws, p.C, p.L, npeers);
+    if (workspace_bytes < pw.total) return FFTSP_EWORKSPACE;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    return hip_status(launch_decode_peers(peers, npeers, codec_args(p, theta), d_spec, ws, p.ws, pw,
+                                          reinterpret_cast<hipStream_t>(stream)));
+}
+
+int fftsp_decompress_accumulate(const void* const* d_packed, int npeers, size_t packed_bytes, float scale,
+                                float* d_grad_out, size_t n, uint32_t chunk_len, float theta, int bits,
+                                void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    PeerList peers;
+    rc = peer_list(&peers, d_packed, npeers);
+    if (rc) return rc;
+    if (!d_grad_out || !d_workspace || !aligned16(d_grad_out) || !aligned16(d_workspace) || !(scale == scale))
+        return FFTSP_EINVAL;
+    if (packed_bytes < kStreamHeader + p.C * p.S) return FFTSP_EFORMAT;
+    const PeerWorkspace pw = make_peer_workspace(p.ws, p.C, p.L, npeers);
+    if (workspace_bytes < pw.total) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
+    CodecArgs a = codec_args(p, theta);
+    a.sstride = padded_bins(p.L);
+    a.pair_log = fft_pair_log(p.logL);
+    hipError_t e = launch_decode_peers(peers, npeers, a, spec, ws, p.ws, pw, s);
+    if (e == hipSuccess)
+        e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
+                         a.pair_log != 0, scale, s);
     return hip_status(e);
 }
 
@@ -447,7 +517,7 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
         hipError_t e = launch_decode(in, in + rec_off, a, spec, ws, w, i == 0, i == 0, s);
         if (e == hipSuccess)
             e = launch_irfft(spec, a.sstride, size, log2_exact(L), 1, d_grad_out + seg_offsets[i],
-                             reinterpret_cast<float2*>(ws + w.mid), t, a.pair_log != 0, s);
+                             reinterpret_cast<float2*>(ws + w.mid), t, a.pair_log != 0, 1.0f, s);
         if (e != hipSuccess) return FFTSP_EHIP;
         rec_off += a.S;
     }

@@ -33,6 +33,9 @@ __device__ __forceinline__ uint32_t vbits_of(float2 z)
     const uint32_t a = __float_as_uint(z.x) & 0x7FFFFFFFu, b = __float_as_uint(z.y) & 0x7FFFFFFFu;
     return a > b ? a : b;
 }
+// a plain 16-byte value that the compiler keeps in registers
+typedef uint32_t u32x4 __attribute__((vector_size(16)));
+
 // number of set bits of a wave-uniform mask below this lane (v_mbcnt_lo/hi: two instructions, no 64-bit math)
 __device__ __forceinline__ uint32_t prefix_popc(uint64_t mask)
 {
@@ -712,18 +715,16 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
 constexpr int GROUP_WORDS = 16;  // one wave of the decode kernel covers 512 bins = 16 bitmap words
 
 // Per chunk: number of set bits before each group of 16 bitmap words (the prefix sum of Sec. 3.2's status
-// vector, kept at the granularity a wave needs); checks the headers and leaves the verdict in sel[c][7].
-__global__ __launch_bounds__(RT) void k_group_prefix(const uint8_t* __restrict__ stream,
-                                                     const uint8_t* __restrict__ records, size_t S, uint32_t W,
-                                                     uint32_t k, uint32_t word3, HeaderInfo hdr,
-                                                     uint32_t* __restrict__ gprefix, uint32_t* __restrict__ sel,
-                                                     uint32_t* __restrict__ status, int reset_status)
+// vector, kept at the granularity a wave needs); checks the headers and leaves the verdict in *verdict.
+__device__ __forceinline__ void group_prefix_chunk(const uint8_t* __restrict__ stream, const uint8_t* __restrict__ record,
+                                                   bool first_of_stream, uint32_t W, uint32_t k, uint32_t word3,
+                                                   const HeaderInfo& hdr, uint32_t* __restrict__ gprefix,
+                                                   uint32_t* __restrict__ verdict)
 {
     __shared__ uint32_t tmp[RW];
     __shared__ uint32_t s_carry;
     const int tid = threadIdx.x;
-    const size_t c = blockIdx.x;
-    const uint32_t* rec = reinterpret_cast<const uint32_t*>(records + c * S);
+    const uint32_t* rec = reinterpret_cast<const uint32_t*>(record);
     const uint32_t* bitmap = rec + 4;
     const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
     if (tid == 0) s_carry = 0;
@@ -746,22 +747,47 @@ __global__ __launch_bounds__(RT) void k_group_prefix(const uint8_t* __restrict__
         }
         const uint32_t carry = s_carry;
         const uint32_t incl = block_scan_incl_1024(cnt, tmp);
-        if (g < G) gprefix[c * G + g] = carry + incl - cnt;
+        if (g < G) gprefix[g] = carry + incl - cnt;
         __syncthreads();
         if (tid == RT - 1) s_carry = carry + incl;
         __syncthreads();
     }
     if (tid == 0) {
         bool bad = s_carry != k || rec[2] != k || rec[3] != word3;
-        if (hdr.write && c == 0) {
+        if (hdr.write && first_of_stream) {
             const uint32_t* h = reinterpret_cast<const uint32_t*>(stream);
             bad = bad || h[0] != 0x31505346u || h[1] != 1u || h[2] != (uint32_t)hdr.n ||
                   h[3] != (uint32_t)(hdr.n >> 32) || h[4] != hdr.L || h[5] != hdr.C || h[6] != hdr.N ||
                   h[7] != hdr.m || h[8] != hdr.k || h[9] != hdr.S;
         }
-        sel[c * 8 + 7] = bad ? 6u : 0u;
-        if (reset_status && c == 0) status[0] = 0u;  // raised again by k_decode, which runs after this kernel
+        *verdict = bad ? 6u : 0u;
     }
+}
+
+__global__ __launch_bounds__(RT) void k_group_prefix(const uint8_t* __restrict__ stream,
+                                                     const uint8_t* __restrict__ records, size_t S, uint32_t W,
+                                                     uint32_t k, uint32_t word3, HeaderInfo hdr,
+                                                     uint32_t* __restrict__ gprefix, uint32_t* __restrict__ sel,
+                                                     uint32_t* __restrict__ status, int reset_status)
+{
+    const size_t c = blockIdx.x;
+    const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
+    group_prefix_chunk(stream, records + c * S, c == 0, W, k, word3, hdr, gprefix + c * G, sel + c * 8 + 7);
+    // raised again by k_decode, which runs after this kernel
+    if (threadIdx.x == 0 && reset_status && c == 0) status[0] = 0u;
+}
+
+// The same for several peers' streams: workgroup (peer, chunk).
+__global__ __launch_bounds__(RT) void k_group_prefix_peers(PeerList streams, uint32_t C, size_t S, uint32_t W, uint32_t k,
+                                                           HeaderInfo hdr, uint32_t* __restrict__ gprefix,
+                                                           uint32_t* __restrict__ verd, uint32_t* __restrict__ status)
+{
+    const uint32_t peer = blockIdx.x / C, c = blockIdx.x % C;
+    const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
+    const uint8_t* stream = streams.p[peer];
+    group_prefix_chunk(stream, stream + 64 + (size_t)c * S, c == 0, W, k, 0u, hdr,
+                       gprefix + ((size_t)peer * C + c) * G, verd + (size_t)peer * C + c);
+    if (threadIdx.x == 0 && blockIdx.x == 0) status[0] = 0u;
 }
 
 // Persistent decoder.  A workgroup walks tiles of 2048 bins (blockIdx, blockIdx + grid, ...), one wave per
@@ -770,23 +796,30 @@ __global__ __launch_bounds__(RT) void k_group_prefix(const uint8_t* __restrict__
 // and picks the codes out of LDS by rank (a per-bin gather from global memory costs one memory instruction per
 // row of 64 bins and was measured at a quarter of the kernel's time).  The work on a tile is a chain of two
 // dependent memory round trips (bitmap word and group prefix, then the codes) before anything can be stored, so
-// the kernel is software-pipelined: while tile t is dequantised and stored, the codes of tile t+1 and the bitmap
-// words of tile t+2 are in flight.  All loads are unconditional (clamped to addresses inside the record).
+// the kernel is software-pipelined: while one item is dequantised, the codes of the next and the bitmap words
+// of the one after are in flight.  All loads are unconditional (clamped to addresses inside the record).
+//
+// With P > 1 peers (receiver under an allgather: Sec. 4, implementation) an item is (tile, peer): a tile's bins
+// are summed over the peers in list order in registers, starting from zero, and stored once.
 struct DecHead {
     uint32_t word, run, pbase;  // this lane's bitmap word (lanes 0..15), kept bins before the wave's group, record pbase
 };
 
 // NL = 16-byte loads per lane: 1 for codes of up to 8 bits, 2 up to 16, 4 for 32
-typedef uint32_t u32x4 __attribute__((vector_size(16)));  // a plain 16-byte value the compiler keeps in registers
-
 template <int NL>
 struct DecCodes {
     u32x4 main[NL];
     u32x4 tail;  // lane 0: the 16 bytes behind the main window (the window starts on a 16-byte boundary <= the first code)
 };
 
+struct DecItem {
+    uint32_t t, peer;  // tile index over all chunks, index into the peer list
+};
+
 // VEC: the spectrum buffer is the codec's own (chunks padded to 16 bins, 16-byte aligned): whole-line stores, and
 // the one bin a partial tile may write past the chunk's last bin lands in the padding.
+// verd: header verdict of (peer, chunk) at verd[peer * C + chunk].
+// One stream.
 template <int NL, bool VEC>
 __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
                                                uint32_t k, int bits, int m, uint32_t Tn, uint32_t total, size_t C,
@@ -930,6 +963,175 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
     }
 }
 
+// The decoder for several peers' streams: same pipeline, items are (tile, peer).
+template <int NL, bool VEC>
+__global__ __launch_bounds__(NT) void k_decode_peers(PeerList recs, uint32_t npeers, size_t S, uint32_t B, uint32_t W,
+                                               uint32_t k, int bits, int m, uint32_t Tn, uint32_t total, size_t C,
+                                               const uint32_t* __restrict__ gprefix, const uint32_t* __restrict__ verd,
+                                               uint32_t* __restrict__ status,
+                                               float2* __restrict__ spec, uint32_t sstride, int pair_log)
+{
+    constexpr int kWin = NL * 1024 + 32;  // bytes of LDS per wave: main window, tail, slack for the 3-word read
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t P = npeers;
+    // header verdicts of the group-prefix kernel raise the status word
+    for (size_t i = (size_t)blockIdx.x * NT + tid; i < C * P; i += (size_t)gridDim.x * NT) {
+        const uint32_t verdict = verd[i];
+        if (verdict) atomicMax(status, verdict);
+    }
+    const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
+    const int shift = 23 - m;
+    const uint32_t code_base = 16u + 4u * W;  // byte offset of the codes inside a record
+    __shared__ float2 stage[kTile];
+    __shared__ __attribute__((aligned(16))) uint8_t cwin_all[4 * kWin];
+    uint8_t* cwin = cwin_all + wave * kWin;
+    const uint32_t step = gridDim.x;
+
+    auto record_of = [&](DecItem it) __attribute__((always_inline)) {
+        return recs.p[it.peer] + (size_t)(it.t / Tn) * S;
+    };
+    auto next_item = [&](DecItem it) __attribute__((always_inline)) {
+        DecItem n;
+        const bool last_peer = it.peer + 1u == P;
+        n.peer = last_peer ? 0u : it.peer + 1u;
+        n.t = last_peer ? it.t + step : it.t;
+        return n;
+    };
+    // live = false: the item does not exist; the loads are still issued, to item (0, 0)
+    auto load_head = [&](DecItem it, bool live) __attribute__((always_inline)) {
+        if (!live) it.t = it.peer = 0;
+        const uint32_t* rec = reinterpret_cast<const uint32_t*>(record_of(it));
+        const uint32_t g = (it.t % Tn) * (kTile / 32 / GROUP_WORDS) + wave;
+        const uint32_t wi = g * GROUP_WORDS + lane;
+        const bool has = live && lane < GROUP_WORDS && wi < W;
+        DecHead h;
+        h.word = rec[4 + (has ? wi : 0u)];
+        h.run = gprefix[((size_t)it.peer * C + it.t / Tn) * G + (g < G ? g : 0u)];
+        h.pbase = rec[0];
+        if (!has) h.word = 0u;
+        return h;
+    };
+    // rank of this lane's bin in row r if its bit is set; advances run past the row
+    auto row_rank = [&](const DecHead& h, int r, uint32_t& run, bool& set) __attribute__((always_inline)) {
+        const uint32_t lo = __shfl(h.word, 2 * r, 64), hi = __shfl(h.word, 2 * r + 1, 64);
+        const uint64_t mask = (uint64_t)lo | ((uint64_t)hi << 32);
+        const uint32_t half = lane < 32 ? lo : hi;
+        set = ((half >> (lane & 31)) & 1u) && k > 0;
+        uint32_t rank = run + prefix_popc(mask);
+        run += (uint32_t)__popcll(mask);
+        return rank < k ? rank : (k ? k - 1u : 0u);  // a corrupt bitmap must not point outside the record
+    };
+    // first byte of the wave's LDS window inside the record: the 16-byte boundary at or below its first code
+    auto window_start = [&](const DecHead& h) __attribute__((always_inline)) {
+        const uint32_t first = h.run < k ? h.run : (k ? k - 1u : 0u);
+        return (code_base + ((2u * (uint32_t)bits * first) >> 3)) & ~15u;
+    };
+    auto load_codes = [&](DecItem it, bool live, const DecHead& h, DecCodes<NL>& cd) __attribute__((always_inline)) {
+        if (!live) it.t = it.peer = 0;
+        const uint8_t* rec = record_of(it);
+        const uint32_t start = window_start(h), last = (uint32_t)S - 16u;  // S is a multiple of 16, at least 32
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            const uint32_t off = start + (uint32_t)(i * 1024 + lane * 16);
+            cd.main[i] = *reinterpret_cast<const u32x4*>(rec + (off < last ? off : last));
+        }
+        const uint32_t off = start + (uint32_t)(NL * 1024);
+        cd.tail = *reinterpret_cast<const u32x4*>(rec + (off < last ? off : last));
+    };
+    float2 acc[ROWS];  // this lane's bins of the tile being summed over the peers
+    auto finish = [&](DecItem it, const DecHead& h, const DecCodes<NL>& cd) __attribute__((always_inline)) {
+        const uint32_t tile = it.t % Tn, tbase = tile * kTile;
+        const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
+        const RowSlots slots = row_slots(j0, tbase, pair_log);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) *reinterpret_cast<u32x4*>(cwin + i * 1024 + lane * 16) = cd.main[i];
+        if (lane == 0) *reinterpret_cast<u32x4*>(cwin + NL * 1024) = cd.tail;
+        __syncthreads();  // codes visible to the wave; the previous tile's stage has been read by everyone
+        const uint32_t start = window_start(h);
+        uint32_t run = h.run;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            bool set;
+            const uint32_t rank = row_rank(h, r, run, set);
+            float2 out = make_float2(0.f, 0.f);
+            if (set) {
+                const uint32_t p = 2u * (uint32_t)bits * rank;                // bit offset of the pair in the codes
+                uint32_t cre, cim;
+                if (bits == 8) {
+                    const uint32_t v = *reinterpret_cast<const uint16_t*>(cwin + (code_base + (p >> 3) - start));
+                    cre = v & 0xFFu;
+                    cim = v >> 8;
+                } else {
+                    const uint32_t* w = reinterpret_cast<const uint32_t*>(cwin + (code_base + 4u * (p >> 5) - start));
+                    const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
+                    const uint32_t sh = p & 31u, q = sh + (uint32_t)bits;
+                    const uint64_t w01 = (uint64_t)w0 | ((uint64_t)w1 << 32), w12 = (uint64_t)w1 | ((uint64_t)w2 << 32);
+                    const uint32_t keep = bits == 32 ? 0xFFFFFFFFu : ((1u << bits) - 1u);
+                    cre = (uint32_t)(w01 >> sh) & keep;
+                    cim = (uint32_t)((q >= 32u ? w12 : w01) >> (q & 31u)) & keep;
+                }
+                out.x = __uint_as_float(dequantize(cre, h.pbase, bits, shift));
+                out.y = __uint_as_float(dequantize(cim, h.pbase, bits, shift));
+            }
+            const float2 prev = it.peer == 0 ? make_float2(0.f, 0.f) : acc[r];
+            acc[r] = make_float2(prev.x + out.x, prev.y + out.y);
+        }
+        if (it.peer + 1u != P) {
+            __syncthreads();  // every lane has picked its codes before the next item overwrites the window
+            return;
+        }
+        // The tile's bins occupy one contiguous range of the spectrum buffer in either bin order (paired runs are
+        // tile-aligned), so the sums are placed in LDS at their in-tile position and written out as whole lines.
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            if (j0 + (uint32_t)r * 64u < B) stage[slot_of(slots, r, j0, tbase, pair_log)] = acc[r];
+        __syncthreads();
+        float2* X = spec + (size_t)(it.t / Tn) * (size_t)sstride;
+        const uint32_t count = B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile;
+        if constexpr (VEC) {
+            float4* dst = reinterpret_cast<float4*>(X + tbase);
+            const float4* src = reinterpret_cast<const float4*>(stage);
+#pragma unroll
+            for (int i = 0; i < kTile / 2 / NT; ++i) {
+                const uint32_t idx = (uint32_t)(tid + i * NT);
+                if (2u * idx < count) dst[idx] = src[idx];
+            }
+        } else {
+            for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = stage[i];
+        }
+    };
+
+    // Three register sets rotate by name through a loop body written out three times: rotating by assignment
+    // would copy registers that loads are still filling, and a copy waits for its load.
+    DecItem cur;
+    cur.t = blockIdx.x;
+    cur.peer = 0;
+    if (cur.t >= total) return;
+    DecHead h0, h1, h2;
+    DecCodes<NL> c0, c1, c2;
+    // item `cur` is in (hc, cc), the next one in (hn, cn); fetches what the next two items need, then finishes cur
+    auto advance = [&](const DecHead& hc, const DecCodes<NL>& cc, const DecHead& hn, DecCodes<NL>& cn, DecHead& hn2) __attribute__((always_inline)) {
+        const DecItem nxt = next_item(cur), nx2 = next_item(nxt);
+        const bool more = nxt.t < total, more2 = more && nx2.t < total;
+        hn2 = load_head(nx2, more2);
+        load_codes(nxt, more, hn, cn);
+        finish(cur, hc, cc);
+        cur = nxt;
+        return more;
+    };
+    h0 = load_head(cur, true);
+    {
+        const DecItem nxt = next_item(cur);
+        h1 = load_head(nxt, nxt.t < total);
+    }
+    load_codes(cur, true, h0, c0);
+    for (;;) {
+        if (!advance(h0, c0, h1, c1, h2)) break;
+        if (!advance(h1, c1, h2, c2, h0)) break;
+        if (!advance(h2, c2, h0, c0, h1)) break;
+    }
+}
+
 }  // namespace
 
 // status words and histograms are adjacent: one fill
@@ -980,25 +1182,28 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     return hipGetLastError();
 }
 
-hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
-                         uint8_t* ws_base, const Workspace& w, int check_header, int reset_status, hipStream_t s)
+// the decode kernel proper: one stream with its verdicts in the sel array (chunk c: word 8c+7), or the peer
+// list with verdicts at verd[peer * C + c]
+static hipError_t launch_decode_kernel(const PeerList& recs, uint32_t npeers, const CodecArgs& a, float* spec,
+                                       const uint32_t* gprefix, const uint32_t* verd, uint32_t* status, bool peers_layout,
+                                       hipStream_t s)
 {
     const uint32_t B = a.L / 2 + 1, W = (B + 31) / 32, Tn = tiles_per_chunk(a.L);
-    uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
-    uint32_t* sel = reinterpret_cast<uint32_t*>(ws_base + w.sel);
-    uint32_t* gprefix = reinterpret_cast<uint32_t*>(ws_base + w.prefix);
-    if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
-    HeaderInfo h{check_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
-                 a.hdr_theta};
-    FFTSP_LAUNCH("group_prefix", k_group_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k,
-                 a.word3, h, gprefix, sel, status, reset_status);
     // persistent grid: about two rounds of the workgroups a chip holds at once (six to eight per compute unit);
     // measured best at 4096 (2048: +10 %, one workgroup per tile: +8 %)
     const uint32_t total = (uint32_t)(a.C * Tn);
     const uint32_t grid = total < 4096u ? total : 4096u;
-#define FFTSP_DECODE(NL, VEC)                                                                                         \
-    FFTSP_LAUNCH("decode", (k_decode<NL, VEC>), dim3(grid), dim3(NT), 0, s, records, a.S, B, W, a.k, a.bits, a.m, Tn, \
-                 total, a.C, gprefix, sel, status, reinterpret_cast<float2*>(spec), a.sstride, a.pair_log)
+#define FFTSP_DECODE(NL, VEC)                                                                                      \
+    do {                                                                                                           \
+        if (peers_layout)                                                                                          \
+            FFTSP_LAUNCH("decode", (k_decode_peers<NL, VEC>), dim3(grid), dim3(NT), 0, s, recs, npeers, a.S, B, W,  \
+                         a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                                  \
+                         reinterpret_cast<float2*>(spec), a.sstride, a.pair_log);                                  \
+        else                                                                                                       \
+            FFTSP_LAUNCH("decode", (k_decode<NL, VEC>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W, a.k,     \
+                         a.bits, a.m, Tn, total, a.C, gprefix, verd, status, reinterpret_cast<float2*>(spec),      \
+                         a.sstride, a.pair_log);                                                                   \
+    } while (0)
     const bool vec = a.sstride == padded_bins(a.L) && (reinterpret_cast<uintptr_t>(spec) & 15u) == 0;
     // code widths are 3..16 or 32 bits
     const int nl = a.bits <= 8 ? 1 : a.bits <= 16 ? 2 : 4;
@@ -1012,6 +1217,40 @@ hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, con
     }
 #undef FFTSP_DECODE
     return hipGetLastError();
+}
+
+hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
+                         uint8_t* ws_base, const Workspace& w, int check_header, int reset_status, hipStream_t s)
+{
+    const uint32_t B = a.L / 2 + 1, W = (B + 31) / 32, Tn = tiles_per_chunk(a.L);
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
+    uint32_t* sel = reinterpret_cast<uint32_t*>(ws_base + w.sel);
+    uint32_t* gprefix = reinterpret_cast<uint32_t*>(ws_base + w.prefix);
+    if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
+    HeaderInfo h{check_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
+                 a.hdr_theta};
+    FFTSP_LAUNCH("group_prefix", k_group_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k,
+                 a.word3, h, gprefix, sel, status, reset_status);
+    PeerList recs{};
+    recs.p[0] = records;
+    return launch_decode_kernel(recs, 1u, a, spec, gprefix, sel, status, false, s);
+}
+
+hipError_t launch_decode_peers(const PeerList& streams, int npeers, const CodecArgs& a, float* spec, uint8_t* ws_base,
+                               const Workspace& w, const PeerWorkspace& pw, hipStream_t s)
+{
+    const uint32_t B = a.L / 2 + 1, W = (B + 31) / 32, Tn = tiles_per_chunk(a.L);
+    uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
+    uint32_t* gprefix = reinterpret_cast<uint32_t*>(ws_base + pw.prefix);
+    uint32_t* verd = reinterpret_cast<uint32_t*>(ws_base + pw.verd);
+    if (npeers < 1 || npeers > kMaxPeers) return hipErrorInvalidValue;
+    if (a.C * (size_t)Tn > 0x7fffffffu || a.C * (size_t)npeers > 0x7fffffffu) return hipErrorInvalidValue;
+    HeaderInfo h{1, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S, a.hdr_theta};
+    FFTSP_LAUNCH("group_prefix", k_group_prefix_peers, dim3((unsigned)(a.C * (size_t)npeers)), dim3(RT), 0, s, streams,
+                 (uint32_t)a.C, a.S, W, a.k, h, gprefix, verd, status);
+    PeerList recs{};
+    for (int i = 0; i < npeers; ++i) recs.p[i] = streams.p[i] + 64;  // records follow the 64-byte stream header
+    return launch_decode_kernel(recs, (uint32_t)npeers, a, spec, gprefix, verd, status, true, s);
 }
 
 }  // namespace fftsp

@@ -251,7 +251,7 @@ __global__ __launch_bounds__(NT) void k_fwd_small(const float* __restrict__ in, 
 
 template <int LOGM, int LOGE, int NT>
 __global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spec, uint32_t sstride, size_t n, size_t C,
-                                                  float* __restrict__ out, Tables tb, int aligned)
+                                                  float* __restrict__ out, Tables tb, int aligned, float gain)
 {
     constexpr int M = 1 << LOGM, LOGT = LOGE - LOGM, ELEMS = 1 << LOGE;
     extern __shared__ float2 smem[];
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spe
     }
     __syncthreads();
     run_fft<LOGM, LOGT, NT, true>(d, tw, tid);
-    const float scale = 1.0f / (float)(2 * M);
+    const float scale = gain * (1.0f / (float)(2 * M));  // 1/L is a power of two: the product is gain, rescaled exactly
 #pragma unroll
     for (int q = 0; q < ELEMS / NT; ++q) {
         const int w = tid + q * NT, i = w & (M - 1), b = w >> LOGM;
@@ -769,7 +769,8 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
 // `aligned`: bit 0 = output is 8-byte aligned, bit 1 = 16-byte aligned.
 template <int LOGN1>
 __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, int logM, float* __restrict__ out,
-                                               size_t n, Tables tb, int aligned, uint32_t total, uint32_t per_wg, int glog)
+                                               size_t n, Tables tb, int aligned, uint32_t total, uint32_t per_wg, int glog,
+                                               float gain)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
@@ -806,7 +807,7 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
     load_tile(t, tid0, true);
     fill(tid0);
     __syncthreads();
-    const float scale = 1.0f / (float)(2u * M);
+    const float scale = gain * (1.0f / (float)(2u * M));
     for (;;) {
         const int tid = opaque_lane(tid0);
         const bool more = t + tstep < tend;
@@ -868,7 +869,7 @@ hipError_t small_fwd(const float* in, size_t n, size_t C, float2* spec, uint32_t
 
 template <int LOGM>
 hipError_t small_inv(const float2* spec, uint32_t sstride, size_t n, size_t C, float* out, Tables t, int aligned,
-                     hipStream_t s)
+                     float gain, hipStream_t s)
 {
     constexpr int LOGE = LOGM >= 12 ? LOGM : 12;
     const size_t lds = ((size_t)(1 << LOGE) + (1 << LOGM)) * sizeof(float2);
@@ -877,7 +878,7 @@ hipError_t small_inv(const float2* spec, uint32_t sstride, size_t n, size_t C, f
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
     FFTSP_LAUNCH("irfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, spec, sstride, n, C,
-                 out, t, aligned);
+                 out, t, aligned, gain);
     return hipGetLastError();
 }
 
@@ -954,7 +955,8 @@ hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float
 }
 
 template <int LOGN1>
-hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Tables t, int aligned, hipStream_t s)
+hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Tables t, int aligned, float gain,
+                 hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN1)) * sizeof(float2);
     auto kern = k_inv_a<LOGN1>;
@@ -964,7 +966,7 @@ hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Ta
     const int glog = logM - kLogE >= kGroupLog ? kGroupLog : 1;
     const Grid g = grouped_grid(total >> glog, glog);
     FFTSP_LAUNCH("irfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, out, n, t, aligned,
-                 (uint32_t)(total >> glog), g.per_wg, glog);
+                 (uint32_t)(total >> glog), g.per_wg, glog, gain);
     return hipGetLastError();
 }
 
@@ -1036,7 +1038,7 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
 }
 
 hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
-                        Tables t, int pair_spec, hipStream_t s)
+                        Tables t, int pair_spec, float gain, hipStream_t s)
 {
     const int logM = logL - 1;
     const uintptr_t addr = reinterpret_cast<uintptr_t>(out);
@@ -1045,7 +1047,7 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
     if (C * ((size_t)1 << (logM > 13 ? logM - 13 : 0)) > 0x7fffffffu) return hipErrorInvalidValue;
     switch (logM) {
 #define X(p) \
-    case p: return small_inv<p>(sp, sstride, n, C, out, t, aligned & 1, s);
+    case p: return small_inv<p>(sp, sstride, n, C, out, t, aligned & 1, gain, s);
         FFTSP_SMALL_CASES(X)
 #undef X
         default: break;
@@ -1071,11 +1073,11 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
     }
     if (e != hipSuccess) return e;
     switch (logN1) {
-        case 7: return inv_a<7>(mid, logM, C, out, n, t, aligned, s);
-        case 8: return inv_a<8>(mid, logM, C, out, n, t, aligned, s);
-        case 9: return inv_a<9>(mid, logM, C, out, n, t, aligned, s);
-        case 10: return inv_a<10>(mid, logM, C, out, n, t, aligned, s);
-        case 11: return inv_a<11>(mid, logM, C, out, n, t, aligned, s);
+        case 7: return inv_a<7>(mid, logM, C, out, n, t, aligned, gain, s);
+        case 8: return inv_a<8>(mid, logM, C, out, n, t, aligned, gain, s);
+        case 9: return inv_a<9>(mid, logM, C, out, n, t, aligned, gain, s);
+        case 10: return inv_a<10>(mid, logM, C, out, n, t, aligned, gain, s);
+        case 11: return inv_a<11>(mid, logM, C, out, n, t, aligned, gain, s);
         default: return hipErrorInvalidValue;
     }
 }

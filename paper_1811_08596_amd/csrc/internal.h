@@ -43,6 +43,18 @@ struct Workspace {
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Several senders' packed streams decoded into one spectrum (receiver under an allgather).
+constexpr int kMaxPeers = 32;
+struct PeerList {
+    const uint8_t* p[kMaxPeers];  // first record of each peer's stream
+};
+// Extra workspace behind the ordinary one: per peer the group prefixes of its bitmaps and its header verdicts.
+struct PeerWorkspace {
+    size_t prefix;  // u32[P][C][ceil(W/16)]
+    size_t verd;    // u32[P][C]
+    size_t total;   // end of the whole workspace
+};
+
 static inline uint32_t tiles_per_chunk(uint32_t L) { return ((L / 2 + 1) + kTile - 1) / kTile; }
 // chunk stride of the codec's own spectrum buffer, in complex bins: L/2+1 rounded up to a 128-byte multiple
 static inline uint32_t padded_bins(uint32_t L) { return (L / 2 + 1 + 15u) & ~15u; }
@@ -110,9 +122,9 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
                        int* pair_log, hipStream_t s);
 // log2(N1) of the two-pass factorisation for chunk length 2^logL, 0 for single-workgroup sizes
 int fft_pair_log(int logL);
-// pair_spec != 0: the spectrum is in paired order (two-pass sizes only)
+// pair_spec != 0: the spectrum is in paired order (two-pass sizes only); the output is gain/L times the plain sum
 hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
-                        Tables t, int pair_spec, hipStream_t s);
+                        Tables t, int pair_spec, float gain, hipStream_t s);
 
 // Codec launchers (codec.hip).
 struct CodecArgs {
@@ -130,6 +142,17 @@ struct CodecArgs {
     uint32_t hdr_L, hdr_C, hdr_k, hdr_S;
     float hdr_theta;
 };
+static inline PeerWorkspace make_peer_workspace(const Workspace& w, size_t C, uint32_t L, int npeers)
+{
+    PeerWorkspace pw;
+    const size_t B = (size_t)L / 2 + 1, W = (B + 31) / 32, G = (W + 15) / 16;
+    size_t off = w.total;
+    pw.prefix = off; off = align256(off + (size_t)npeers * C * G * 4);
+    pw.verd = off;   off = align256(off + (size_t)npeers * C * 4);
+    pw.total = off;
+    return pw;
+}
+
 // hist_ready != 0: the status words are cleared and the per-chunk histograms already hold the keys' top digit
 hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
                          uint8_t* ws_base, const Workspace& w, int hist_ready, hipStream_t s);
@@ -137,5 +160,9 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
 // reset_status != 0: this call also clears the device status word (first record set of a stream)
 hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
                          uint8_t* ws_base, const Workspace& w, int check_header, int reset_status, hipStream_t s);
+
+// npeers streams (each: 64-byte header + records) summed bin by bin, in list order, into spec; clears the status word
+hipError_t launch_decode_peers(const PeerList& streams, int npeers, const CodecArgs& a, float* spec, uint8_t* ws_base,
+                               const Workspace& w, const PeerWorkspace& pw, hipStream_t s);
 
 }  // namespace fftsp

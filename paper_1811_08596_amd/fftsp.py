@@ -26,6 +26,13 @@ SIGNATURES = {
                                  C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_decompress": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fftsp_workspace_bytes_accumulate": (C.c_size_t, [C.c_size_t, C.c_uint32, C.c_int, C.c_int]),
+    "fftsp_decompress_accumulate": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_size_t, C.c_float, C.c_void_p,
+                                              C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_void_p, C.c_size_t,
+                                              C.c_void_p]),
+    "fftsp_decode_accumulate_spectrum": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_size_t, C.c_size_t, C.c_uint32,
+                                                   C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
+                                                   C.c_void_p]),
     "fftsp_rfft": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_irfft": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_encode_spectrum": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_void_p,
@@ -139,6 +146,31 @@ def compress(grad, chunk_len: int, theta: float, bits: int, packed, workspace, s
 def decompress(packed, packed_nbytes: int, grad_out, chunk_len: int, theta: float, bits: int, workspace, stream=None):
     _check(load().fftsp_decompress(_ptr(packed), packed_nbytes, _ptr(grad_out), grad_out.numel(), chunk_len, theta,
                                    bits, _ptr(workspace), _nbytes(workspace), _stream(stream)), "fftsp_decompress")
+
+
+def workspace_bytes_accumulate(n: int, chunk_len: int, bits: int, npeers: int) -> int:
+    return load().fftsp_workspace_bytes_accumulate(n, chunk_len, bits, npeers)
+
+
+def _peer_array(packed_list):
+    return (C.c_void_p * len(packed_list))(*[_ptr(p) for p in packed_list])
+
+
+def decompress_accumulate(packed_list, packed_nbytes: int, scale: float, grad_out, chunk_len: int, theta: float,
+                          bits: int, workspace, stream=None):
+    """grad_out = scale * iFFT(sum of the peers' decoded spectra); packed_list: equally long device buffers."""
+    _check(load().fftsp_decompress_accumulate(_peer_array(packed_list), len(packed_list), packed_nbytes, scale,
+                                              _ptr(grad_out), grad_out.numel(), chunk_len, theta, bits,
+                                              _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "fftsp_decompress_accumulate")
+
+
+def decode_accumulate_spectrum(packed_list, packed_nbytes: int, n: int, chunk_len: int, theta: float, bits: int, spec,
+                               workspace, stream=None):
+    _check(load().fftsp_decode_accumulate_spectrum(_peer_array(packed_list), len(packed_list), packed_nbytes, n,
+                                                   chunk_len, theta, bits, _ptr(spec), _ptr(workspace),
+                                                   _nbytes(workspace), _stream(stream)),
+           "fftsp_decode_accumulate_spectrum")
 
 
 def rfft(grad, chunk_len: int, spec, workspace, stream=None):

@@ -89,6 +89,23 @@ class Device:
         res = out.cpu().numpy()
         return (res, st) if want_status else res
 
+    def decode_accumulate(self, packed_list, n, L, theta, bits):
+        pds = [self.to_dev(np.asarray(p, np.uint8)) for p in packed_list]
+        C = (n + L - 1) // L
+        spec = self.torch.full((C * (L + 2),), float("nan"), dtype=self.torch.float32, device=self.dev)
+        ws = self.workspace(self.f.workspace_bytes_accumulate(n, L, bits, len(pds)))
+        self.f.decode_accumulate_spectrum(pds, pds[0].numel(), n, L, theta, bits, spec, ws)
+        st = self.f.device_status(ws)
+        return spec.cpu().numpy(), st
+
+    def decompress_accumulate(self, packed_list, scale, n, L, theta, bits):
+        pds = [self.to_dev(np.asarray(p, np.uint8)) for p in packed_list]
+        out = self.torch.full((n,), float("nan"), dtype=self.torch.float32, device=self.dev)
+        ws = self.workspace(self.f.workspace_bytes_accumulate(n, L, bits, len(pds)))
+        self.f.decompress_accumulate(pds, pds[0].numel(), scale, out, L, theta, bits, ws)
+        st = self.f.device_status(ws)
+        return out.cpu().numpy(), st
+
     def compress_segments(self, g, offs, theta, bits):
         gd = self.to_dev(g.astype(np.float32))
         nb = self.f.packed_bytes_segments(offs, theta, bits)

@@ -84,6 +84,22 @@ def test_argument_errors_come_back_before_any_launch(lib):
     rc = lib.fftsp_decompress(a, fftsp.packed_bytes(100, 64, 0.5, 8) - 1, a, 100, 64, 0.5, 8, a, 1 << 30, None)
     assert rc == fftsp.EFORMAT
     assert fftsp.packed_bytes(0, 64, 0.5, 8) == 0 and fftsp.workspace_bytes(10, 63, 8) == 0
+    # several peers: list checks
+    peers = (C.c_void_p * 2)(a, a)
+    nb, wsb = fftsp.packed_bytes(100, 64, 0.5, 8), fftsp.workspace_bytes_accumulate(100, 64, 8, 2)
+    assert wsb > fftsp.workspace_bytes(100, 64, 8)
+    acc = lambda **kw: lib.fftsp_decompress_accumulate(kw.get("lst", peers), kw.get("np", 2), kw.get("nb", nb),
+                                                       kw.get("scale", 0.5), a, 100, 64, 0.5, 8, a,
+                                                       kw.get("wsb", wsb), None)
+    assert acc(np=0) == fftsp.EINVAL
+    assert acc(lst=None) == fftsp.EINVAL
+    assert acc(np=33, lst=(C.c_void_p * 33)(*([a] * 33))) == fftsp.EUNSUPPORTED
+    assert acc(lst=(C.c_void_p * 2)(a, None)) == fftsp.EINVAL
+    assert acc(lst=(C.c_void_p * 2)(a, a + 8)) == fftsp.EINVAL
+    assert acc(scale=float("nan")) == fftsp.EINVAL
+    assert acc(nb=nb - 1) == fftsp.EFORMAT
+    assert acc(wsb=wsb - 1) == fftsp.EWORKSPACE
+    assert fftsp.workspace_bytes_accumulate(100, 64, 8, 0) == 0 and fftsp.workspace_bytes_accumulate(100, 64, 8, 33) == 0
     # segments
     arr = (C.c_size_t * 3)(0, 10, 10)
     assert lib.fftsp_compress_segments(a, arr, 2, 0.5, 8, a, 1 << 20, a, 1 << 30, None) == fftsp.EINVAL

@@ -71,6 +71,25 @@ def test_config3_all_chunks(dev, ref, alexnet):
         assert st == 0 and rel_l2(out_gpu, ref.irfft(dec_or, n, L, nthreads=THREADS)) <= TOL
 
 
+def test_config3_four_peers_accumulated(dev, ref, alexnet):
+    """Receiver under an allgather at the benchmark size: four peers' AlexNet-shaped gradients, one inverse."""
+    w = alexnet
+    L, bits, theta, n = w.chunk_len, w.bits, 0.5, w.grad.size
+    pks = []
+    for p in range(4):
+        print(f"config3 x4 peers: oracle compress peer {p}", flush=True)
+        g = np.roll(w.grad, 1000003 * p) * np.float32(1.0 + 0.25 * p)
+        pks.append(ref.compress(g, L, theta, bits, nthreads=THREADS))
+    print("config3 x4 peers: gpu", flush=True)
+    spec_gpu, st = dev.decode_accumulate(pks, n, L, theta, bits)
+    assert st == 0
+    spec_or = ref.decode_accumulate_spectrum(pks, n, L, theta, bits, nthreads=THREADS)
+    assert np.array_equal(spec_gpu.view(np.uint32), spec_or.view(np.uint32))
+    out_gpu, st = dev.decompress_accumulate(pks, 0.25, n, L, theta, bits)
+    out_or = ref.decompress_accumulate(pks, 0.25, n, L, theta, bits, nthreads=THREADS)
+    assert st == 0 and rel_l2(out_gpu, out_or) <= TOL
+
+
 def test_config4_segments(dev, ref):
     w = workloads.config4()
     offs = w.seg_offsets
