@@ -187,6 +187,16 @@ def main() -> int:
                          "end-to-end training speedup 2.26x on 8x P100 + 56 Gb/s IB (Table 2)",
     }
 
+    # Sec. 3.3, Eq. 4 with the two directions as measured here: smallest compression ratio that pays on a link,
+    # and the link speed from which no ratio pays (this run's ratio is compression_ratio above)
+    from paper_1811_08596_amd import sensitivity
+    T_c, T_d = 4.0 * n / t_c / 1e9, 4.0 * n / t_d / 1e9
+    links = {"100GbE_12.5GBps": 12.5, "400GbE_50GBps": 50.0, "xGMI_link_153GBps": 153.0}
+    result["min_useful_ratio_eq4"] = {name: (round(sensitivity.min_useful_ratio_measured(bw, T_c, T_d), 3)
+                                             if sensitivity.min_useful_ratio_measured(bw, T_c, T_d) != float("inf")
+                                             else None) for name, bw in links.items()}
+    result["break_even_link_GBps"] = round(sensitivity.break_even_link(T_c, T_d), 1)
+
     # receiver under an allgather: eight peers' streams summed in the spectrum, one inverse transform
     # (extra keys; the headline above is one compress + one decompress)
     peers = 8
