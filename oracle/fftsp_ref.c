@@ -422,7 +422,7 @@ static uint32_t get_bits(const uint8_t* stream, uint64_t pos, int nbits)
  *          re0, im0, re1, im1, ... by ascending kept bin
  * `rec` must have `stride` bytes. */
 static int encode_chunk(const float* spec, uint32_t L, uint32_t k, int bits, int m, uint32_t word3, uint8_t* rec,
-                        size_t stride)
+                        size_t stride, uint32_t fixed_vmax)
 {
     uint32_t B = L / 2 + 1;
     size_t W = ((size_t)B + 31) / 32;
@@ -449,6 +449,9 @@ static int encode_chunk(const float* spec, uint32_t L, uint32_t k, int bits, int
         if (a > vmax) vmax = a;
         if (b > vmax) vmax = b;
     }
+    /* static range (Sec. 3.2.1: max estimated beforehand): the range no longer follows the survivors; whatever
+       exceeds it is clamped to the top code by 32bit_to_Nbit */
+    if (fixed_vmax) vmax = fixed_vmax;
     uint32_t pbase = fftsp_ref_pbase(vmax, bits, m);
 
     memset(rec, 0, stride);
@@ -492,27 +495,44 @@ static int decode_chunk(const uint8_t* rec, uint32_t L, uint32_t k, int bits, in
     return rank == k ? REF_OK : REF_EFORMAT;
 }
 
-int fftsp_ref_encode_spectrum(const float* spec, size_t n, uint32_t L, float theta, int bits, uint8_t* packed,
-                              size_t cap, int nthreads)
+/* Quantizer options of Sec. 3.2.1 that the plain entry points fix: m (0 = the default for the width) and a static
+ * range [-range_max, +range_max] (0 = fitted per chunk to the largest surviving component). */
+static int quantizer_m(int bits, int m)
+{
+    if (m == 0 || bits == 32) return fftsp_ref_mantissa_bits(bits);
+    if (bits < 3 || bits > 16 || m < 1 || m > bits - 1) return -1;
+    return m;
+}
+
+int fftsp_ref_encode_spectrum_q(const float* spec, size_t n, uint32_t L, float theta, int bits, int m_opt,
+                                float range_max, uint8_t* packed, size_t cap, int nthreads)
 {
     uint32_t k;
-    int m = fftsp_ref_mantissa_bits(bits);
-    if (!spec || !packed || n == 0 || m < 0) return REF_EINVAL;
+    int m = quantizer_m(bits, m_opt);
+    if (!spec || !packed || n == 0 || m < 0 || !(range_max >= 0.0f) || isinf(range_max)) return REF_EINVAL;
     if (fftsp_ref_kept_per_chunk(L, theta, &k)) return REF_EINVAL;
     size_t S = fftsp_ref_record_stride(L, k, bits);
     long C = (long)chunk_count(n, L);
     if (cap < STREAM_HEADER_BYTES + (size_t)C * S) return REF_ENOSPC;
     write_stream_header(packed, n, L, (uint32_t)C, bits, m, k, (uint32_t)S, theta);
+    uint32_t fixed = range_max > 0.0f ? f2u(range_max) : 0u;
     int err = 0;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
     for (long c = 0; c < C; ++c) {
-        int e = encode_chunk(spec + (size_t)c * (L + 2), L, k, bits, m, 0, packed + STREAM_HEADER_BYTES + (size_t)c * S, S);
+        int e = encode_chunk(spec + (size_t)c * (L + 2), L, k, bits, m, 0, packed + STREAM_HEADER_BYTES + (size_t)c * S, S,
+                             fixed);
         if (e) {
 #pragma omp atomic write
             err = e;
         }
     }
     return err;
+}
+
+int fftsp_ref_encode_spectrum(const float* spec, size_t n, uint32_t L, float theta, int bits, uint8_t* packed,
+                              size_t cap, int nthreads)
+{
+    return fftsp_ref_encode_spectrum_q(spec, n, L, theta, bits, 0, 0.0f, packed, cap, nthreads);
 }
 
 static int check_stream_header(const uint8_t* p, size_t bytes, uint64_t n, uint32_t L, uint32_t C, int bits, int m,
@@ -526,11 +546,11 @@ static int check_stream_header(const uint8_t* p, size_t bytes, uint64_t n, uint3
     return REF_OK;
 }
 
-int fftsp_ref_decode_spectrum(const uint8_t* packed, size_t bytes, size_t n, uint32_t L, float theta, int bits,
-                              float* spec, int nthreads)
+int fftsp_ref_decode_spectrum_q(const uint8_t* packed, size_t bytes, size_t n, uint32_t L, float theta, int bits,
+                                int m_opt, float* spec, int nthreads)
 {
     uint32_t k;
-    int m = fftsp_ref_mantissa_bits(bits);
+    int m = quantizer_m(bits, m_opt);
     if (!spec || !packed || n == 0 || m < 0) return REF_EINVAL;
     if (fftsp_ref_kept_per_chunk(L, theta, &k)) return REF_EINVAL;
     size_t S = fftsp_ref_record_stride(L, k, bits);
@@ -550,32 +570,78 @@ int fftsp_ref_decode_spectrum(const uint8_t* packed, size_t bytes, size_t n, uin
     return err;
 }
 
+int fftsp_ref_decode_spectrum(const uint8_t* packed, size_t bytes, size_t n, uint32_t L, float theta, int bits,
+                              float* spec, int nthreads)
+{
+    return fftsp_ref_decode_spectrum_q(packed, bytes, n, L, theta, bits, 0, spec, nthreads);
+}
+
 /* sender: chunk -> real FFT -> top-k -> quantize -> pack */
-int fftsp_ref_compress(const float* g, size_t n, uint32_t L, float theta, int bits, uint8_t* packed, size_t cap,
-                       int nthreads)
+int fftsp_ref_compress_q(const float* g, size_t n, uint32_t L, float theta, int bits, int m_opt, float range_max,
+                         uint8_t* packed, size_t cap, int nthreads)
 {
     if (!g || !packed || n == 0 || L < 2 || !is_pow2(L)) return REF_EINVAL;
     size_t C = chunk_count(n, L);
     float* spec = (float*)malloc(sizeof(float) * C * ((size_t)L + 2));
     if (!spec) return REF_ENOSPC;
     int e = fftsp_ref_rfft(g, n, L, spec, nthreads);
-    if (!e) e = fftsp_ref_encode_spectrum(spec, n, L, theta, bits, packed, cap, nthreads);
+    if (!e) e = fftsp_ref_encode_spectrum_q(spec, n, L, theta, bits, m_opt, range_max, packed, cap, nthreads);
     free(spec);
     return e;
 }
 
+int fftsp_ref_compress(const float* g, size_t n, uint32_t L, float theta, int bits, uint8_t* packed, size_t cap,
+                       int nthreads)
+{
+    return fftsp_ref_compress_q(g, n, L, theta, bits, 0, 0.0f, packed, cap, nthreads);
+}
+
 /* receiver: unpack -> dequantize -> scatter -> inverse real FFT */
-int fftsp_ref_decompress(const uint8_t* packed, size_t bytes, float* out, size_t n, uint32_t L, float theta, int bits,
-                         int nthreads)
+int fftsp_ref_decompress_q(const uint8_t* packed, size_t bytes, float* out, size_t n, uint32_t L, float theta, int bits,
+                           int m_opt, int nthreads)
 {
     if (!out || !packed || n == 0 || L < 2 || !is_pow2(L)) return REF_EINVAL;
     size_t C = chunk_count(n, L);
     float* spec = (float*)malloc(sizeof(float) * C * ((size_t)L + 2));
     if (!spec) return REF_ENOSPC;
-    int e = fftsp_ref_decode_spectrum(packed, bytes, n, L, theta, bits, spec, nthreads);
+    int e = fftsp_ref_decode_spectrum_q(packed, bytes, n, L, theta, bits, m_opt, spec, nthreads);
     if (!e) e = fftsp_ref_irfft(spec, n, L, out, nthreads);
     free(spec);
     return e;
+}
+
+int fftsp_ref_decompress(const uint8_t* packed, size_t bytes, float* out, size_t n, uint32_t L, float theta, int bits,
+                         int nthreads)
+{
+    return fftsp_ref_decompress_q(packed, bytes, out, n, L, theta, bits, 0, nthreads);
+}
+
+/*
+ * The paper's way to the smallest representable number eps for a static range [-max, +max] (Sec. 3.2.1, last
+ * paragraph before Algorithm 1): start from some eps, convert the all-ones code (the most negative representable
+ * number) back to binary32 with it, and move eps down if that number lies beyond the range, up otherwise, until
+ * the positive and negative halves of the code space are both in use (P = 2^N / 2).  Done here as a bisection on
+ * eps's bit pattern; returns eps (0 if the arguments are invalid).  The codec itself does not iterate: the
+ * closed form in fftsp_ref_pbase must land on the same pbase, which is what the tests check.
+ */
+float fftsp_ref_tune_eps(float range_max, int bits, int m)
+{
+    if (bits < 3 || bits > 16 || m < 1 || m > bits - 1 || !(range_max > 0.0f) || isinf(range_max)) return 0.0f;
+    const uint32_t all_ones = (1u << bits) - 1u;
+    uint32_t lo = 1u << (23 - m), hi = f2u(range_max);     /* candidate eps patterns; pbase >= 1 */
+    if (hi < lo) return u2f(lo);
+    while (lo < hi) {
+        uint32_t mid = lo + (hi - lo + 1) / 2;
+        uint32_t pbase = mid >> (23 - m);                    /* init(): pbase = eps >> (23-m) */
+        float actual_min = u2f(fftsp_ref_dequantize(all_ones, pbase, bits, m));
+        /* the top code's pattern may run past the largest finite binary32: that is beyond any range */
+        uint64_t top_pattern = ((uint64_t)pbase + (all_ones >> 1) - 1u) << (23 - m);
+        if (top_pattern >= 0x7F800000u || actual_min < -range_max)
+            hi = mid - 1;                                    /* reaches beyond the range: decrease eps */
+        else
+            lo = mid;                                        /* still inside: eps may grow */
+    }
+    return u2f(lo);
 }
 
 /* ------------------------------------------------------------------------ */
@@ -675,7 +741,7 @@ int fftsp_ref_compress_segments(const float* g, const size_t* off, int nseg, flo
         fftsp_ref_kept_per_chunk(L, theta, &k);
         float* spec = (float*)malloc(sizeof(float) * ((size_t)L + 2));
         int e = spec ? rfft_chunk(g + off[i], size, L, spec) : REF_ENOSPC;
-        if (!e) e = encode_chunk(spec, L, k, bits, m, L, packed + rec_off[i], rec_off[i + 1] - rec_off[i]);
+        if (!e) e = encode_chunk(spec, L, k, bits, m, L, packed + rec_off[i], rec_off[i + 1] - rec_off[i], 0u);
         free(spec);
         if (e) {
 #pragma omp atomic write

@@ -56,6 +56,11 @@ def lib():
             "fftsp_ref_decode_spectrum": (C.c_int, [u8p, C.c_size_t, C.c_size_t, C.c_uint32, C.c_float, C.c_int, fp, C.c_int]),
             "fftsp_ref_compress": (C.c_int, [fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, u8p, C.c_size_t, C.c_int]),
             "fftsp_ref_decompress": (C.c_int, [u8p, C.c_size_t, fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int]),
+            "fftsp_ref_encode_spectrum_q": (C.c_int, [fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int, C.c_float, u8p, C.c_size_t, C.c_int]),
+            "fftsp_ref_decode_spectrum_q": (C.c_int, [u8p, C.c_size_t, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int, fp, C.c_int]),
+            "fftsp_ref_compress_q": (C.c_int, [fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int, C.c_float, u8p, C.c_size_t, C.c_int]),
+            "fftsp_ref_decompress_q": (C.c_int, [u8p, C.c_size_t, fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int, C.c_int]),
+            "fftsp_ref_tune_eps": (C.c_float, [C.c_float, C.c_int, C.c_int]),
             "fftsp_ref_decode_accumulate_spectrum": (C.c_int, [C.POINTER(u8p), C.c_int, C.c_size_t, C.c_size_t, C.c_uint32, C.c_float, C.c_int, fp, C.c_int]),
             "fftsp_ref_decompress_accumulate": (C.c_int, [C.POINTER(u8p), C.c_int, C.c_size_t, C.c_float, fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int]),
             "fftsp_ref_segment_length": (C.c_uint32, [C.c_size_t]),
@@ -213,6 +218,50 @@ def decompress(packed, n, L, theta, bits, nthreads=1):
     _chk(lib().fftsp_ref_decompress(pp, packed.size, out.ctypes.data_as(C.POINTER(C.c_float)), n, L,
                                     np.float32(theta), bits, nthreads), "decompress")
     return out
+
+
+# ---- quantizer options of Sec. 3.2.1: m (0 = default for the width), static range [-range_max, range_max] (0 = fitted)
+def encode_spectrum_q(spec, n, L, theta, bits, m=0, range_max=0.0, nthreads=1):
+    spec, sp = _f32(spec)
+    nb = packed_bytes(n, L, theta, bits)
+    if nb == 0:
+        raise OracleError(EINVAL, "encode_spectrum_q")
+    out = np.empty(nb, dtype=np.uint8)
+    _chk(lib().fftsp_ref_encode_spectrum_q(sp, n, L, np.float32(theta), bits, m, np.float32(range_max),
+                                           out.ctypes.data_as(C.POINTER(C.c_uint8)), nb, nthreads), "encode_spectrum_q")
+    return out
+
+
+def decode_spectrum_q(packed, n, L, theta, bits, m=0, nthreads=1):
+    packed, pp = _u8(packed)
+    spec = np.empty(n_chunks(n, L) * (L + 2), dtype=np.float32)
+    _chk(lib().fftsp_ref_decode_spectrum_q(pp, packed.size, n, L, np.float32(theta), bits, m,
+                                           spec.ctypes.data_as(C.POINTER(C.c_float)), nthreads), "decode_spectrum_q")
+    return spec
+
+
+def compress_q(g, L, theta, bits, m=0, range_max=0.0, nthreads=1):
+    g, gp = _f32(g)
+    nb = packed_bytes(g.size, L, theta, bits)
+    if nb == 0:
+        raise OracleError(EINVAL, "compress_q")
+    out = np.empty(nb, dtype=np.uint8)
+    _chk(lib().fftsp_ref_compress_q(gp, g.size, L, np.float32(theta), bits, m, np.float32(range_max),
+                                    out.ctypes.data_as(C.POINTER(C.c_uint8)), nb, nthreads), "compress_q")
+    return out
+
+
+def decompress_q(packed, n, L, theta, bits, m=0, nthreads=1):
+    packed, pp = _u8(packed)
+    out = np.empty(n, dtype=np.float32)
+    _chk(lib().fftsp_ref_decompress_q(pp, packed.size, out.ctypes.data_as(C.POINTER(C.c_float)), n, L,
+                                      np.float32(theta), bits, m, nthreads), "decompress_q")
+    return out
+
+
+def tune_eps(range_max, bits, m) -> float:
+    """The paper's iterative choice of eps for a static range (bisection on the most negative code)."""
+    return float(lib().fftsp_ref_tune_eps(np.float32(range_max), bits, m))
 
 
 def _peer_list(packed_list):
