@@ -85,6 +85,36 @@ int fftsp_decompress(const void* d_packed, size_t packed_bytes,
                      float* d_grad_out, size_t n, uint32_t chunk_len, float theta, int bits,
                      void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
 
+/* ---- quantizer options (Sec. 3.2.1: "we tune m and eps"; "manual setting of a representation range") ----
+ *
+ * The entry points above fix m from the code width and fit the range of every chunk to its largest surviving
+ * component.  The _q variants take both from the caller; quantizer == NULL means the defaults.
+ *   mantissa_bits: m, 1 .. bits-1 (ignored for bits = 32); 0 = fftsp_mantissa_bits(bits).
+ *   range_max:     > 0: static range [-range_max, +range_max] for every chunk, as in the paper's experiments
+ *                  (range estimated beforehand); components beyond it clamp to the top code (Algorithm 1) and no
+ *                  reduction over the survivors is needed.  0 = fitted per chunk.  Negative, infinite or NaN:
+ *                  FFTSP_EINVAL.
+ * eps is not an input: for a given range it is the closed form the paper's iterative tuning converges to.
+ * The receiver needs the same mantissa_bits (the stream header carries m and a mismatch raises FFTSP_EFORMAT);
+ * range_max is ignored there (every record carries its pbase). */
+typedef struct fftsp_quantizer {
+    int mantissa_bits;
+    float range_max;
+} fftsp_quantizer;
+
+int fftsp_compress_q(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits,
+                     void* d_packed, size_t packed_capacity, void* d_workspace, size_t workspace_bytes,
+                     const fftsp_quantizer* quantizer, fftsp_stream_t stream);
+int fftsp_decompress_q(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n, uint32_t chunk_len,
+                       float theta, int bits, void* d_workspace, size_t workspace_bytes,
+                       const fftsp_quantizer* quantizer, fftsp_stream_t stream);
+int fftsp_encode_spectrum_q(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits,
+                            void* d_packed, size_t packed_capacity, void* d_workspace, size_t workspace_bytes,
+                            const fftsp_quantizer* quantizer, fftsp_stream_t stream);
+int fftsp_decode_spectrum_q(const void* d_packed, size_t packed_bytes, size_t n, uint32_t chunk_len, float theta,
+                            int bits, float* d_spec, void* d_workspace, size_t workspace_bytes,
+                            const fftsp_quantizer* quantizer, fftsp_stream_t stream);
+
 /* ---- receiver under an allgather (Sec. 4, "Implementation": every worker collects the packed gradients of all
  *      peers; Sec. 3.1: the receiver applies the inverse steps) ----
  *

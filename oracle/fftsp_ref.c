@@ -27,8 +27,11 @@
  *     the lowest bin index.
  *   - sign-magnitude code space: top bit sign, low N-1 bits magnitude code c,
  *     c = 0 is exactly zero, c = 1 is eps (pbase), c = 2^(N-1)-1 holds the
- *     largest surviving component; eps is chosen in closed form from that
- *     largest component instead of by the paper's bisection on eps.
+ *     top of the range; eps is the closed form that the paper's iterative
+ *     tuning converges to (fftsp_ref_tune_eps implements the iteration and the
+ *     tests check that both give the same pbase).  The range is the largest
+ *     surviving component of the chunk by default, or the caller's static max
+ *     (the *_q entry points), above which values clamp as in Algorithm 1.
  *   - default mantissa width m as a function of N (see fftsp_ref_mantissa_bits).
  *   - the byte layout of the packed stream (see the comment above encode_chunk).
  *

@@ -165,6 +165,22 @@ CodecArgs codec_args(const Plan& p, float theta)
 
 int hip_status(hipError_t e) { return e == hipSuccess ? FFTSP_OK : FFTSP_EHIP; }
 
+// quantizer options (Sec. 3.2.1): a chosen m replaces the default of the width, a static range replaces the
+// per-chunk fit; q == nullptr keeps both defaults
+int apply_quantizer(Plan* p, const fftsp_quantizer* q, uint32_t* static_vmax)
+{
+    *static_vmax = 0;
+    if (!q) return FFTSP_OK;
+    if (q->mantissa_bits != 0 && p->bits != 32) {
+        if (q->mantissa_bits < 1 || q->mantissa_bits > p->bits - 1) return FFTSP_EINVAL;
+        p->m = q->mantissa_bits;
+    }
+    const float r = q->range_max;
+    if (!(r >= 0.0f) || std::isinf(r)) return FFTSP_EINVAL;
+    if (r > 0.0f) std::memcpy(static_vmax, &r, sizeof(uint32_t));
+    return FFTSP_OK;
+}
+
 }  // namespace
 }  // namespace fftsp
 
@@ -229,11 +245,14 @@ int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad
                                    0, 1.0f, reinterpret_cast<hipStream_t>(stream)));
 }
 
-int fftsp_encode_spectrum(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
-                          size_t packed_capacity, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+int fftsp_encode_spectrum_q(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                          size_t packed_capacity, void* d_workspace, size_t workspace_bytes, const fftsp_quantizer* quantizer, fftsp_stream_t stream)
 {
     Plan p;
     int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    uint32_t static_vmax = 0;
+    rc = apply_quantizer(&p, quantizer, &static_vmax);
     if (rc) return rc;
     if (!d_spec || !d_packed || !d_workspace || !aligned16(d_spec) || !aligned16(d_packed) || !aligned16(d_workspace))
         return FFTSP_EINVAL;
@@ -241,16 +260,28 @@ int fftsp_encode_spectrum(const float* d_spec, size_t n, uint32_t chunk_len, flo
     if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     uint8_t* out = static_cast<uint8_t*>(d_packed);
-    return hip_status(launch_encode(d_spec, codec_args(p, theta), out, out + kStreamHeader, ws, p.ws, 0,
+    CodecArgs a = codec_args(p, theta);
+    a.static_vmax = static_vmax;
+    return hip_status(launch_encode(d_spec, a, out, out + kStreamHeader, ws, p.ws, 0,
                                     reinterpret_cast<hipStream_t>(stream)));
 }
 
-int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, uint32_t chunk_len, float theta,
-                          int bits, float* d_spec, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+int fftsp_encode_spectrum(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                          size_t packed_capacity, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    return fftsp_encode_spectrum_q(d_spec, n, chunk_len, theta, bits, d_packed, packed_capacity, d_workspace, workspace_bytes, nullptr, stream);
+}
+
+int fftsp_decode_spectrum_q(const void* d_packed, size_t packed_bytes, size_t n, uint32_t chunk_len, float theta,
+                          int bits, float* d_spec, void* d_workspace, size_t workspace_bytes, const fftsp_quantizer* quantizer, fftsp_stream_t stream)
 {
     Plan p;
     int rc = make_plan(&p, n, chunk_len, &theta, &bits);
     if (rc) return rc;
+    uint32_t static_vmax = 0;
+    rc = apply_quantizer(&p, quantizer, &static_vmax);
+    if (rc) return rc;
+    (void)static_vmax;  // the receiver reads the range from the records; only m matters here
     if (!d_spec || !d_packed || !d_workspace || !aligned16(d_spec) || !aligned16(d_packed) || !aligned16(d_workspace))
         return FFTSP_EINVAL;
     if (packed_bytes < kStreamHeader + p.C * p.S) return FFTSP_EFORMAT;
@@ -262,11 +293,20 @@ int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, u
     return hip_status(e);
 }
 
-int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
-                   size_t packed_capacity, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, uint32_t chunk_len, float theta,
+                          int bits, float* d_spec, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    return fftsp_decode_spectrum_q(d_packed, packed_bytes, n, chunk_len, theta, bits, d_spec, d_workspace, workspace_bytes, nullptr, stream);
+}
+
+int fftsp_compress_q(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                   size_t packed_capacity, void* d_workspace, size_t workspace_bytes, const fftsp_quantizer* quantizer, fftsp_stream_t stream)
 {
     Plan p;
     int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    uint32_t static_vmax = 0;
+    rc = apply_quantizer(&p, quantizer, &static_vmax);
     if (rc) return rc;
     if (!d_grad || !d_packed || !d_workspace || !aligned16(d_grad) || !aligned16(d_packed) || !aligned16(d_workspace))
         return FFTSP_EINVAL;
@@ -280,6 +320,7 @@ int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float thet
     float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
     int hist_done = 0;
     CodecArgs a = codec_args(p, theta);
+    a.static_vmax = static_vmax;
     a.sstride = padded_bins(p.L);
     hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, a.sstride, reinterpret_cast<float2*>(ws + p.ws.mid), t,
                                reinterpret_cast<uint32_t*>(ws + p.ws.hist),
@@ -290,12 +331,22 @@ int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float thet
     return hip_status(e);
 }
 
-int fftsp_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n, uint32_t chunk_len,
-                     float theta, int bits, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                   size_t packed_capacity, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    return fftsp_compress_q(d_grad, n, chunk_len, theta, bits, d_packed, packed_capacity, d_workspace, workspace_bytes, nullptr, stream);
+}
+
+int fftsp_decompress_q(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n, uint32_t chunk_len,
+                     float theta, int bits, void* d_workspace, size_t workspace_bytes, const fftsp_quantizer* quantizer, fftsp_stream_t stream)
 {
     Plan p;
     int rc = make_plan(&p, n, chunk_len, &theta, &bits);
     if (rc) return rc;
+    uint32_t static_vmax = 0;
+    rc = apply_quantizer(&p, quantizer, &static_vmax);
+    if (rc) return rc;
+    (void)static_vmax;  // the receiver reads the range from the records; only m matters here
     if (!d_grad_out || !d_packed || !d_workspace || !aligned16(d_grad_out) || !aligned16(d_packed) ||
         !aligned16(d_workspace))
         return FFTSP_EINVAL;
@@ -315,6 +366,12 @@ int fftsp_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_ou
         e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
                          a.pair_log != 0, 1.0f, s);
     return hip_status(e);
+}
+
+int fftsp_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n, uint32_t chunk_len,
+                     float theta, int bits, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    return fftsp_decompress_q(d_packed, packed_bytes, d_grad_out, n, chunk_len, theta, bits, d_workspace, workspace_bytes, nullptr, stream);
 }
 
 /* ---------------- receiver under an allgather: several peers' streams, one inverse transform ---------------- */

@@ -317,7 +317,8 @@ struct HeaderInfo {
 // scan the tiles, find the survivors' largest component, write the record header and zero the
 // code words that two tiles will share.
 __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bits, int m, uint32_t W, size_t S,
-                                                uint32_t word3, uint32_t stage_cap, uint32_t* __restrict__ sel,
+                                                uint32_t word3, uint32_t stage_cap, uint32_t static_vmax,
+                                                uint32_t* __restrict__ sel,
                                                 const uint32_t* __restrict__ tinfo, uint32_t* __restrict__ tscan,
                                                 const uint2* __restrict__ cand, uint8_t* __restrict__ records,
                                                 uint8_t* __restrict__ stream, HeaderInfo hdr)
@@ -498,9 +499,11 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
         __syncthreads();
     }
 
-    // largest component over the survivors
+    // largest component over the survivors (not needed when the caller fixed the range: Sec. 3.2.1, static max)
     uint32_t vm = 0;  // per-lane running maximum, reduced once at the end
-    if (staged) {
+    if (static_vmax) {
+        // nothing to find
+    } else if (staged) {
         for (uint32_t t = tid; t < Tn; t += RT) {
             const uint32_t nc = tnc[t], o = toff[t], take = ttake[t];
             if (tdef[t]) vm = tvd[t] > vm ? tvd[t] : vm;
@@ -534,7 +537,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     if (lane == 0 && vm) atomicMax(&s_vmax, vm);
     __syncthreads();
 
-    const uint32_t vmax = s_vmax;
+    const uint32_t vmax = static_vmax ? static_vmax : s_vmax;
     uint32_t pbase = 0;
     if (bits != 32) {
         const int shift = 23 - m;
@@ -1176,7 +1179,7 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
         lds_set = true;
     }
     FFTSP_LAUNCH("resolve", k_resolve, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k, a.bits, a.m,
-                 W, a.S, a.word3, kStageCap, sel, tinfo, tscan, cand, records, stream_base, h);
+                 W, a.S, a.word3, kStageCap, a.static_vmax, sel, tinfo, tscan, cand, records, stream_base, h);
     FFTSP_LAUNCH("emit", k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
                        records);
     return hipGetLastError();

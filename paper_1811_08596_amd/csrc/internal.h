@@ -134,6 +134,7 @@ struct CodecArgs {
     int bits, m;        // code width, mantissa width
     size_t S;           // record stride in bytes
     uint32_t word3;     // 4th word of every record header
+    uint32_t static_vmax;  // != 0: bit pattern of the caller's fixed range maximum (instead of the largest survivor)
     uint32_t sstride;   // distance between consecutive chunks' spectra, in complex bins
     int pair_log;       // 0: spectrum in natural bin order; log2(N1): paired order (see spec_index)
     // stream header (written iff write_header)

@@ -17,6 +17,13 @@ OK, EINVAL, ENOSPC, EWORKSPACE, EUNSUPPORTED, EHIP, EFORMAT = range(7)
 
 # name -> (restype, argtypes); every symbol include/fftsp.h declares
 _szp = C.POINTER(C.c_size_t)
+class Quantizer(C.Structure):
+    """fftsp_quantizer: mantissa_bits (0 = default for the width), range_max (0 = fitted per chunk)."""
+    _fields_ = [("mantissa_bits", C.c_int), ("range_max", C.c_float)]
+
+
+_qp = C.POINTER(Quantizer)
+
 SIGNATURES = {
     "fftsp_kept_per_chunk": (C.c_int, [C.c_uint32, C.c_float, C.POINTER(C.c_uint32)]),
     "fftsp_mantissa_bits": (C.c_int, [C.c_int]),
@@ -26,6 +33,14 @@ SIGNATURES = {
                                  C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_decompress": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fftsp_compress_q": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_void_p, C.c_size_t,
+                                   C.c_void_p, C.c_size_t, _qp, C.c_void_p]),
+    "fftsp_decompress_q": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
+                                     C.c_void_p, C.c_size_t, _qp, C.c_void_p]),
+    "fftsp_encode_spectrum_q": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_void_p,
+                                          C.c_size_t, C.c_void_p, C.c_size_t, _qp, C.c_void_p]),
+    "fftsp_decode_spectrum_q": (C.c_int, [C.c_void_p, C.c_size_t, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
+                                          C.c_void_p, C.c_void_p, C.c_size_t, _qp, C.c_void_p]),
     "fftsp_workspace_bytes_accumulate": (C.c_size_t, [C.c_size_t, C.c_uint32, C.c_int, C.c_int]),
     "fftsp_decompress_accumulate": (C.c_int, [C.POINTER(C.c_void_p), C.c_int, C.c_size_t, C.c_float, C.c_void_p,
                                               C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_void_p, C.c_size_t,
@@ -146,6 +161,40 @@ def compress(grad, chunk_len: int, theta: float, bits: int, packed, workspace, s
 def decompress(packed, packed_nbytes: int, grad_out, chunk_len: int, theta: float, bits: int, workspace, stream=None):
     _check(load().fftsp_decompress(_ptr(packed), packed_nbytes, _ptr(grad_out), grad_out.numel(), chunk_len, theta,
                                    bits, _ptr(workspace), _nbytes(workspace), _stream(stream)), "fftsp_decompress")
+
+
+def compress_q(grad, chunk_len: int, theta: float, bits: int, packed, workspace, mantissa_bits=0, range_max=0.0,
+               stream=None):
+    q = Quantizer(mantissa_bits, range_max)  # kept alive until the call returns
+    _check(load().fftsp_compress_q(_ptr(grad), grad.numel(), chunk_len, theta, bits, _ptr(packed), _nbytes(packed),
+                                   _ptr(workspace), _nbytes(workspace), C.byref(q),
+                                   _stream(stream)), "fftsp_compress_q")
+
+
+def decompress_q(packed, packed_nbytes: int, grad_out, chunk_len: int, theta: float, bits: int, workspace,
+                 mantissa_bits=0, stream=None):
+    q = Quantizer(mantissa_bits, 0.0)  # kept alive until the call returns
+    _check(load().fftsp_decompress_q(_ptr(packed), packed_nbytes, _ptr(grad_out), grad_out.numel(), chunk_len, theta,
+                                     bits, _ptr(workspace), _nbytes(workspace),
+                                     C.byref(q), _stream(stream)), "fftsp_decompress_q")
+
+
+def encode_spectrum_q(spec, n: int, chunk_len: int, theta: float, bits: int, packed, workspace, mantissa_bits=0,
+                      range_max=0.0, stream=None):
+    q = Quantizer(mantissa_bits, range_max)  # kept alive until the call returns
+    _check(load().fftsp_encode_spectrum_q(_ptr(spec), n, chunk_len, theta, bits, _ptr(packed), _nbytes(packed),
+                                          _ptr(workspace), _nbytes(workspace),
+                                          C.byref(q), _stream(stream)),
+           "fftsp_encode_spectrum_q")
+
+
+def decode_spectrum_q(packed, packed_nbytes: int, n: int, chunk_len: int, theta: float, bits: int, spec, workspace,
+                      mantissa_bits=0, stream=None):
+    q = Quantizer(mantissa_bits, 0.0)  # kept alive until the call returns
+    _check(load().fftsp_decode_spectrum_q(_ptr(packed), packed_nbytes, n, chunk_len, theta, bits, _ptr(spec),
+                                          _ptr(workspace), _nbytes(workspace),
+                                          C.byref(q), _stream(stream)),
+           "fftsp_decode_spectrum_q")
 
 
 def workspace_bytes_accumulate(n: int, chunk_len: int, bits: int, npeers: int) -> int:

@@ -89,6 +89,38 @@ class Device:
         res = out.cpu().numpy()
         return (res, st) if want_status else res
 
+    def encode_q(self, spec, n, L, theta, bits, m=0, range_max=0.0):
+        sd = self.to_dev(np.asarray(spec, np.float32))
+        nb = self.f.packed_bytes(n, L, theta, bits)
+        packed = self.torch.full((nb,), 0xEE, dtype=self.torch.uint8, device=self.dev)
+        self.f.encode_spectrum_q(sd, n, L, theta, bits, packed, self.ws_for(n, L, bits), m, range_max)
+        self.sync()
+        return packed.cpu().numpy()
+
+    def decode_q(self, packed, n, L, theta, bits, m=0):
+        pd = self.to_dev(np.asarray(packed, np.uint8))
+        C = (n + L - 1) // L
+        spec = self.torch.full((C * (L + 2),), float("nan"), dtype=self.torch.float32, device=self.dev)
+        ws = self.ws_for(n, L, bits)
+        self.f.decode_spectrum_q(pd, pd.numel(), n, L, theta, bits, spec, ws, m)
+        return spec.cpu().numpy(), self.f.device_status(ws)
+
+    def compress_q(self, g, L, theta, bits, m=0, range_max=0.0):
+        n = g.size
+        gd = self.to_dev(g.astype(np.float32))
+        nb = self.f.packed_bytes(n, L, theta, bits)
+        packed = self.torch.full((nb,), 0xEE, dtype=self.torch.uint8, device=self.dev)
+        self.f.compress_q(gd, L, theta, bits, packed, self.ws_for(n, L, bits), m, range_max)
+        self.sync()
+        return packed.cpu().numpy()
+
+    def decompress_q(self, packed, n, L, theta, bits, m=0):
+        pd = self.to_dev(np.asarray(packed, np.uint8))
+        out = self.torch.full((n,), float("nan"), dtype=self.torch.float32, device=self.dev)
+        ws = self.ws_for(n, L, bits)
+        self.f.decompress_q(pd, pd.numel(), out, L, theta, bits, ws, m)
+        return out.cpu().numpy(), self.f.device_status(ws)
+
     def decode_accumulate(self, packed_list, n, L, theta, bits):
         pds = [self.to_dev(np.asarray(p, np.uint8)) for p in packed_list]
         C = (n + L - 1) // L
@@ -137,7 +169,7 @@ def per_chunk_rel_l2(a, b, C):
     return max(rel_l2(a[c], b[c]) for c in range(C))
 
 
-def explain_end_to_end(ref, packed_gpu, packed_or, spec_or, n, L, theta, bits):
+def explain_end_to_end(ref, packed_gpu, packed_or, spec_or, n, L, theta, bits, m=0):
     """End-to-end streams come from two different spectra (binary32 FFT on the GPU, double FFT rounded once in
     the oracle), so they may differ, but only in ways rounding explains:
       - a bin may be kept by one side only if its oracle key is within 2e-5 (relative) of the oracle's threshold key;
@@ -145,10 +177,10 @@ def explain_end_to_end(ref, packed_gpu, packed_or, spec_or, n, L, theta, bits):
     Returns (selection mismatches, code mismatches)."""
     C = (n + L - 1) // L
     B = L // 2 + 1
-    m = ref.mantissa_bits(bits)
     Xo = np.asarray(spec_or).reshape(C, L + 2).view(np.complex64)
-    Sg = ref.decode_spectrum(packed_gpu, n, L, theta, bits).reshape(C, L + 2).view(np.complex64)
-    So = ref.decode_spectrum(packed_or, n, L, theta, bits).reshape(C, L + 2).view(np.complex64)
+    Sg = ref.decode_spectrum_q(packed_gpu, n, L, theta, bits, m).reshape(C, L + 2).view(np.complex64)
+    So = ref.decode_spectrum_q(packed_or, n, L, theta, bits, m).reshape(C, L + 2).view(np.complex64)
+    m = m if m and bits != 32 else ref.mantissa_bits(bits)
     sel_mis = code_mis = 0
     for c in range(C):
         _, _, k, _, bg, _ = ref.record_fields(packed_gpu, L, c)

@@ -84,6 +84,12 @@ def test_argument_errors_come_back_before_any_launch(lib):
     rc = lib.fftsp_decompress(a, fftsp.packed_bytes(100, 64, 0.5, 8) - 1, a, 100, 64, 0.5, 8, a, 1 << 30, None)
     assert rc == fftsp.EFORMAT
     assert fftsp.packed_bytes(0, 64, 0.5, 8) == 0 and fftsp.workspace_bytes(10, 63, 8) == 0
+    # quantizer options
+    def cq(m, r, bits=8):
+        q = fftsp.Quantizer(m, r)
+        return lib.fftsp_compress_q(a, 100, 64, 0.5, bits, a, 1 << 20, a, 1 << 30, C.byref(q), None)
+    assert cq(8, 0.0) == fftsp.EINVAL and cq(-1, 0.0) == fftsp.EINVAL          # m must be 1..bits-1 (0 = default)
+    assert cq(0, -1.0) == fftsp.EINVAL and cq(0, float("inf")) == fftsp.EINVAL and cq(0, float("nan")) == fftsp.EINVAL
     # several peers: list checks
     peers = (C.c_void_p * 2)(a, a)
     nb, wsb = fftsp.packed_bytes(100, 64, 0.5, 8), fftsp.workspace_bytes_accumulate(100, 64, 8, 2)
