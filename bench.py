@@ -197,6 +197,21 @@ def main() -> int:
                                              else None) for name, bw in links.items()}
     result["break_even_link_GBps"] = round(sensitivity.break_even_link(T_c, T_d), 1)
 
+    # the paper's static-range quantizer setting (Sec. 4.2: range (-1, 1)) on the sender: no per-chunk maximum pass
+    st_steps = max(3, args.steps // 2)
+
+    def sender_ms(range_max):
+        for i in range(2):
+            fftsp.compress_q(gd[i % NSETS], L, args.theta, bits, packed[i % NSETS], ws, 0, range_max, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(st_steps):
+            fftsp.compress_q(gd[i % NSETS], L, args.theta, bits, packed[i % NSETS], ws, 0, range_max, stream)
+        torch.cuda.synchronize()
+        return round((time.perf_counter() - t0) / st_steps * 1e3, 4)
+
+    result["static_range_compress"] = {"range_max": 1.0, "ms": sender_ms(1.0), "fitted_range_ms": sender_ms(0.0)}
+
     # receiver under an allgather: eight peers' streams summed in the spectrum, one inverse transform
     # (extra keys; the headline above is one compress + one decompress)
     peers = 8
