@@ -732,8 +732,8 @@ __device__ __forceinline__ void group_prefix_chunk(const uint8_t* __restrict__ s
     const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
     if (tid == 0) s_carry = 0;
     __syncthreads();
-    for (uint32_t base = 0; base < G; base += RT) {
-        const uint32_t g = base + tid;
+    // set bits of one group of 16 words
+    auto group_count = [&](uint32_t g) {
         uint32_t cnt = 0;
         if (g < G) {
             const uint32_t w0 = g * GROUP_WORDS;
@@ -748,9 +748,17 @@ __device__ __forceinline__ void group_prefix_chunk(const uint8_t* __restrict__ s
                 for (uint32_t w = w0; w < W; ++w) cnt += (uint32_t)__popc(bitmap[w]);
             }
         }
+        return cnt;
+    };
+    // two adjacent groups per lane, so that the longest chunk (1025 groups) is one scan, not two
+    for (uint32_t base = 0; base < G; base += 2 * RT) {
+        const uint32_t g = base + 2 * (uint32_t)tid;
+        const uint32_t cnt0 = group_count(g), cnt1 = group_count(g + 1);
         const uint32_t carry = s_carry;
-        const uint32_t incl = block_scan_incl_1024(cnt, tmp);
-        if (g < G) gprefix[g] = carry + incl - cnt;
+        const uint32_t incl = block_scan_incl_1024(cnt0 + cnt1, tmp);
+        const uint32_t before = carry + incl - cnt0 - cnt1;
+        if (g < G) gprefix[g] = before;
+        if (g + 1 < G) gprefix[g + 1] = before + cnt0;
         __syncthreads();
         if (tid == RT - 1) s_carry = carry + incl;
         __syncthreads();
