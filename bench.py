@@ -70,6 +70,8 @@ def main() -> int:
     ap.add_argument("--bits", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time theta in {.1,.3,.7,.9} (extra keys)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the extra timings (static-range sender, eight-peer receiver): only the headline path runs")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is a single-GPU codec; there is no multi-GPU path to time (--gpus must be 1)",
@@ -197,48 +199,49 @@ def main() -> int:
                                              else None) for name, bw in links.items()}
     result["break_even_link_GBps"] = round(sensitivity.break_even_link(T_c, T_d), 1)
 
-    # the paper's static-range quantizer setting (Sec. 4.2: range (-1, 1)) on the sender: no per-chunk maximum pass
-    st_steps = max(3, args.steps // 2)
+    if not args.no_extras:
+        # the paper's static-range quantizer setting (Sec. 4.2: range (-1, 1)) on the sender: no per-chunk maximum pass
+        st_steps = max(3, args.steps // 2)
 
-    def sender_ms(range_max):
-        for i in range(2):
-            fftsp.compress_q(gd[i % NSETS], L, args.theta, bits, packed[i % NSETS], ws, 0, range_max, stream)
+        def sender_ms(range_max):
+            for i in range(2):
+                fftsp.compress_q(gd[i % NSETS], L, args.theta, bits, packed[i % NSETS], ws, 0, range_max, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(st_steps):
+                fftsp.compress_q(gd[i % NSETS], L, args.theta, bits, packed[i % NSETS], ws, 0, range_max, stream)
+            torch.cuda.synchronize()
+            return round((time.perf_counter() - t0) / st_steps * 1e3, 4)
+
+        result["static_range_compress"] = {"range_max": 1.0, "ms": sender_ms(1.0), "fitted_range_ms": sender_ms(0.0)}
+
+        # receiver under an allgather: eight peers' streams summed in the spectrum, one inverse transform
+        # (extra keys; the headline above is one compress + one decompress)
+        peers = 8
+        ws_acc = torch.empty(fftsp.workspace_bytes_accumulate(n, L, bits, peers), dtype=torch.uint8, device=dev)
+        peer_packed = []
+        for p in range(peers):
+            gp = torch.roll(gd[0], 1 + 104729 * (p + 1)).contiguous()
+            pk = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            fftsp.compress(gp, L, args.theta, bits, pk, ws, stream)
+            peer_packed.append(pk)
+            del gp
+        torch.cuda.synchronize()
+        acc_steps = max(3, args.steps // 2)
+        for _ in range(2):
+            fftsp.decompress_accumulate(peer_packed, nbytes, 1.0 / peers, out[0], L, args.theta, bits, ws_acc, stream)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i in range(st_steps):
-            fftsp.compress_q(gd[i % NSETS], L, args.theta, bits, packed[i % NSETS], ws, 0, range_max, stream)
+        for _ in range(acc_steps):
+            fftsp.decompress_accumulate(peer_packed, nbytes, 1.0 / peers, out[0], L, args.theta, bits, ws_acc, stream)
         torch.cuda.synchronize()
-        return round((time.perf_counter() - t0) / st_steps * 1e3, 4)
-
-    result["static_range_compress"] = {"range_max": 1.0, "ms": sender_ms(1.0), "fitted_range_ms": sender_ms(0.0)}
-
-    # receiver under an allgather: eight peers' streams summed in the spectrum, one inverse transform
-    # (extra keys; the headline above is one compress + one decompress)
-    peers = 8
-    ws_acc = torch.empty(fftsp.workspace_bytes_accumulate(n, L, bits, peers), dtype=torch.uint8, device=dev)
-    peer_packed = []
-    for p in range(peers):
-        gp = torch.roll(gd[0], 1 + 104729 * (p + 1)).contiguous()
-        pk = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-        fftsp.compress(gp, L, args.theta, bits, pk, ws, stream)
-        peer_packed.append(pk)
-        del gp
-    torch.cuda.synchronize()
-    acc_steps = max(3, args.steps // 2)
-    for _ in range(2):
-        fftsp.decompress_accumulate(peer_packed, nbytes, 1.0 / peers, out[0], L, args.theta, bits, ws_acc, stream)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(acc_steps):
-        fftsp.decompress_accumulate(peer_packed, nbytes, 1.0 / peers, out[0], L, args.theta, bits, ws_acc, stream)
-    torch.cuda.synchronize()
-    t_acc = (time.perf_counter() - t0) / acc_steps
-    assert fftsp.device_status(ws_acc) == 0
-    result["receiver_accumulate"] = {"peers": peers, "ms": round(t_acc * 1e3, 4),
-                                     "ms_if_decompressed_one_by_one": round(peers * t_d * 1e3, 4),
-                                     "packed_GBps_in": round(peers * nbytes / t_acc / 1e9, 2),
-                                     "gradient_GBps_equivalent": round(peers * 4.0 * n / t_acc / 1e9, 2)}
-    del peer_packed, ws_acc
+        t_acc = (time.perf_counter() - t0) / acc_steps
+        assert fftsp.device_status(ws_acc) == 0
+        result["receiver_accumulate"] = {"peers": peers, "ms": round(t_acc * 1e3, 4),
+                                         "ms_if_decompressed_one_by_one": round(peers * t_d * 1e3, 4),
+                                         "packed_GBps_in": round(peers * nbytes / t_acc / 1e9, 2),
+                                         "gradient_GBps_equivalent": round(peers * 4.0 * n / t_acc / 1e9, 2)}
+        del peer_packed, ws_acc
 
     if args.sweep:
         sweep = {}
