@@ -159,7 +159,10 @@ int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, u
 
 /* ---- per-tensor variant: segment i = d_grad[seg_offsets[i] .. seg_offsets[i+1]) is one chunk of
  *      L_i = max(32, next power of two >= its size); seg_offsets (nseg+1 entries, ascending) is on the HOST
- *      and is consumed before the call returns.  Sizes above 2^22 are FFTSP_EUNSUPPORTED. ---- */
+ *      and is consumed before the call returns.  Sizes above 2^22 are FFTSP_EUNSUPPORTED.
+ *      Records follow tensor order in the stream.  Tensors that pad to the same L_i run together as the chunks
+ *      of shared launches (up to 64 at a time), so the cost grows with the number of distinct lengths rather
+ *      than with the number of tensors; the workspace is sized for the largest such group. ---- */
 size_t fftsp_packed_bytes_segments(const size_t* seg_offsets, int nseg, float theta, int bits);
 size_t fftsp_workspace_bytes_segments(const size_t* seg_offsets, int nseg, int bits);
 int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int nseg, float theta, int bits,

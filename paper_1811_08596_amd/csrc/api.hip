@@ -2,6 +2,7 @@
 #include "../../include/fftsp.h"
 #include "internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -225,7 +226,7 @@ int fftsp_rfft(const float* d_grad, size_t n, uint32_t chunk_len, float* d_spec,
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     return hip_status(launch_rfft(d_grad, n, p.logL, p.C, d_spec, p.L / 2 + 1, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                                  nullptr, nullptr, 0, nullptr, 0, nullptr, reinterpret_cast<hipStream_t>(stream)));
+                                  nullptr, nullptr, 0, nullptr, 0, nullptr, nullptr, reinterpret_cast<hipStream_t>(stream)));
 }
 
 int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad_out, void* d_workspace,
@@ -242,7 +243,7 @@ int fftsp_irfft(const float* d_spec, size_t n, uint32_t chunk_len, float* d_grad
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     return hip_status(launch_irfft(d_spec, p.L / 2 + 1, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                                   0, 1.0f, reinterpret_cast<hipStream_t>(stream)));
+                                   0, 1.0f, nullptr, reinterpret_cast<hipStream_t>(stream)));
 }
 
 int fftsp_encode_spectrum_q(const float* d_spec, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
@@ -325,7 +326,7 @@ int fftsp_compress_q(const float* d_grad, size_t n, uint32_t chunk_len, float th
     hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, a.sstride, reinterpret_cast<float2*>(ws + p.ws.mid), t,
                                reinterpret_cast<uint32_t*>(ws + p.ws.hist),
                                reinterpret_cast<uint32_t*>(ws + p.ws.status),
-                               (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, &hist_done, 1, &a.pair_log, s);
+                               (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, &hist_done, 1, &a.pair_log, nullptr, s);
     if (e == hipSuccess)
         e = launch_encode(spec, a, out, out + kStreamHeader, ws, p.ws, hist_done, s);
     return hip_status(e);
@@ -364,7 +365,7 @@ int fftsp_decompress_q(const void* d_packed, size_t packed_bytes, float* d_grad_
     hipError_t e = launch_decode(in, in + kStreamHeader, a, spec, ws, p.ws, 1, 1, s);
     if (e == hipSuccess)
         e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                         a.pair_log != 0, 1.0f, s);
+                         a.pair_log != 0, 1.0f, nullptr, s);
     return hip_status(e);
 }
 
@@ -440,7 +441,7 @@ int fftsp_decompress_accumulate(const void* const* d_packed, int npeers, size_t 
     hipError_t e = launch_decode_peers(peers, npeers, a, spec, ws, p.ws, pw, s);
     if (e == hipSuccess)
         e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                         a.pair_log != 0, scale, s);
+                         a.pair_log != 0, scale, nullptr, s);
     return hip_status(e);
 }
 
@@ -467,16 +468,87 @@ size_t fftsp_packed_bytes_segments(const size_t* seg_offsets, int nseg, float th
     return total;
 }
 
+// Tensors that pad to the same chunk length L run as the chunks of one launch set, at most this many at a time
+// (the per-launch table holds kMaxTableChunks; long chunks are also capped at 2^26 samples per launch set so that the
+// workspace stays a small multiple of the largest tensor).
+static size_t batch_cap(uint32_t L)
+{
+    const size_t by_size = ((size_t)1 << 26) / L;
+    const size_t cap = by_size < (size_t)kMaxTableChunks ? by_size : (size_t)kMaxTableChunks;
+    return cap < 1 ? 1 : cap;
+}
+
+// One launch set of the per-tensor path: `count` tensors of padded length L.
+struct SegBatch {
+    uint32_t L;
+    size_t count;
+    ChunkTable tab;
+};
+
+// Groups the tensors by padded length (ascending) and cuts every group into launch sets.  Records keep tensor
+// order in the stream: tensor i's record starts rec_off[i] bytes after the stream header.
+static std::vector<SegBatch> plan_segments(const size_t* off, int nseg, float theta, int bits, bool with_tables)
+{
+    std::vector<uint32_t> len(nseg);
+    std::vector<size_t> rec_off(nseg);
+    std::vector<int> order(nseg);
+    size_t ro = 0;
+    for (int i = 0; i < nseg; ++i) {
+        len[i] = segment_length(off[i + 1] - off[i]);
+        rec_off[i] = ro;
+        if (with_tables) ro += record_stride(len[i], kept(len[i], theta), bits);
+        order[i] = i;
+    }
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return len[a] < len[b]; });
+    std::vector<SegBatch> out;
+    for (int j = 0; j < nseg; ++j) {
+        const int i = order[j];
+        if (out.empty() || out.back().L != len[i] || out.back().count == batch_cap(len[i])) {
+            out.emplace_back();
+            out.back().L = len[i];
+            out.back().count = 0;
+        }
+        SegBatch& b = out.back();
+        if (with_tables) {
+            b.tab.goff[b.count] = off[i];
+            b.tab.glen[b.count] = (uint32_t)(off[i + 1] - off[i]);
+            b.tab.roff[b.count] = rec_off[i];
+        }
+        ++b.count;
+    }
+    return out;
+}
+
 size_t fftsp_workspace_bytes_segments(const size_t* seg_offsets, int nseg, int bits)
 {
     if (segments_ok(seg_offsets, nseg) != FFTSP_OK || mantissa(bits) < 0) return 0;
     size_t best = 0;
-    for (int i = 0; i < nseg; ++i) {
-        const uint32_t L = segment_length(seg_offsets[i + 1] - seg_offsets[i]);
-        const size_t t = make_workspace(1, L).total;
+    for (const SegBatch& b : plan_segments(seg_offsets, nseg, 0.5f, bits, false)) {
+        const size_t t = make_workspace(b.count, b.L).total;
         best = t > best ? t : best;
     }
     return best;
+}
+
+static CodecArgs segment_args(const SegBatch& b, const size_t* seg_offsets, int nseg, float theta, int bits, int m)
+{
+    CodecArgs a{};
+    a.C = b.count;
+    a.L = b.L;
+    a.k = kept(b.L, theta);
+    a.bits = bits;
+    a.m = m;
+    a.S = record_stride(b.L, a.k, bits);
+    a.word3 = b.L;
+    a.sstride = padded_bins(b.L);
+    a.tab = &b.tab;
+    a.hdr_n = seg_offsets[nseg] - seg_offsets[0];
+    a.hdr_L = 0;
+    a.hdr_C = (uint32_t)nseg;
+    a.hdr_k = 0;
+    a.hdr_S = 0;
+    a.hdr_theta = theta;
+    return a;
 }
 
 int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int nseg, float theta, int bits,
@@ -496,36 +568,21 @@ int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int 
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     uint8_t* out = static_cast<uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    size_t rec_off = kStreamHeader;
-    for (int i = 0; i < nseg; ++i) {
-        const size_t size = seg_offsets[i + 1] - seg_offsets[i];
-        const uint32_t L = segment_length(size);
-        const Workspace w = make_workspace(1, L);
-        CodecArgs a{};
-        a.C = 1;
-        a.L = L;
-        a.k = kept(L, theta);
-        a.bits = bits;
-        a.m = m;
-        a.S = record_stride(L, a.k, bits);
-        a.word3 = L;
-        a.sstride = padded_bins(L);
-        a.write_header = (i == 0);
-        a.hdr_n = seg_offsets[nseg] - seg_offsets[0];
-        a.hdr_L = 0;
-        a.hdr_C = (uint32_t)nseg;
-        a.hdr_k = 0;
-        a.hdr_S = 0;
-        a.hdr_theta = theta;
+    const std::vector<SegBatch> batches = plan_segments(seg_offsets, nseg, theta, bits, true);
+    for (size_t bi = 0; bi < batches.size(); ++bi) {
+        const SegBatch& b = batches[bi];
+        const Workspace w = make_workspace(b.count, b.L);
+        CodecArgs a = segment_args(b, seg_offsets, nseg, theta, bits, m);
+        a.write_header = (bi == 0);
         float* spec = reinterpret_cast<float*>(ws + w.spec);
         int hist_done = 0;
-        hipError_t e = launch_rfft(d_grad + seg_offsets[i], size, log2_exact(L), 1, spec, a.sstride,
+        hipError_t e = launch_rfft(d_grad, 0, log2_exact(b.L), b.count, spec, a.sstride,
                                    reinterpret_cast<float2*>(ws + w.mid), t, reinterpret_cast<uint32_t*>(ws + w.hist),
                                    reinterpret_cast<uint32_t*>(ws + w.status),
-                                   (w.hist - w.status) / 4 + (size_t)kHistBins, &hist_done, 1, &a.pair_log, s);
-        if (e == hipSuccess) e = launch_encode(spec, a, out, out + rec_off, ws, w, hist_done, s);
+                                   (w.hist - w.status) / 4 + b.count * (size_t)kHistBins, &hist_done, 1, &a.pair_log,
+                                   &b.tab, s);
+        if (e == hipSuccess) e = launch_encode(spec, a, out, out + kStreamHeader, ws, w, hist_done, s);
         if (e != hipSuccess) return FFTSP_EHIP;
-        rec_off += a.S;
     }
     return FFTSP_OK;
 }
@@ -548,35 +605,19 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     const uint8_t* in = static_cast<const uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    // every segment uses the same status word; it is cleared once, by the first segment's kernels
-    size_t rec_off = kStreamHeader;
-    for (int i = 0; i < nseg; ++i) {
-        const size_t size = seg_offsets[i + 1] - seg_offsets[i];
-        const uint32_t L = segment_length(size);
-        const Workspace w = make_workspace(1, L);
-        CodecArgs a{};
-        a.C = 1;
-        a.L = L;
-        a.k = kept(L, theta);
-        a.bits = bits;
-        a.m = m;
-        a.S = record_stride(L, a.k, bits);
-        a.word3 = L;
-        a.sstride = padded_bins(L);
-        a.pair_log = fft_pair_log(log2_exact(L));
-        a.hdr_n = seg_offsets[nseg] - seg_offsets[0];
-        a.hdr_L = 0;
-        a.hdr_C = (uint32_t)nseg;
-        a.hdr_k = 0;
-        a.hdr_S = 0;
-        a.hdr_theta = theta;
+    // every launch set raises the same status word; it is cleared once, by the first set's kernels
+    const std::vector<SegBatch> batches = plan_segments(seg_offsets, nseg, theta, bits, true);
+    for (size_t bi = 0; bi < batches.size(); ++bi) {
+        const SegBatch& b = batches[bi];
+        const Workspace w = make_workspace(b.count, b.L);
+        CodecArgs a = segment_args(b, seg_offsets, nseg, theta, bits, m);
+        a.pair_log = fft_pair_log(log2_exact(b.L));
         float* spec = reinterpret_cast<float*>(ws + w.spec);
-        hipError_t e = launch_decode(in, in + rec_off, a, spec, ws, w, i == 0, i == 0, s);
+        hipError_t e = launch_decode(in, in + kStreamHeader, a, spec, ws, w, bi == 0, bi == 0, s);
         if (e == hipSuccess)
-            e = launch_irfft(spec, a.sstride, size, log2_exact(L), 1, d_grad_out + seg_offsets[i],
-                             reinterpret_cast<float2*>(ws + w.mid), t, a.pair_log != 0, 1.0f, s);
+            e = launch_irfft(spec, a.sstride, 0, log2_exact(b.L), b.count, d_grad_out,
+                             reinterpret_cast<float2*>(ws + w.mid), t, a.pair_log != 0, 1.0f, &b.tab, s);
         if (e != hipSuccess) return FFTSP_EHIP;
-        rec_off += a.S;
     }
     return FFTSP_OK;
 }

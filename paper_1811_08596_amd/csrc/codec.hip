@@ -304,6 +304,16 @@ __device__ __forceinline__ uint32_t block_scan_incl_1024(uint32_t v, uint32_t* t
     return x + add;
 }
 
+// byte offset of chunk c's record from the first record of the launch: c * S, or from the table in per-tensor launches
+template <bool TABLE>
+__device__ __forceinline__ size_t record_offset(const TableArg<TABLE>& tab, size_t c, size_t S)
+{
+    if constexpr (TABLE)
+        return (size_t)tab.t.roff[c];
+    else
+        return c * S;
+}
+
 constexpr int kStageBatch = 12;  // candidates per lane fetched in one go by k_resolve (12 Ki staged / 1024 lanes)
 
 struct HeaderInfo {
@@ -316,12 +326,13 @@ struct HeaderInfo {
 // One workgroup per chunk: finish the radix select on the candidates, break ties by bin order,
 // scan the tiles, find the survivors' largest component, write the record header and zero the
 // code words that two tiles will share.
+template <bool TABLE>
 __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bits, int m, uint32_t W, size_t S,
                                                 uint32_t word3, uint32_t stage_cap, uint32_t static_vmax,
                                                 uint32_t* __restrict__ sel,
                                                 const uint32_t* __restrict__ tinfo, uint32_t* __restrict__ tscan,
                                                 const uint2* __restrict__ cand, uint8_t* __restrict__ records,
-                                                uint8_t* __restrict__ stream, HeaderInfo hdr)
+                                                uint8_t* __restrict__ stream, HeaderInfo hdr, TableArg<TABLE> tab)
 {
     __shared__ uint32_t h[1024];
     __shared__ uint32_t tmp[RW];
@@ -544,7 +555,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
         const int64_t pb = (int64_t)(vmax >> shift) - (int64_t)((1u << (bits - 1)) - 2u);
         pbase = pb < 1 ? 1u : (uint32_t)pb;
     }
-    uint32_t* rec = reinterpret_cast<uint32_t*>(records + c * S);
+    uint32_t* rec = reinterpret_cast<uint32_t*>(records + record_offset<TABLE>(tab, c, S));
     if (tid == 0) {
         sel[c * 8 + 2] = tau;
         sel[c * 8 + 3] = quota;
@@ -589,9 +600,11 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
 
 // ------------------------------------------------------------------ emit ----
 // Per tile: flags, ranks, Algorithm 1 codes, bit-packing, bitmap words.
+template <bool TABLE>
 __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, uint32_t sstride, int pair_log, uint32_t B, uint32_t Tn, uint32_t W,
                                              int bits, int m, size_t S, const uint32_t* __restrict__ sel,
-                                             const uint32_t* __restrict__ tscan, uint8_t* __restrict__ records)
+                                             const uint32_t* __restrict__ tscan, uint8_t* __restrict__ records,
+                                             TableArg<TABLE> tab)
 {
     __shared__ uint32_t cw[kTile * 2 + 2];  // code words of this tile (bits = 32 worst case)
     __shared__ uint32_t bmw[kTile / 32];
@@ -694,7 +707,7 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
         }
     }
     __syncthreads();
-    uint32_t* rec = reinterpret_cast<uint32_t*>(records + c * S);
+    uint32_t* rec = reinterpret_cast<uint32_t*>(records + record_offset<TABLE>(tab, c, S));
     uint32_t* bitmap = rec + 4;
     uint32_t* codes = bitmap + W;
     if (tid < kTile / 32) {
@@ -775,15 +788,18 @@ __device__ __forceinline__ void group_prefix_chunk(const uint8_t* __restrict__ s
     }
 }
 
+template <bool TABLE>
 __global__ __launch_bounds__(RT) void k_group_prefix(const uint8_t* __restrict__ stream,
                                                      const uint8_t* __restrict__ records, size_t S, uint32_t W,
                                                      uint32_t k, uint32_t word3, HeaderInfo hdr,
                                                      uint32_t* __restrict__ gprefix, uint32_t* __restrict__ sel,
-                                                     uint32_t* __restrict__ status, int reset_status)
+                                                     uint32_t* __restrict__ status, int reset_status,
+                                                     TableArg<TABLE> tab)
 {
     const size_t c = blockIdx.x;
     const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
-    group_prefix_chunk(stream, records + c * S, c == 0, W, k, word3, hdr, gprefix + c * G, sel + c * 8 + 7);
+    group_prefix_chunk(stream, records + record_offset<TABLE>(tab, c, S), c == 0, W, k, word3, hdr, gprefix + c * G,
+                       sel + c * 8 + 7);
     // raised again by k_decode, which runs after this kernel
     if (threadIdx.x == 0 && reset_status && c == 0) status[0] = 0u;
 }
@@ -831,11 +847,12 @@ struct DecItem {
 // the one bin a partial tile may write past the chunk's last bin lands in the padding.
 // verd: header verdict of (peer, chunk) at verd[peer * C + chunk].
 // One stream.
-template <int NL, bool VEC>
+template <int NL, bool VEC, bool TABLE>
 __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
                                                uint32_t k, int bits, int m, uint32_t Tn, uint32_t total, size_t C,
                                                const uint32_t* __restrict__ gprefix, const uint32_t* __restrict__ sel,
-                                               uint32_t* __restrict__ status, float2* __restrict__ spec, uint32_t sstride, int pair_log)
+                                               uint32_t* __restrict__ status, float2* __restrict__ spec, uint32_t sstride, int pair_log,
+                                               TableArg<TABLE> tab)
 {
     constexpr int kWin = NL * 1024 + 32;  // bytes of LDS per wave: main window, tail, slack for the 3-word read
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -851,7 +868,9 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
     __shared__ __attribute__((aligned(16))) uint8_t cwin_all[4 * kWin];
     uint8_t* cwin = cwin_all + wave * kWin;
 
-    auto record_of = [&](uint32_t t) __attribute__((always_inline)) { return records + (size_t)(t / Tn) * S; };
+    auto record_of = [&](uint32_t t) __attribute__((always_inline)) {
+        return records + record_offset<TABLE>(tab, t / Tn, S);
+    };
     auto load_head = [&](uint32_t t, bool live) __attribute__((always_inline)) {
         if (!live) t = 0;
         const uint32_t* rec = reinterpret_cast<const uint32_t*>(record_of(t));
@@ -1181,15 +1200,28 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     constexpr uint32_t kStageCap = 12 * 1024;
     static bool lds_set = false;
     if (!lds_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_resolve),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_resolve<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kStageCap * sizeof(uint2)));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_resolve<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kStageCap * sizeof(uint2)));
         if (e != hipSuccess) return e;
         lds_set = true;
     }
-    FFTSP_LAUNCH("resolve", k_resolve, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k, a.bits, a.m,
-                 W, a.S, a.word3, kStageCap, a.static_vmax, sel, tinfo, tscan, cand, records, stream_base, h);
-    FFTSP_LAUNCH("emit", k_emit, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B, Tn, W, a.bits, a.m, a.S, sel, tscan,
-                       records);
+    if (a.tab && a.C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
+#define FFTSP_ENCODE_TAIL(TABLE)                                                                                       \
+    do {                                                                                                               \
+        FFTSP_LAUNCH("resolve", k_resolve<TABLE>, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k, \
+                     a.bits, a.m, W, a.S, a.word3, kStageCap, a.static_vmax, sel, tinfo, tscan, cand, records,         \
+                     stream_base, h, table_arg<TABLE>(a.tab));                                                         \
+        FFTSP_LAUNCH("emit", k_emit<TABLE>, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B,   \
+                     Tn, W, a.bits, a.m, a.S, sel, tscan, records, table_arg<TABLE>(a.tab));                           \
+    } while (0)
+    if (a.tab)
+        FFTSP_ENCODE_TAIL(true);
+    else
+        FFTSP_ENCODE_TAIL(false);
+#undef FFTSP_ENCODE_TAIL
     return hipGetLastError();
 }
 
@@ -1210,10 +1242,14 @@ static hipError_t launch_decode_kernel(const PeerList& recs, uint32_t npeers, co
             FFTSP_LAUNCH("decode", (k_decode_peers<NL, VEC>), dim3(grid), dim3(NT), 0, s, recs, npeers, a.S, B, W,  \
                          a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                                  \
                          reinterpret_cast<float2*>(spec), a.sstride, a.pair_log);                                  \
+        else if (a.tab)                                                                                            \
+            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, true>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W,    \
+                         a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                                  \
+                         reinterpret_cast<float2*>(spec), a.sstride, a.pair_log, table_arg<true>(a.tab));          \
         else                                                                                                       \
-            FFTSP_LAUNCH("decode", (k_decode<NL, VEC>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W, a.k,     \
-                         a.bits, a.m, Tn, total, a.C, gprefix, verd, status, reinterpret_cast<float2*>(spec),      \
-                         a.sstride, a.pair_log);                                                                   \
+            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W,   \
+                         a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                                  \
+                         reinterpret_cast<float2*>(spec), a.sstride, a.pair_log, table_arg<false>(a.tab));         \
     } while (0)
     const bool vec = a.sstride == padded_bins(a.L) && (reinterpret_cast<uintptr_t>(spec) & 15u) == 0;
     // code widths are 3..16 or 32 bits
@@ -1240,8 +1276,13 @@ hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, con
     if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
     HeaderInfo h{check_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
                  a.hdr_theta};
-    FFTSP_LAUNCH("group_prefix", k_group_prefix, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S, W, a.k,
-                 a.word3, h, gprefix, sel, status, reset_status);
+    if (a.tab && a.C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
+    if (a.tab)
+        FFTSP_LAUNCH("group_prefix", k_group_prefix<true>, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S,
+                     W, a.k, a.word3, h, gprefix, sel, status, reset_status, table_arg<true>(a.tab));
+    else
+        FFTSP_LAUNCH("group_prefix", k_group_prefix<false>, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S,
+                     W, a.k, a.word3, h, gprefix, sel, status, reset_status, table_arg<false>(a.tab));
     PeerList recs{};
     recs.p[0] = records;
     return launch_decode_kernel(recs, 1u, a, spec, gprefix, sel, status, false, s);

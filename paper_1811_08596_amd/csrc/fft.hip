@@ -194,6 +194,32 @@ __device__ __forceinline__ void store_pair(float* __restrict__ out, size_t gi, s
     }
 }
 
+// Where chunk c's samples live: elements [first, limit) of the gradient; pairs != 0 allows 8-byte accesses.
+struct Span {
+    size_t first, limit;
+    int pairs;
+};
+template <bool TABLE>
+__device__ __forceinline__ Span chunk_span(const TableArg<TABLE>& tab, size_t c, size_t C, size_t chunk_len, size_t n,
+                                           int aligned8)
+{
+    Span sp;
+    if constexpr (TABLE) {
+        if (c < C) {
+            sp.first = tab.t.goff[c];
+            sp.limit = sp.first + tab.t.glen[c];
+        } else {
+            sp.first = sp.limit = 0;
+        }
+        sp.pairs = aligned8 && !(sp.first & 1u);
+    } else {
+        sp.first = c * chunk_len;
+        sp.limit = n;
+        sp.pairs = aligned8;
+    }
+    return sp;
+}
+
 // X[k] from a = Z[k], b = Z[M-k], w = W_L^k   (0 < k < M)
 __device__ __forceinline__ float2 split_fwd(float2 a, float2 b, float2 w)
 {
@@ -213,9 +239,10 @@ __device__ __forceinline__ float2 split_inv(float2 a, float2 b, float2 w)
 
 // ------------------------------------------------------------------ small ---
 // M = 2^LOGM <= 2^13 complex points per chunk, 2^(LOGE-LOGM) chunks per workgroup.
-template <int LOGM, int LOGE, int NT>
+template <int LOGM, int LOGE, int NT, bool TABLE>
 __global__ __launch_bounds__(NT) void k_fwd_small(const float* __restrict__ in, size_t n, size_t C,
-                                                  float2* __restrict__ spec, uint32_t sstride, Tables tb, int aligned)
+                                                  float2* __restrict__ spec, uint32_t sstride, Tables tb, int aligned,
+                                                  TableArg<TABLE> tab)
 {
     constexpr int M = 1 << LOGM, LOGT = LOGE - LOGM, ELEMS = 1 << LOGE;
     extern __shared__ float2 smem[];
@@ -227,8 +254,8 @@ __global__ __launch_bounds__(NT) void k_fwd_small(const float* __restrict__ in, 
 #pragma unroll
     for (int q = 0; q < ELEMS / NT; ++q) {
         const int w = tid + q * NT, i = w & (M - 1), b = w >> LOGM;
-        const size_t gi = (c0 + b) * (size_t)(2 * M) + 2 * (size_t)i;
-        d[sw_idx<LOGT>(i, b)] = load_pair(in, gi, n, aligned);
+        const Span sp = chunk_span<TABLE>(tab, c0 + b, C, 2 * M, n, aligned);
+        d[sw_idx<LOGT>(i, b)] = load_pair(in, sp.first + 2 * (size_t)i, sp.limit, sp.pairs);
     }
     __syncthreads();
     run_fft<LOGM, LOGT, NT, false>(d, tw, tid);
@@ -249,9 +276,10 @@ __global__ __launch_bounds__(NT) void k_fwd_small(const float* __restrict__ in, 
     }
 }
 
-template <int LOGM, int LOGE, int NT>
+template <int LOGM, int LOGE, int NT, bool TABLE>
 __global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spec, uint32_t sstride, size_t n, size_t C,
-                                                  float* __restrict__ out, Tables tb, int aligned, float gain)
+                                                  float* __restrict__ out, Tables tb, int aligned, float gain,
+                                                  TableArg<TABLE> tab)
 {
     constexpr int M = 1 << LOGM, LOGT = LOGE - LOGM, ELEMS = 1 << LOGE;
     extern __shared__ float2 smem[];
@@ -282,9 +310,9 @@ __global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spe
 #pragma unroll
     for (int q = 0; q < ELEMS / NT; ++q) {
         const int w = tid + q * NT, i = w & (M - 1), b = w >> LOGM;
-        const size_t gi = (c0 + b) * (size_t)(2 * M) + 2 * (size_t)i;
+        const Span sp = chunk_span<TABLE>(tab, c0 + b, C, 2 * M, n, aligned);
         float2 v = d[sw_idx<LOGT>(i, b)];
-        store_pair(out, gi, n, aligned, make_float2(v.x * scale, v.y * scale));
+        store_pair(out, sp.first + 2 * (size_t)i, sp.limit, sp.pairs, make_float2(v.x * scale, v.y * scale));
     }
 }
 
@@ -402,10 +430,10 @@ __device__ __forceinline__ uint32_t mirror_row(uint32_t kp, uint32_t N1) { retur
 // 16-byte aligned: two columns per 16-byte load, no guards.  Otherwise every element is loaded under a guard
 // (ragged last chunk, unaligned tensors); the two variants are separate loops so that the guarded one does
 // not put branches between the fast one's loads and their use.
-template <int LOGN1, bool FAST>
+template <int LOGN1, bool FAST, bool TABLE>
 __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n, int logM, float2* __restrict__ mid,
                                           const Tables& tb, int aligned, uint32_t t, uint32_t tend, uint32_t tstep, float2* d,
-                                          const float2* tw, int tid0)
+                                          const float2* tw, int tid0, const TableArg<TABLE>& tab)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT;
@@ -420,10 +448,11 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
     float4 r[PER2];
     // live = false: the tile does not exist; the fast loads are still issued, all to one valid address
     auto load_tile = [&](uint32_t tile, int tid, bool live) {
-        const size_t cbase = (size_t)(tile / tiles) * (size_t)(2 * (size_t)M);
+        // every tile lies in a real chunk, so the span needs no chunk count
+        const Span sp = chunk_span<TABLE>(tab, tile / tiles, ~(size_t)0, 2 * (size_t)M, n, aligned & 1);
         const uint32_t col0 = tile_in_chunk(tile, tiles) << LOGT;
         if constexpr (FAST) {
-            const float4* src = live ? reinterpret_cast<const float4*>(in + cbase) + (col0 >> 1)
+            const float4* src = live ? reinterpret_cast<const float4*>(in + sp.first) + (col0 >> 1)
                                      : reinterpret_cast<const float4*>(tb.hi);
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
@@ -435,8 +464,8 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
                 const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
-                const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
-                r[q] = join(load_pair(in, gi, n, aligned & 1), load_pair(in, gi + 2, n, aligned & 1));
+                const size_t gi = sp.first + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
+                r[q] = join(load_pair(in, gi, sp.limit, sp.pairs), load_pair(in, gi + 2, sp.limit, sp.pairs));
             }
         }
     };
@@ -493,10 +522,11 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
 }
 
 // `aligned`: bit 0 = input is 8-byte aligned, bit 1 = 16-byte aligned.
-template <int LOGN1>
+template <int LOGN1, bool TABLE>
 __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, size_t n, int logM,
                                                float2* __restrict__ mid, Tables tb, int aligned, uint32_t total,
-                                               uint32_t per_wg, int glog, uint32_t* __restrict__ zero_ptr, uint32_t zero_words)
+                                               uint32_t per_wg, int glog, uint32_t* __restrict__ zero_ptr, uint32_t zero_words,
+                                               TableArg<TABLE> tab)
 {
     constexpr int NT = kNT, ELEMS = 1 << kLogE;
     // clears the status words and key histograms the next kernels of the sender accumulate into
@@ -509,11 +539,19 @@ __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, siz
     if (!grouped_run(total, per_wg, glog, t, tend)) return;
     load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
     const uint32_t tiles = (1u << logM) >> kLogE;  // tiles per chunk
-    const size_t last_chunk_end = ((size_t)((tend - 1) / tiles) + 1) << (logM + 1);
-    if ((aligned & 2) && last_chunk_end <= n)
-        fwd_a_run<LOGN1, true>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0);
+    bool fast = (aligned & 2) != 0;
+    if constexpr (TABLE) {
+        // every tensor this run touches fills its chunk and starts on a 16-byte boundary
+        for (uint32_t c = t / tiles; c <= (tend - 1) / tiles; ++c)
+            fast = fast && (tab.t.goff[c] & 3u) == 0 && tab.t.glen[c] == (2u << logM);
+    } else {
+        const size_t last_chunk_end = ((size_t)((tend - 1) / tiles) + 1) << (logM + 1);
+        fast = fast && last_chunk_end <= n;
+    }
+    if (fast)
+        fwd_a_run<LOGN1, true, TABLE>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0, tab);
     else
-        fwd_a_run<LOGN1, false>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0);
+        fwd_a_run<LOGN1, false, TABLE>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0, tab);
 }
 
 __device__ __forceinline__ uint32_t fft_key_of(float2 z)
@@ -767,10 +805,10 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
 
 // Inverse pass A: inverse N1-point FFTs over k1 for a tile of columns n2; writes the real samples.
 // `aligned`: bit 0 = output is 8-byte aligned, bit 1 = 16-byte aligned.
-template <int LOGN1>
+template <int LOGN1, bool TABLE>
 __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, int logM, float* __restrict__ out,
                                                size_t n, Tables tb, int aligned, uint32_t total, uint32_t per_wg, int glog,
-                                               float gain)
+                                               float gain, TableArg<TABLE> tab)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
@@ -813,9 +851,11 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
         const bool more = t + tstep < tend;
         load_tile(more ? t + tstep : t, tid, more);
         run_fft<LOGN1, LOGT, NT, true>(d, tw, tid);
-        const size_t cbase = (size_t)(t / tiles) * (size_t)(2 * (size_t)M);
+        const Span sp = chunk_span<TABLE>(tab, t / tiles, ~(size_t)0, 2 * (size_t)M, n, aligned & 1);
+        const size_t cbase = sp.first;
         const uint32_t col0 = tile_in_chunk(t, tiles) << LOGT;
-        if ((aligned & 2) && cbase + 2 * (size_t)M <= n) {  // whole chunk inside the output: no per-element guards
+        // whole chunk inside the output (per-tensor: the tensor fills its chunk, 16-byte aligned): no guards
+        if ((aligned & 2) && cbase + 2 * (size_t)M <= sp.limit && (!TABLE || (cbase & 3u) == 0)) {
             float4* dst = reinterpret_cast<float4*>(out + cbase) + (col0 >> 1);
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
@@ -829,8 +869,8 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
                 const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
                 const float4 v = lds_load2<LOGT>(d, n1, 2 * bp);
                 const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
-                store_pair(out, gi, n, aligned & 1, make_float2(v.x * scale, v.y * scale));
-                store_pair(out, gi + 2, n, aligned & 1, make_float2(v.z * scale, v.w * scale));
+                store_pair(out, gi, sp.limit, sp.pairs, make_float2(v.x * scale, v.y * scale));
+                store_pair(out, gi + 2, sp.limit, sp.pairs, make_float2(v.z * scale, v.w * scale));
             }
         }
         if (!more) break;
@@ -852,33 +892,33 @@ hipError_t set_lds(K kernel, size_t bytes)
                                (int)bytes);
 }
 
-template <int LOGM>
+template <int LOGM, bool TABLE>
 hipError_t small_fwd(const float* in, size_t n, size_t C, float2* spec, uint32_t sstride, Tables t, int aligned,
-                     hipStream_t s)
+                     const ChunkTable* tab, hipStream_t s)
 {
     constexpr int LOGE = LOGM >= 12 ? LOGM : 12;
     const size_t lds = ((size_t)(1 << LOGE) + (1 << LOGM)) * sizeof(float2);
-    auto kern = k_fwd_small<LOGM, LOGE, kSmallNT>;
+    auto kern = k_fwd_small<LOGM, LOGE, kSmallNT, TABLE>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
     FFTSP_LAUNCH("rfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, in, n, C, spec, sstride,
-                 t, aligned);
+                 t, aligned, table_arg<TABLE>(tab));
     return hipGetLastError();
 }
 
-template <int LOGM>
+template <int LOGM, bool TABLE>
 hipError_t small_inv(const float2* spec, uint32_t sstride, size_t n, size_t C, float* out, Tables t, int aligned,
-                     float gain, hipStream_t s)
+                     float gain, const ChunkTable* tab, hipStream_t s)
 {
     constexpr int LOGE = LOGM >= 12 ? LOGM : 12;
     const size_t lds = ((size_t)(1 << LOGE) + (1 << LOGM)) * sizeof(float2);
-    auto kern = k_inv_small<LOGM, LOGE, kSmallNT>;
+    auto kern = k_inv_small<LOGM, LOGE, kSmallNT, TABLE>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t per = (size_t)1 << (LOGE - LOGM);
     FFTSP_LAUNCH("irfft_small", kern, dim3((unsigned)((C + per - 1) / per)), dim3(kSmallNT), lds, s, spec, sstride, n, C,
-                 out, t, aligned, gain);
+                 out, t, aligned, gain, table_arg<TABLE>(tab));
     return hipGetLastError();
 }
 
@@ -909,19 +949,19 @@ Grid grouped_grid(size_t groups, int glog, uint32_t kMaxWgs = 512)
     return g;
 }
 
-template <int LOGN1>
+template <int LOGN1, bool TABLE>
 hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tables t, int aligned, uint32_t* zero_ptr,
-                 uint32_t zero_words, hipStream_t s)
+                 uint32_t zero_words, const ChunkTable* tab, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN1)) * sizeof(float2);
-    auto kern = k_fwd_a<LOGN1>;
+    auto kern = k_fwd_a<LOGN1, TABLE>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
     const int glog = logM - kLogE >= kGroupLog ? kGroupLog : 1;  // a chunk has 2^(logM-kLogE) >= 2 tiles
     const Grid g = grouped_grid(total >> glog, glog, 2048);  // measured: 143 us against 149 with 512
     FFTSP_LAUNCH("rfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, in, n, logM, mid, t, aligned,
-                 (uint32_t)(total >> glog), g.per_wg, glog, zero_ptr, zero_words);
+                 (uint32_t)(total >> glog), g.per_wg, glog, zero_ptr, zero_words, table_arg<TABLE>(tab));
     return hipGetLastError();
 }
 
@@ -954,19 +994,19 @@ hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float
     return hipGetLastError();
 }
 
-template <int LOGN1>
+template <int LOGN1, bool TABLE>
 hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Tables t, int aligned, float gain,
-                 hipStream_t s)
+                 const ChunkTable* tab, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN1)) * sizeof(float2);
-    auto kern = k_inv_a<LOGN1>;
+    auto kern = k_inv_a<LOGN1, TABLE>;
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
     const int glog = logM - kLogE >= kGroupLog ? kGroupLog : 1;
     const Grid g = grouped_grid(total >> glog, glog);
     FFTSP_LAUNCH("irfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, out, n, t, aligned,
-                 (uint32_t)(total >> glog), g.per_wg, glog, gain);
+                 (uint32_t)(total >> glog), g.per_wg, glog, gain, table_arg<TABLE>(tab));
     return hipGetLastError();
 }
 
@@ -985,9 +1025,10 @@ int fft_pair_log(int logL)
 
 hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, uint32_t sstride, float2* mid,
                        Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, int pair_spec,
-                       int* pair_log, hipStream_t s)
+                       int* pair_log, const ChunkTable* tab, hipStream_t s)
 {
     if (pair_log) *pair_log = 0;
+    if (tab && C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
     if (zero_words > 0xffffffffu) return hipErrorInvalidValue;
     if (!hist) zero_words = 0;
     const int logM = logL - 1;
@@ -998,7 +1039,9 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     if (C * ((size_t)1 << (logM > 13 ? logM - 13 : 0)) > 0x7fffffffu) return hipErrorInvalidValue;
     switch (logM) {
 #define X(p) \
-    case p: return small_fwd<p>(in, n, C, sp, sstride, t, aligned & 1, s);
+    case p: \
+        return tab ? small_fwd<p, true>(in, n, C, sp, sstride, t, aligned & 1, tab, s) \
+                   : small_fwd<p, false>(in, n, C, sp, sstride, t, aligned & 1, nullptr, s);
         FFTSP_SMALL_CASES(X)
 #undef X
         default: break;
@@ -1008,14 +1051,18 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     if ((hist != nullptr) != (pair_spec != 0)) return hipErrorInvalidValue;
     const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
     hipError_t e;
+#define FWD_A(p)                                                                              \
+    (tab ? fwd_a<p, true>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, tab, s)      \
+         : fwd_a<p, false>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, nullptr, s))
     switch (logN1) {
-        case 7: e = fwd_a<7>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
-        case 8: e = fwd_a<8>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
-        case 9: e = fwd_a<9>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
-        case 10: e = fwd_a<10>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
-        case 11: e = fwd_a<11>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, s); break;
+        case 7: e = FWD_A(7); break;
+        case 8: e = FWD_A(8); break;
+        case 9: e = FWD_A(9); break;
+        case 10: e = FWD_A(10); break;
+        case 11: e = FWD_A(11); break;
         default: return hipErrorInvalidValue;
     }
+#undef FWD_A
     if (e != hipSuccess) return e;
     if (hist_done) *hist_done = hist != nullptr;
     if (pair_log && pair_spec) *pair_log = logN1;
@@ -1038,8 +1085,9 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
 }
 
 hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
-                        Tables t, int pair_spec, float gain, hipStream_t s)
+                        Tables t, int pair_spec, float gain, const ChunkTable* tab, hipStream_t s)
 {
+    if (tab && C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
     const int logM = logL - 1;
     const uintptr_t addr = reinterpret_cast<uintptr_t>(out);
     const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
@@ -1047,7 +1095,9 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
     if (C * ((size_t)1 << (logM > 13 ? logM - 13 : 0)) > 0x7fffffffu) return hipErrorInvalidValue;
     switch (logM) {
 #define X(p) \
-    case p: return small_inv<p>(sp, sstride, n, C, out, t, aligned & 1, gain, s);
+    case p: \
+        return tab ? small_inv<p, true>(sp, sstride, n, C, out, t, aligned & 1, gain, tab, s) \
+                   : small_inv<p, false>(sp, sstride, n, C, out, t, aligned & 1, gain, nullptr, s);
         FFTSP_SMALL_CASES(X)
 #undef X
         default: break;
@@ -1072,14 +1122,18 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
         }
     }
     if (e != hipSuccess) return e;
+#define INV_A(p)                                                          \
+    (tab ? inv_a<p, true>(mid, logM, C, out, n, t, aligned, gain, tab, s) \
+         : inv_a<p, false>(mid, logM, C, out, n, t, aligned, gain, nullptr, s))
     switch (logN1) {
-        case 7: return inv_a<7>(mid, logM, C, out, n, t, aligned, gain, s);
-        case 8: return inv_a<8>(mid, logM, C, out, n, t, aligned, gain, s);
-        case 9: return inv_a<9>(mid, logM, C, out, n, t, aligned, gain, s);
-        case 10: return inv_a<10>(mid, logM, C, out, n, t, aligned, gain, s);
-        case 11: return inv_a<11>(mid, logM, C, out, n, t, aligned, gain, s);
+        case 7: return INV_A(7);
+        case 8: return INV_A(8);
+        case 9: return INV_A(9);
+        case 10: return INV_A(10);
+        case 11: return INV_A(11);
         default: return hipErrorInvalidValue;
     }
+#undef INV_A
 }
 
 }  // namespace fftsp

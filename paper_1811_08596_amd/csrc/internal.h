@@ -43,6 +43,31 @@ struct Workspace {
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
+// Per-tensor mode: the chunks of one launch are separate tensors of the same (padded) length, so where a chunk's
+// samples and its record live is a table instead of c*L and c*S.  The table travels by value as a kernel argument
+// (no host-to-device copy to order against the stream); longer lists are cut into launches of kMaxTableChunks.
+constexpr int kMaxTableChunks = 64;
+struct ChunkTable {
+    uint64_t goff[kMaxTableChunks];  // element offset of the chunk's first sample in the gradient
+    uint64_t roff[kMaxTableChunks];  // byte offset of the chunk's record from the first record of the launch
+    uint32_t glen[kMaxTableChunks];  // samples present; the rest of the chunk is zero
+};
+// kernel parameter that is a ChunkTable in per-tensor launches and nothing otherwise
+template <bool TABLE>
+struct TableArg {
+};
+template <>
+struct TableArg<true> {
+    ChunkTable t;
+};
+template <bool TABLE>
+inline TableArg<TABLE> table_arg(const ChunkTable* tab)
+{
+    TableArg<TABLE> a;
+    if constexpr (TABLE) a.t = *tab;
+    return a;
+}
+
 // Several senders' packed streams decoded into one spectrum (receiver under an allgather).
 constexpr int kMaxPeers = 32;
 struct PeerList {
@@ -117,14 +142,15 @@ hipError_t get_tables(Tables* out);
 // the status words) and fill hist, setting *hist_done = 1; otherwise the caller clears and fills it.
 // pair_spec != 0 asks the two-pass kernels to write the spectrum in paired order; *pair_log receives log2(N1)
 // if they did, 0 otherwise (single-workgroup sizes always write natural order).
+// tab != nullptr: per-tensor launch, chunk c is in[tab->goff[c] .. + tab->glen[c]) (n is not used)
 hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, uint32_t sstride, float2* mid,
                        Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, int pair_spec,
-                       int* pair_log, hipStream_t s);
+                       int* pair_log, const ChunkTable* tab, hipStream_t s);
 // log2(N1) of the two-pass factorisation for chunk length 2^logL, 0 for single-workgroup sizes
 int fft_pair_log(int logL);
 // pair_spec != 0: the spectrum is in paired order (two-pass sizes only); the output is gain/L times the plain sum
 hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
-                        Tables t, int pair_spec, float gain, hipStream_t s);
+                        Tables t, int pair_spec, float gain, const ChunkTable* tab, hipStream_t s);
 
 // Codec launchers (codec.hip).
 struct CodecArgs {
@@ -136,6 +162,7 @@ struct CodecArgs {
     uint32_t word3;     // 4th word of every record header
     uint32_t static_vmax;  // != 0: bit pattern of the caller's fixed range maximum (instead of the largest survivor)
     uint32_t sstride;   // distance between consecutive chunks' spectra, in complex bins
+    const ChunkTable* tab;  // per-tensor launches: where each chunk's record lives (host pointer); else nullptr
     int pair_log;       // 0: spectrum in natural bin order; log2(N1): paired order (see spec_index)
     // stream header (written iff write_header)
     int write_header;

@@ -199,6 +199,41 @@ def test_segments_match_per_tensor_chunks(dev, ref):
     assert rel_l2(out, ref.decompress_segments(por, offs, theta, bits, nthreads=8)) <= TOL
 
 
+@pytest.mark.parametrize("sizes, theta, bits", [
+    # one padded length many times over (more tensors than one launch takes), tiny tensors, odd offsets
+    ([40 + (i % 20) for i in range(150)] + [700, 64, 700, 1, 512, 3], 0.5, 5),
+    # two-pass lengths: tensors that fill their chunk at 16-byte offsets, ragged ones, and odd offsets, mixed in a class
+    ([32768, 32768, 5, 32768, 30000, 65536, 40000, 65536, 7, 131072, 131071, 2, 131072], 0.25, 8),
+    ([3, 65536, 65535, 1, 65536, 1 << 20, (1 << 20) - 1], 0.4, 32),
+])
+def test_segments_grouped_by_length(dev, ref, sizes, theta, bits):
+    """per-tensor mode runs the tensors of one padded length as the chunks of shared launches; every record
+    must still be what the uniform path makes of that tensor alone, at its place in tensor order"""
+    offs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    g = workloads.small_mixed(int(offs[-1]), seed=len(sizes))
+    packed = dev.compress_segments(g, offs, theta, bits)
+    assert packed.size == ref.packed_bytes_segments(offs, theta, bits)
+    pos = 64
+    for i, s in enumerate(sizes):
+        L = ref.segment_length(s)
+        # a tensor alone starts 16-byte aligned; inside the gradient it may not, which changes the load width only
+        one = dev.compress(g[offs[i]:offs[i + 1]], L, theta, bits)
+        S = one.size - 64
+        rec = packed[pos:pos + S].copy()
+        assert int(rec[12:16].view("<u4")[0]) == L
+        rec[12:16] = 0
+        assert np.array_equal(rec, one[64:]), f"tensor {i} (size {s})"
+        pos += S
+    assert pos == packed.size
+    por = ref.compress_segments(g, offs, theta, bits, nthreads=8)
+    out, st = dev.decompress_segments(por, offs, theta, bits)
+    assert st == 0
+    out_or = ref.decompress_segments(por, offs, theta, bits, nthreads=8)
+    for i in range(len(sizes)):
+        a, b = out[offs[i]:offs[i + 1]], out_or[offs[i]:offs[i + 1]]
+        assert rel_l2(a, b) <= TOL or not b.any(), f"tensor {i} (size {sizes[i]})"
+
+
 @pytest.mark.parametrize("logL", list(range(5, 23)))
 def test_every_chunk_length(dev, ref, logL):
     """one full chunk plus a ragged tail at every supported chunk length (all FFT kernel instantiations)"""
