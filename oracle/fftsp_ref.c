@@ -794,6 +794,160 @@ int fftsp_ref_decompress_segments(const uint8_t* packed, size_t bytes, float* ou
     return err;
 }
 
+/* ------------------------------------------------------------------------ */
+/* Time-domain Top-k: the sparsifier the paper measures its own against       */
+/* (Sec. 4, "Choice of Algorithms"; the right panel of the Sec. 3.1.1 figure   */
+/* that puts FFT Top-k beside direct Top-k).  The gradient samples themselves  */
+/* are thresholded by magnitude; nothing is transformed.  Readings: the same   */
+/* chunking, Algorithm 1 quantizer and bitmap/dense packing as the frequency   */
+/* path, so that the two differ in the transform alone; N = 32 is the paper's  */
+/* plain Top-k (values kept as binary32).                                      */
+/*   - unit of selection: one sample; rank key = bit pattern of |x| (exact     */
+/*     magnitude order); ties go to the lowest index; samples past the end of  */
+/*     the gradient are zeros that take part like any other zero.              */
+/*   - kept samples per chunk: round-half-up of theta * L (theta = KEPT        */
+/*     fraction, as everywhere in this interface).                             */
+/*   - record: +0 pbase | +4 vmax_bits | +8 k | +12 0 | bitmap ceil(L/32)     */
+/*     words | ONE code per kept sample, ascending index; stream header as     */
+/*     above with word 11 (offset 44) = 1 marking the time domain.             */
+/* ------------------------------------------------------------------------ */
+int fftsp_ref_topk_kept_per_chunk(uint32_t L, float theta, uint32_t* k_out)
+{
+    if (!k_out || L < 2 || !is_pow2(L) || !(theta >= 0.0f && theta <= 1.0f)) return REF_EINVAL;
+    double k = floor((double)theta * (double)L + 0.5);
+    if (k < 0) k = 0;
+    if (k > (double)L) k = (double)L;
+    *k_out = (uint32_t)k;
+    return REF_OK;
+}
+
+size_t fftsp_ref_topk_record_stride(uint32_t L, uint32_t k, int bits)
+{
+    size_t W = ((size_t)L + 31) / 32;
+    size_t code_words = ((size_t)k * (size_t)bits + 31) / 32;
+    return align16(16 + 4 * W + 4 * code_words);
+}
+
+size_t fftsp_ref_topk_packed_bytes(size_t n, uint32_t L, float theta, int bits)
+{
+    uint32_t k;
+    if (n == 0 || fftsp_ref_mantissa_bits(bits) < 0) return 0;
+    if (fftsp_ref_topk_kept_per_chunk(L, theta, &k)) return 0;
+    return STREAM_HEADER_BYTES + chunk_count(n, L) * fftsp_ref_topk_record_stride(L, k, bits);
+}
+
+static int topk_encode_chunk(const float* x, size_t valid, uint32_t L, uint32_t k, int bits, int m, uint8_t* rec,
+                             size_t stride)
+{
+    size_t W = ((size_t)L + 31) / 32;
+    uint32_t* pat = (uint32_t*)malloc(sizeof(uint32_t) * L);  /* sample bit patterns, zero past the end */
+    uint32_t* keys = (uint32_t*)malloc(sizeof(uint32_t) * L);
+    uint8_t* status = (uint8_t*)malloc(L);
+    uint32_t* location = (uint32_t*)malloc(sizeof(uint32_t) * L);
+    if (!pat || !keys || !status || !location) {
+        free(pat); free(keys); free(status); free(location);
+        return REF_ENOSPC;
+    }
+    for (uint32_t j = 0; j < L; ++j) {
+        pat[j] = j < valid ? f2u(x[j]) : 0u;
+        keys[j] = pat[j] & 0x7FFFFFFFu;
+    }
+    int e = fftsp_ref_select(keys, L, k, status);
+    if (e) {
+        free(pat); free(keys); free(status); free(location);
+        return e;
+    }
+    prefix_locations(status, L, location);
+    uint32_t vmax = 0;
+    for (uint32_t j = 0; j < L; ++j)
+        if (status[j] && keys[j] > vmax) vmax = keys[j];
+    uint32_t pbase = fftsp_ref_pbase(vmax, bits, m);
+    memset(rec, 0, stride);
+    put_u32(rec + 0, pbase);
+    put_u32(rec + 4, vmax);
+    put_u32(rec + 8, k);
+    uint8_t* bitmap = rec + 16;
+    uint8_t* codes = rec + 16 + 4 * W;
+    for (uint32_t j = 0; j < L; ++j) {
+        if (!status[j]) continue;
+        bitmap[j >> 3] |= (uint8_t)(1u << (j & 7));
+        put_bits(codes, (uint64_t)location[j] * (uint64_t)bits, fftsp_ref_quantize(pat[j], pbase, bits, m), bits);
+    }
+    free(pat); free(keys); free(status); free(location);
+    return REF_OK;
+}
+
+static int topk_decode_chunk(const uint8_t* rec, size_t valid, uint32_t L, uint32_t k, int bits, int m, float* x)
+{
+    size_t W = ((size_t)L + 31) / 32;
+    uint32_t pbase = get_u32(rec + 0);
+    if (get_u32(rec + 8) != k) return REF_EFORMAT;
+    const uint8_t* bitmap = rec + 16;
+    const uint8_t* codes = rec + 16 + 4 * W;
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < L; ++j) {
+        float v = 0.0f;
+        if ((bitmap[j >> 3] >> (j & 7)) & 1u) {
+            if (rank >= k) return REF_EFORMAT;
+            v = u2f(fftsp_ref_dequantize(get_bits(codes, (uint64_t)rank * (uint64_t)bits, bits), pbase, bits, m));
+            ++rank;
+        }
+        if (j < valid) x[j] = v;
+    }
+    return rank == k ? REF_OK : REF_EFORMAT;
+}
+
+int fftsp_ref_topk_compress(const float* g, size_t n, uint32_t L, float theta, int bits, uint8_t* packed, size_t cap,
+                            int nthreads)
+{
+    uint32_t k;
+    int m = fftsp_ref_mantissa_bits(bits);
+    if (!g || !packed || n == 0 || m < 0) return REF_EINVAL;
+    if (fftsp_ref_topk_kept_per_chunk(L, theta, &k)) return REF_EINVAL;
+    size_t S = fftsp_ref_topk_record_stride(L, k, bits);
+    long C = (long)chunk_count(n, L);
+    if (cap < STREAM_HEADER_BYTES + (size_t)C * S) return REF_ENOSPC;
+    write_stream_header(packed, n, L, (uint32_t)C, bits, m, k, (uint32_t)S, theta);
+    put_u32(packed + 44, 1);
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
+    for (long c = 0; c < C; ++c) {
+        int e = topk_encode_chunk(g + (size_t)c * L, chunk_valid(n, L, (size_t)c), L, k, bits, m,
+                                  packed + STREAM_HEADER_BYTES + (size_t)c * S, S);
+        if (e) {
+#pragma omp atomic write
+            err = e;
+        }
+    }
+    return err;
+}
+
+int fftsp_ref_topk_decompress(const uint8_t* packed, size_t bytes, float* out, size_t n, uint32_t L, float theta,
+                              int bits, int nthreads)
+{
+    uint32_t k;
+    int m = fftsp_ref_mantissa_bits(bits);
+    if (!out || !packed || n == 0 || m < 0) return REF_EINVAL;
+    if (fftsp_ref_topk_kept_per_chunk(L, theta, &k)) return REF_EINVAL;
+    size_t S = fftsp_ref_topk_record_stride(L, k, bits);
+    long C = (long)chunk_count(n, L);
+    if (bytes < STREAM_HEADER_BYTES + (size_t)C * S) return REF_EFORMAT;
+    int e0 = check_stream_header(packed, bytes, n, L, (uint32_t)C, bits, m, k, (uint32_t)S);
+    if (e0) return e0;
+    if (get_u32(packed + 44) != 1) return REF_EFORMAT;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
+    for (long c = 0; c < C; ++c) {
+        int e = topk_decode_chunk(packed + STREAM_HEADER_BYTES + (size_t)c * S, chunk_valid(n, L, (size_t)c), L, k, bits,
+                                  m, out + (size_t)c * L);
+        if (e) {
+#pragma omp atomic write
+            err = e;
+        }
+    }
+    return err;
+}
+
 int fftsp_ref_max_threads(void)
 {
 #ifdef _OPENMP

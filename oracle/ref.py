@@ -67,6 +67,11 @@ def lib():
             "fftsp_ref_packed_bytes_segments": (C.c_size_t, [szp, C.c_int, C.c_float, C.c_int]),
             "fftsp_ref_compress_segments": (C.c_int, [fp, szp, C.c_int, C.c_float, C.c_int, u8p, C.c_size_t, C.c_int]),
             "fftsp_ref_decompress_segments": (C.c_int, [u8p, C.c_size_t, fp, szp, C.c_int, C.c_float, C.c_int, C.c_int]),
+            "fftsp_ref_topk_kept_per_chunk": (C.c_int, [C.c_uint32, C.c_float, u32p]),
+            "fftsp_ref_topk_record_stride": (C.c_size_t, [C.c_uint32, C.c_uint32, C.c_int]),
+            "fftsp_ref_topk_packed_bytes": (C.c_size_t, [C.c_size_t, C.c_uint32, C.c_float, C.c_int]),
+            "fftsp_ref_topk_compress": (C.c_int, [fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, u8p, C.c_size_t, C.c_int]),
+            "fftsp_ref_topk_decompress": (C.c_int, [u8p, C.c_size_t, fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int]),
             "fftsp_ref_max_threads": (C.c_int, []),
         }
         for name, (res, args) in sig.items():
@@ -324,12 +329,58 @@ def decompress_segments(packed, seg_offsets, theta, bits, nthreads=1):
     return out
 
 
+# ---- time-domain Top-k (Sec. 4, "Choice of Algorithms"): same selector, quantizer and packing, no transform ----
+def topk_kept_per_chunk(L, theta) -> int:
+    k = C.c_uint32(0)
+    _chk(lib().fftsp_ref_topk_kept_per_chunk(L, np.float32(theta), C.byref(k)), "topk_kept_per_chunk")
+    return int(k.value)
+
+
+def topk_record_stride(L, k, bits) -> int:
+    return int(lib().fftsp_ref_topk_record_stride(L, k, bits))
+
+
+def topk_packed_bytes(n, L, theta, bits) -> int:
+    return int(lib().fftsp_ref_topk_packed_bytes(n, L, np.float32(theta), bits))
+
+
+def topk_compress(g, L, theta, bits, nthreads=1):
+    g, gp = _f32(g)
+    nb = topk_packed_bytes(g.size, L, theta, bits)
+    if nb == 0:
+        raise OracleError(EINVAL, "topk_compress")
+    out = np.empty(nb, dtype=np.uint8)
+    _chk(lib().fftsp_ref_topk_compress(gp, g.size, L, np.float32(theta), bits,
+                                       out.ctypes.data_as(C.POINTER(C.c_uint8)), nb, nthreads), "topk_compress")
+    return out
+
+
+def topk_decompress(packed, n, L, theta, bits, nthreads=1):
+    packed, pp = _u8(packed)
+    out = np.empty(n, dtype=np.float32)
+    _chk(lib().fftsp_ref_topk_decompress(pp, packed.size, out.ctypes.data_as(C.POINTER(C.c_float)), n, L,
+                                         np.float32(theta), bits, nthreads), "topk_decompress")
+    return out
+
+
+def topk_record_fields(packed, L, c=0):
+    """pbase, vmax_bits, k, word3, bitmap bits (L,) and code bytes of record c of a time-domain stream."""
+    h = parse_header(packed)
+    p = np.ascontiguousarray(packed, dtype=np.uint8)
+    W = (L + 31) // 32
+    rec = p[64 + c * h["S"]: 64 + (c + 1) * h["S"]]
+    hdr = rec[:16].view("<u4")
+    bitmap = np.unpackbits(rec[16:16 + 4 * W], bitorder="little")[:L]
+    return int(hdr[0]), int(hdr[1]), int(hdr[2]), int(hdr[3]), bitmap, rec[16 + 4 * W:]
+
+
 # ---- helpers that only parse the documented byte layout (used by tests) ----
 def parse_header(packed):
     p = np.ascontiguousarray(packed, dtype=np.uint8)
     u32 = lambda o: int(p[o:o + 4].view("<u4")[0])
     return dict(magic=bytes(p[0:4]), version=u32(4), n=int(p[8:16].view("<u8")[0]), L=u32(16), C=u32(20),
-                bits=u32(24), m=u32(28), k=u32(32), S=u32(36), theta=float(p[40:44].view("<f4")[0]))
+                bits=u32(24), m=u32(28), k=u32(32), S=u32(36), theta=float(p[40:44].view("<f4")[0]),
+                domain=u32(44))
 
 
 def record_fields(packed, L, c=0):
