@@ -157,6 +157,26 @@ int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, u
                           float theta, int bits, float* d_spec,
                           void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
 
+/* ---- time-domain Top-k, the sparsifier the paper measures its own against (Sec. 4, "Choice of Algorithms";
+ *      the Sec. 3.1.1 figure sets it beside FFT Top-k): the magnitude selection (Sec. 3.1.1), Algorithm 1 and the
+ *      packing of Sec. 3.2 applied to the gradient's samples themselves, no transform.  Chunk c is samples
+ *      [c*L, (c+1)*L) (the last one zero-padded for the selection; the padding is never written back); a sample
+ *      ranks by |x|, ties to the lowest index; k = round-half-up(theta * L) samples are kept per chunk, theta
+ *      being the KEPT fraction; bits = 32 is the paper's plain Top-k.  Record: 16-byte header as above, bitmap of
+ *      ceil(L/32) words, ONE code per kept sample; stream header word 11 (offset 44) is 1, and each decompress
+ *      accepts only its own kind of stream (status FFTSP_EFORMAT otherwise).  chunk_len: power of two in
+ *      [32, 2^21].  Pointers, alignment, workspace, stream and error behaviour are those of
+ *      fftsp_compress / fftsp_decompress; the workspace here holds no spectrum. ---- */
+int fftsp_topk_kept_per_chunk(uint32_t chunk_len, float theta, uint32_t* k_out);
+size_t fftsp_topk_packed_bytes(size_t n, uint32_t chunk_len, float theta, int bits);
+size_t fftsp_topk_workspace_bytes(size_t n, uint32_t chunk_len, int bits);
+int fftsp_topk_compress(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits,
+                        void* d_packed, size_t packed_capacity,
+                        void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+int fftsp_topk_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n,
+                          uint32_t chunk_len, float theta, int bits,
+                          void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+
 /* ---- per-tensor variant: segment i = d_grad[seg_offsets[i] .. seg_offsets[i+1]) is one chunk of
  *      L_i = max(32, next power of two >= its size); seg_offsets (nseg+1 entries, ascending) is on the HOST
  *      and is consumed before the call returns.  Sizes above 2^22 are FFTSP_EUNSUPPORTED.

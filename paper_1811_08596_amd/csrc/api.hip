@@ -166,6 +166,55 @@ CodecArgs codec_args(const Plan& p, float theta)
 
 int hip_status(hipError_t e) { return e == hipSuccess ? FFTSP_OK : FFTSP_EHIP; }
 
+// ---- time-domain Top-k: chunks of L samples are ranked, coded and packed as they are ----
+// a chunk's selection runs in one workgroup that keeps per-tile state in LDS for up to 1025 tiles of 2048
+constexpr int kTopkMaxLogL = 21;
+
+uint32_t topk_kept(uint32_t L, float theta)
+{
+    double k = std::floor((double)theta * (double)L + 0.5);
+    if (k < 0) k = 0;
+    if (k > (double)L) k = (double)L;
+    return (uint32_t)k;
+}
+
+size_t topk_record_stride(uint32_t L, uint32_t k, int bits)
+{
+    const size_t W = ((size_t)L + 31) / 32;
+    const size_t code_words = ((size_t)k * (size_t)bits + 31) / 32;
+    return (16 + 4 * W + 4 * code_words + 15) & ~(size_t)15;
+}
+
+int make_topk_plan(Plan* p, size_t n, uint32_t L, const float* theta, int bits)
+{
+    if (n == 0) return FFTSP_EINVAL;
+    p->logL = check_len(L);
+    if (p->logL < 0 || p->logL > kTopkMaxLogL) return FFTSP_EUNSUPPORTED;
+    p->n = n;
+    p->L = L;
+    p->C = (n + L - 1) / L;
+    p->k = 0;
+    if (theta) {
+        if (!theta_ok(*theta)) return FFTSP_EINVAL;
+        p->k = topk_kept(L, *theta);
+    }
+    p->m = mantissa(bits);
+    if (p->m < 0) return FFTSP_EINVAL;
+    p->bits = bits;
+    p->S = topk_record_stride(L, p->k, bits);
+    p->ws = make_workspace(p->C, L, 1);
+    return FFTSP_OK;
+}
+
+CodecArgs topk_args(const Plan& p, float theta)
+{
+    CodecArgs a = codec_args(p, theta);
+    a.sstride = p.L;  // chunk c of the "spectrum" is the gradient's own samples [c*L, (c+1)*L)
+    a.time_domain = 1;
+    a.n = p.n;
+    return a;
+}
+
 // quantizer options (Sec. 3.2.1): a chosen m replaces the default of the width, a static range replaces the
 // per-chunk fit; q == nullptr keeps both defaults
 int apply_quantizer(Plan* p, const fftsp_quantizer* q, uint32_t* static_vmax)
@@ -443,6 +492,66 @@ int fftsp_decompress_accumulate(const void* const* d_packed, int npeers, size_t 
         e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
                          a.pair_log != 0, scale, nullptr, s);
     return hip_status(e);
+}
+
+/* ---------------- time-domain Top-k: the same select / quantize / pack kernels, no transform ---------------- */
+
+int fftsp_topk_kept_per_chunk(uint32_t chunk_len, float theta, uint32_t* k_out)
+{
+    if (!k_out || !theta_ok(theta)) return FFTSP_EINVAL;
+    const int l = check_len(chunk_len);
+    if (l < 0 || l > kTopkMaxLogL) return FFTSP_EUNSUPPORTED;
+    *k_out = topk_kept(chunk_len, theta);
+    return FFTSP_OK;
+}
+
+size_t fftsp_topk_packed_bytes(size_t n, uint32_t chunk_len, float theta, int bits)
+{
+    Plan p;
+    if (make_topk_plan(&p, n, chunk_len, &theta, bits) != FFTSP_OK) return 0;
+    return kStreamHeader + p.C * p.S;
+}
+
+size_t fftsp_topk_workspace_bytes(size_t n, uint32_t chunk_len, int bits)
+{
+    Plan p;
+    if (make_topk_plan(&p, n, chunk_len, nullptr, bits) != FFTSP_OK) return 0;
+    return p.ws.total;
+}
+
+int fftsp_topk_compress(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                        size_t packed_capacity, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_topk_plan(&p, n, chunk_len, &theta, bits);
+    if (rc) return rc;
+    if (!d_grad || !d_packed || !d_workspace || !aligned16(d_grad) || !aligned16(d_packed) || !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_capacity < kStreamHeader + p.C * p.S) return FFTSP_ENOSPC;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    uint8_t* out = static_cast<uint8_t*>(d_packed);
+    const CodecArgs a = topk_args(p, theta);
+    return hip_status(launch_encode(d_grad, a, out, out + kStreamHeader, ws, p.ws, 0,
+                                    reinterpret_cast<hipStream_t>(stream)));
+}
+
+int fftsp_topk_decompress(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n, uint32_t chunk_len,
+                          float theta, int bits, void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_topk_plan(&p, n, chunk_len, &theta, bits);
+    if (rc) return rc;
+    if (!d_grad_out || !d_packed || !d_workspace || !aligned16(d_grad_out) || !aligned16(d_packed) ||
+        !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_bytes < kStreamHeader + p.C * p.S) return FFTSP_EFORMAT;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    const uint8_t* in = static_cast<const uint8_t*>(d_packed);
+    const CodecArgs a = topk_args(p, theta);
+    return hip_status(launch_decode(in, in + kStreamHeader, a, d_grad_out, ws, p.ws, 1, 1,
+                                    reinterpret_cast<hipStream_t>(stream)));
 }
 
 /* ---------------- per-tensor variant: one single-chunk codec per segment ---------------- */

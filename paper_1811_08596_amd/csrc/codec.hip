@@ -33,6 +33,34 @@ __device__ __forceinline__ uint32_t vbits_of(float2 z)
     const uint32_t a = __float_as_uint(z.x) & 0x7FFFFFFFu, b = __float_as_uint(z.y) & 0x7FFFFFFFu;
     return a > b ? a : b;
 }
+// What is ranked and coded is either a complex frequency bin (two codes) or, for time-domain Top-k, a sample of
+// the gradient itself (one code; the rank key is the bit pattern of |x|, an exact magnitude order).
+__device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+__device__ __forceinline__ uint32_t vbits_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+template <bool REAL>
+struct Elem {
+    using T = float2;
+    static constexpr uint32_t kCodes = 2;
+    static __device__ __forceinline__ T zero() { return make_float2(0.f, 0.f); }
+};
+template <>
+struct Elem<true> {
+    using T = float;
+    static constexpr uint32_t kCodes = 1;
+    static __device__ __forceinline__ T zero() { return 0.f; }
+};
+// samples of chunk c that exist (time domain: the last chunk may end early, the rest counts as zeros)
+template <bool REAL>
+__device__ __forceinline__ uint32_t present_of(size_t n, size_t c, uint32_t B)
+{
+    if constexpr (REAL) {
+        const size_t left = n - c * (size_t)B;
+        return left < (size_t)B ? (uint32_t)left : B;
+    } else {
+        return B;
+    }
+}
+
 // a plain 16-byte value that the compiler keeps in registers
 typedef uint32_t u32x4 __attribute__((vector_size(16)));
 
@@ -55,6 +83,20 @@ __device__ __forceinline__ void tile_to_lds(const float2* __restrict__ X, uint32
         for (int i = 0; i < kTile / 2 / kTileThreads; ++i) dst[tid + i * kTileThreads] = src[tid + i * kTileThreads];
     } else {
         for (uint32_t i = tid; i < count; i += kTileThreads) stage[i] = X[tbase + i];
+    }
+}
+
+// Time domain: samples [tbase, tbase + kTile) of a chunk, zeros from `present` on.
+__device__ __forceinline__ void tile_to_lds(const float* __restrict__ X, uint32_t tbase, uint32_t present, float* stage,
+                                            int tid)
+{
+    if (tbase + (uint32_t)kTile <= present) {  // chunks start on multiples of 32 samples of a 16-byte aligned gradient
+        const float4* src = reinterpret_cast<const float4*>(X + tbase);
+        float4* dst = reinterpret_cast<float4*>(stage);
+#pragma unroll
+        for (int i = 0; i < kTile / 4 / kTileThreads; ++i) dst[tid + i * kTileThreads] = src[tid + i * kTileThreads];
+    } else {
+        for (uint32_t i = tid; i < (uint32_t)kTile; i += kTileThreads) stage[i] = tbase + i < present ? X[tbase + i] : 0.f;
     }
 }
 
@@ -137,8 +179,9 @@ __global__ void k_zero_u32(uint32_t* p, size_t count)
 // ------------------------------------------------------------- histogram ----
 constexpr int HIST_TILES = 4;  // tiles per workgroup
 
-__global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, uint32_t sstride, int pair_log, uint32_t B, uint32_t groups,
-                                             uint32_t* __restrict__ hist)
+template <bool REAL>
+__global__ __launch_bounds__(NT) void k_hist(const typename Elem<REAL>::T* __restrict__ spec, uint32_t sstride, int pair_log,
+                                             uint32_t B, uint32_t groups, uint32_t* __restrict__ hist, size_t n)
 {
     __shared__ uint32_t h[kHistBins];
     const int tid = threadIdx.x;
@@ -146,11 +189,15 @@ __global__ __launch_bounds__(NT) void k_hist(const float2* __restrict__ spec, ui
     const uint32_t base = (blockIdx.x % groups) * (HIST_TILES * kTile);
     for (int i = tid; i < kHistBins; i += NT) h[i] = 0u;
     __syncthreads();
-    const float2* X = spec + c * (size_t)sstride;
+    const typename Elem<REAL>::T* X = spec + c * (size_t)sstride;
+    const uint32_t present = present_of<REAL>(n, c, B);
 #pragma unroll 4
     for (int i = tid; i < HIST_TILES * kTile; i += NT) {
         const uint32_t j = base + i;
-        if (j < B) atomicAdd(&h[key_of(X[spec_index(j, pair_log)]) >> kKeyShift], 1u);
+        if (j < B) {
+            const typename Elem<REAL>::T z = j < present ? X[spec_index(j, pair_log)] : Elem<REAL>::zero();
+            atomicAdd(&h[key_of(z) >> kKeyShift], 1u);
+        }
     }
     __syncthreads();
     uint32_t* g = hist + c * kHistBins;
@@ -215,18 +262,23 @@ __global__ __launch_bounds__(NT) void k_find_bucket(const uint32_t* __restrict__
 
 // --------------------------------------------------------------- collect ----
 // Per tile: count and range of the bins kept outright, and the candidates in bin order.
-__global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec, uint32_t sstride, int pair_log, uint32_t B, uint32_t Tn,
-                                                const uint32_t* __restrict__ sel, uint32_t* __restrict__ tinfo,
-                                                uint2* __restrict__ cand)
+template <bool REAL>
+__global__ __launch_bounds__(NT) void k_collect(const typename Elem<REAL>::T* __restrict__ spec, uint32_t sstride, int pair_log,
+                                                uint32_t B, uint32_t Tn, const uint32_t* __restrict__ sel,
+                                                uint32_t* __restrict__ tinfo, uint2* __restrict__ cand, size_t n)
 {
+    using E = typename Elem<REAL>::T;
     __shared__ uint32_t wcnt[4], wdef[4], wvmax[4];
-    __shared__ float2 stage[kTile];
+    __shared__ E stage[kTile];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t c = blockIdx.x / Tn;
     const uint32_t tile = blockIdx.x % Tn;
-    const float2* X = spec + c * (size_t)sstride;
+    const E* X = spec + c * (size_t)sstride;
     const uint32_t tbase = tile * kTile;
-    tile_to_lds(X, tbase, B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile, sstride, stage, tid);
+    if constexpr (REAL)
+        tile_to_lds(X, tbase, present_of<REAL>(n, c, B), stage, tid);
+    else
+        tile_to_lds(X, tbase, B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile, sstride, stage, tid);
     const uint32_t bstar = sel[c * 8 + 0];
     __syncthreads();
     const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
@@ -238,7 +290,7 @@ __global__ __launch_bounds__(NT) void k_collect(const float2* __restrict__ spec,
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
-        const float2 z = valid ? stage[slot_of(slots, r, j0, tbase, pair_log)] : make_float2(0.f, 0.f);
+        const E z = valid ? stage[slot_of(slots, r, j0, tbase, pair_log)] : Elem<REAL>::zero();
         key[r] = key_of(z);
         vb[r] = vbits_of(z);
         const uint32_t bucket = key[r] >> kKeyShift;
@@ -314,6 +366,34 @@ __device__ __forceinline__ size_t record_offset(const TableArg<TABLE>& tab, size
         return c * S;
 }
 
+// Candidates that did not fit in LDS are walked tile by tile, a wave per tile: the wave fetches up to kWalk rows
+// of 64 candidates in one memory round trip (long runs of equal keys, such as a chunk of zeros, fill whole tiles)
+// and hands them to f(entry, valid) row by row, in candidate order (f is called by the whole wave, so it may use
+// ballots).
+constexpr int kWalk = 8;
+template <typename F>
+__device__ __forceinline__ void walk_tile(const uint2* __restrict__ tile_cands, uint32_t nc, int lane, F&& f)
+{
+    if (nc <= 64u) {  // the usual tile: less than one row of candidates, one load
+        if (nc) f(tile_cands[(uint32_t)lane < nc ? (uint32_t)lane : 0u], (uint32_t)lane < nc);
+        return;
+    }
+    for (uint32_t i0 = 0; i0 < nc; i0 += 64u * kWalk) {
+        uint2 e[kWalk];
+        // all loads are issued before the first is used; rows past the end re-read the tile's first slot
+#pragma unroll
+        for (int u = 0; u < kWalk; ++u) {
+            const uint32_t i = i0 + (uint32_t)u * 64u + (uint32_t)lane;
+            e[u] = tile_cands[i < nc ? i : 0u];
+        }
+#pragma unroll
+        for (int u = 0; u < kWalk; ++u) {
+            const uint32_t row = i0 + (uint32_t)u * 64u;
+            if (row < nc) f(e[u], row + (uint32_t)lane < nc);
+        }
+    }
+}
+
 constexpr int kStageBatch = 12;  // candidates per lane fetched in one go by k_resolve (12 Ki staged / 1024 lanes)
 
 struct HeaderInfo {
@@ -321,6 +401,7 @@ struct HeaderInfo {
     uint64_t n;
     uint32_t L, C, N, m, k, S;
     float theta;
+    uint32_t domain;  // 0: records hold frequency bins, 1: samples (time-domain Top-k)
 };
 
 // One workgroup per chunk: finish the radix select on the candidates, break ties by bin order,
@@ -329,6 +410,7 @@ struct HeaderInfo {
 template <bool TABLE>
 __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bits, int m, uint32_t W, size_t S,
                                                 uint32_t word3, uint32_t stage_cap, uint32_t static_vmax,
+                                                uint32_t codes_per_bin,
                                                 uint32_t* __restrict__ sel,
                                                 const uint32_t* __restrict__ tinfo, uint32_t* __restrict__ tscan,
                                                 const uint2* __restrict__ cand, uint8_t* __restrict__ records,
@@ -419,11 +501,21 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
                 }
             } else {
                 for (uint32_t t = wave; t < Tn; t += RW) {
-                    const uint32_t nc = tnc[t];
-                    for (uint32_t i = lane; i < nc; i += 64) {
-                        const uint32_t key = cd[(size_t)t * kTile + i].x;
-                        if ((key & pmask) == prefix) atomicAdd(&h[(key >> shift) & dmask], 1u);
-                    }
+                    walk_tile(cd + (size_t)t * kTile, tnc[t], lane, [&](uint2 e, bool valid) {
+                        const bool hit = valid && (e.x & pmask) == prefix;
+                        const uint32_t digit = (e.x >> shift) & dmask;
+                        const uint64_t act = __ballot(hit);
+                        if (act) {
+                            // a row whose keys share the digit (a run of equal values, e.g. zeros) is one atomic
+                            const int first = __ffsll((unsigned long long)act) - 1;
+                            const uint32_t d0 = __shfl(digit, first, 64);
+                            if (__ballot(hit && digit == d0) == act) {
+                                if (lane == first) atomicAdd(&h[d0], (uint32_t)__popcll(act));
+                            } else if (hit) {
+                                atomicAdd(&h[digit], 1u);
+                            }
+                        }
+                    });
                 }
             }
             __syncthreads();
@@ -461,15 +553,11 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
         }
     } else {
         for (uint32_t t = wave; t < Tn; t += RW) {
-            const uint32_t nc = tnc[t];
             uint32_t gt = 0, eq = 0;  // wave-uniform counts from ballots
-            for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
-                const uint32_t i = i0 + lane;
-                const bool valid = i < nc;
-                const uint32_t key = valid ? cd[(size_t)t * kTile + i].x : 0u;
-                gt += (uint32_t)__popcll(__ballot(valid && key > tau));
-                eq += (uint32_t)__popcll(__ballot(valid && key == tau));
-            }
+            walk_tile(cd + (size_t)t * kTile, tnc[t], lane, [&](uint2 e, bool valid) {
+                gt += (uint32_t)__popcll(__ballot(valid && e.x > tau));
+                eq += (uint32_t)__popcll(__ballot(valid && e.x == tau));
+            });
             if (lane == 0) {
                 tgt[t] = gt;
                 teq[t] = eq;
@@ -529,19 +617,16 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
         }
     } else {
         for (uint32_t t = wave; t < Tn; t += RW) {
-            const uint32_t nc = tnc[t], take = ttake[t];
+            const uint32_t take = ttake[t];
             if (lane == 0 && tdef[t]) vm = tvd[t] > vm ? tvd[t] : vm;
             uint32_t eqrun = 0;
-            for (uint32_t i0 = 0; i0 < nc; i0 += 64) {
-                const uint32_t i = i0 + lane;
-                const bool valid = i < nc;
-                const uint2 e = valid ? cd[(size_t)t * kTile + i] : make_uint2(0u, 0u);
+            walk_tile(cd + (size_t)t * kTile, tnc[t], lane, [&](uint2 e, bool valid) {
                 const bool iseq = valid && e.x == tau;
                 const uint64_t em = __ballot(iseq);
                 const bool kept = valid && (e.x > tau || (iseq && eqrun + prefix_popc(em) < take));
                 if (kept) vm = e.y > vm ? e.y : vm;
                 eqrun += (uint32_t)__popcll(em);
-            }
+            });
         }
     }
     vm = wave_max(vm);
@@ -567,7 +652,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
         rec[3] = word3;
     }
     uint32_t* codes = rec + 4 + W;
-    const uint32_t twoN = 2u * (uint32_t)bits;
+    const uint32_t twoN = codes_per_bin * (uint32_t)bits;  // code bits per kept bin
     for (uint32_t t = tid; t < Tn; t += RT) {
         if (tsurv[t]) {
             codes[(twoN * trank[t]) >> 5] = 0u;
@@ -592,6 +677,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             case 8: v = hdr.k; break;
             case 9: v = hdr.S; break;
             case 10: v = __float_as_uint(hdr.theta); break;
+            case 11: v = hdr.domain; break;
             default: break;
         }
         reinterpret_cast<uint32_t*>(stream)[tid] = v;
@@ -600,12 +686,14 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
 
 // ------------------------------------------------------------------ emit ----
 // Per tile: flags, ranks, Algorithm 1 codes, bit-packing, bitmap words.
-template <bool TABLE>
-__global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, uint32_t sstride, int pair_log, uint32_t B, uint32_t Tn, uint32_t W,
-                                             int bits, int m, size_t S, const uint32_t* __restrict__ sel,
-                                             const uint32_t* __restrict__ tscan, uint8_t* __restrict__ records,
-                                             TableArg<TABLE> tab)
+template <bool TABLE, bool REAL>
+__global__ __launch_bounds__(NT) void k_emit(const typename Elem<REAL>::T* __restrict__ spec, uint32_t sstride, int pair_log,
+                                             uint32_t B, uint32_t Tn, uint32_t W, int bits, int m, size_t S,
+                                             const uint32_t* __restrict__ sel, const uint32_t* __restrict__ tscan,
+                                             uint8_t* __restrict__ records, TableArg<TABLE> tab, size_t n)
 {
+    using E = typename Elem<REAL>::T;
+    constexpr uint32_t CODES = Elem<REAL>::kCodes;
     __shared__ uint32_t cw[kTile * 2 + 2];  // code words of this tile (bits = 32 worst case)
     __shared__ uint32_t bmw[kTile / 32];
     __shared__ uint32_t weq[4], wfl[4];
@@ -614,27 +702,30 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     const uint32_t tile = blockIdx.x % Tn;
     const uint32_t tau = sel[c * 8 + 2], quota = sel[c * 8 + 3], pbase = sel[c * 8 + 4];
     const uint32_t rank0 = tscan[(c * Tn + tile) * 2 + 0], eq0 = tscan[(c * Tn + tile) * 2 + 1];
-    const uint32_t twoN = 2u * (uint32_t)bits;
+    const uint32_t twoN = CODES * (uint32_t)bits;  // code bits per kept bin
     const int shift = 23 - m;
     const uint32_t lds_words = (uint32_t)kTile * twoN / 32u + 2u;
 
     // the spectrum tile is staged in the LDS words that later hold the packed codes
-    const float2* X = spec + c * (size_t)sstride;
-    float2* stage = reinterpret_cast<float2*>(cw);
+    const E* X = spec + c * (size_t)sstride;
+    E* stage = reinterpret_cast<E*>(cw);
     static_assert(sizeof(cw) >= kTile * sizeof(float2), "the code buffer doubles as the tile staging area");
     const uint32_t tbase = tile * kTile;
-    tile_to_lds(X, tbase, B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile, sstride, stage, tid);
+    if constexpr (REAL)
+        tile_to_lds(X, tbase, present_of<REAL>(n, c, B), stage, tid);
+    else
+        tile_to_lds(X, tbase, B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile, sstride, stage, tid);
     __syncthreads();
     const uint32_t j0 = tbase + wave * WAVE_BINS + lane;
     const RowSlots slots = row_slots(j0, tbase, pair_log);
-    float2 z[ROWS];
+    E z[ROWS];
     uint64_t em[ROWS], fm[ROWS];
     uint32_t neq = 0, gtbits = 0, eqbits = 0;  // bit r = this lane's bin of row r is above / equal to the threshold
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t j = j0 + r * 64;
         const bool valid = j < B;
-        z[r] = valid ? stage[slot_of(slots, r, j0, tbase, pair_log)] : make_float2(0.f, 0.f);
+        z[r] = valid ? stage[slot_of(slots, r, j0, tbase, pair_log)] : Elem<REAL>::zero();
         const uint32_t key = key_of(z[r]);
         const bool gt = valid && key > tau, eq = valid && key == tau;
         gtbits |= (uint32_t)gt << r;
@@ -672,17 +763,30 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
     for (int w = 0; w < wave; ++w) rank += wfl[w];
     const uint32_t total = wfl[0] + wfl[1] + wfl[2] + wfl[3];
     const uint32_t w0 = (twoN * rank0) >> 5;
+    // the one or two binary32 patterns a bin is coded from
+    auto part = [](const E& v, int h) __attribute__((always_inline)) {
+        if constexpr (REAL)
+            return __float_as_uint(v);
+        else
+            return __float_as_uint(h ? v.y : v.x);
+    };
     if (bits == 8) {
-        // two 8-bit codes per survivor = one aligned 16-bit store, no read-modify-write
+        // 8-bit codes: a survivor is one aligned 16-bit store (bin) or one byte (sample), no read-modify-write
         uint16_t* cw16 = reinterpret_cast<uint16_t*>(cw);
-        const uint32_t base16 = rank0 - 2u * w0;  // first survivor's 16-bit slot inside cw
+        uint8_t* cw8 = reinterpret_cast<uint8_t*>(cw);
+        const uint32_t base16 = rank0 - 2u * w0;  // first survivor's 16-bit slot inside cw (two codes each)
+        const uint32_t base8 = rank0 - 4u * w0;   // first survivor's byte inside cw (one code each)
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             if ((flbits >> r) & 1u) {
                 const uint32_t rk = rank + prefix_popc(fm[r]);
-                const uint32_t cre = quantize(__float_as_uint(z[r].x), pbase, 8, shift);
-                const uint32_t cim = quantize(__float_as_uint(z[r].y), pbase, 8, shift);
-                cw16[base16 + (rk - rank0)] = (uint16_t)(cre | (cim << 8));
+                const uint32_t cre = quantize(part(z[r], 0), pbase, 8, shift);
+                if constexpr (REAL) {
+                    cw8[base8 + (rk - rank0)] = (uint8_t)cre;
+                } else {
+                    const uint32_t cim = quantize(part(z[r], 1), pbase, 8, shift);
+                    cw16[base16 + (rk - rank0)] = (uint16_t)(cre | (cim << 8));
+                }
             }
             rank += (uint32_t)__popcll(fm[r]);
         }
@@ -691,11 +795,11 @@ __global__ __launch_bounds__(NT) void k_emit(const float2* __restrict__ spec, ui
         for (int r = 0; r < ROWS; ++r) {
             if ((flbits >> r) & 1u) {
                 const uint32_t rk = rank + prefix_popc(fm[r]);
-                const uint32_t cre = quantize(__float_as_uint(z[r].x), pbase, bits, shift);
-                const uint32_t cim = quantize(__float_as_uint(z[r].y), pbase, bits, shift);
+                const uint32_t cre = quantize(part(z[r], 0), pbase, bits, shift);
+                const uint32_t cim = quantize(part(z[r], 1), pbase, bits, shift);
                 uint32_t p = twoN * rk - (w0 << 5);  // bit position inside cw
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
+                for (int h = 0; h < (int)CODES; ++h) {
                     const uint32_t code = h ? cim : cre;
                     const uint32_t wi = p >> 5, sh = p & 31u;
                     atomicOr(&cw[wi], code << sh);
@@ -782,7 +886,7 @@ __device__ __forceinline__ void group_prefix_chunk(const uint8_t* __restrict__ s
             const uint32_t* h = reinterpret_cast<const uint32_t*>(stream);
             bad = bad || h[0] != 0x31505346u || h[1] != 1u || h[2] != (uint32_t)hdr.n ||
                   h[3] != (uint32_t)(hdr.n >> 32) || h[4] != hdr.L || h[5] != hdr.C || h[6] != hdr.N ||
-                  h[7] != hdr.m || h[8] != hdr.k || h[9] != hdr.S;
+                  h[7] != hdr.m || h[8] != hdr.k || h[9] != hdr.S || h[11] != hdr.domain;
         }
         *verdict = bad ? 6u : 0u;
     }
@@ -847,13 +951,17 @@ struct DecItem {
 // the one bin a partial tile may write past the chunk's last bin lands in the padding.
 // verd: header verdict of (peer, chunk) at verd[peer * C + chunk].
 // One stream.
-template <int NL, bool VEC, bool TABLE>
+// REAL: time-domain records (one code per kept sample); `spec` is then the gradient itself, chunk stride B = L
+// samples, written up to sample n only.
+template <int NL, bool VEC, bool TABLE, bool REAL>
 __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
                                                uint32_t k, int bits, int m, uint32_t Tn, uint32_t total, size_t C,
                                                const uint32_t* __restrict__ gprefix, const uint32_t* __restrict__ sel,
-                                               uint32_t* __restrict__ status, float2* __restrict__ spec, uint32_t sstride, int pair_log,
-                                               TableArg<TABLE> tab)
+                                               uint32_t* __restrict__ status, typename Elem<REAL>::T* __restrict__ spec,
+                                               uint32_t sstride, int pair_log, TableArg<TABLE> tab, size_t n)
 {
+    using E = typename Elem<REAL>::T;
+    constexpr uint32_t CODES = Elem<REAL>::kCodes;
     constexpr int kWin = NL * 1024 + 32;  // bytes of LDS per wave: main window, tail, slack for the 3-word read
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // header verdicts of k_group_prefix raise the status word
@@ -864,7 +972,7 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
     const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
     const int shift = 23 - m;
     const uint32_t code_base = 16u + 4u * W;  // byte offset of the codes inside a record
-    __shared__ float2 stage[kTile];
+    __shared__ __attribute__((aligned(16))) E stage[kTile];
     __shared__ __attribute__((aligned(16))) uint8_t cwin_all[4 * kWin];
     uint8_t* cwin = cwin_all + wave * kWin;
 
@@ -897,7 +1005,7 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
     // first byte of the wave's LDS window inside the record: the 16-byte boundary at or below its first code
     auto window_start = [&](const DecHead& h) __attribute__((always_inline)) {
         const uint32_t first = h.run < k ? h.run : (k ? k - 1u : 0u);
-        return (code_base + ((2u * (uint32_t)bits * first) >> 3)) & ~15u;
+        return (code_base + ((CODES * (uint32_t)bits * first) >> 3)) & ~15u;
     };
     auto load_codes = [&](uint32_t t, bool live, const DecHead& h, DecCodes<NL>& cd) __attribute__((always_inline)) {
         if (!live) t = 0;
@@ -927,42 +1035,70 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
         for (int r = 0; r < ROWS; ++r) {
             bool set;
             const uint32_t rank = row_rank(h, r, run, set);
-            float2 out = make_float2(0.f, 0.f);
+            E out = Elem<REAL>::zero();
             if (set) {
-                const uint32_t p = 2u * (uint32_t)bits * rank;                // bit offset of the pair in the codes
-                uint32_t cre, cim;
+                const uint32_t p = CODES * (uint32_t)bits * rank;             // bit offset of the bin's codes
+                uint32_t cre, cim = 0u;
                 if (bits == 8) {
-                    const uint32_t v = *reinterpret_cast<const uint16_t*>(cwin + (code_base + (p >> 3) - start));
-                    cre = v & 0xFFu;
-                    cim = v >> 8;
+                    if constexpr (REAL) {
+                        cre = cwin[code_base + (p >> 3) - start];
+                    } else {
+                        const uint32_t v = *reinterpret_cast<const uint16_t*>(cwin + (code_base + (p >> 3) - start));
+                        cre = v & 0xFFu;
+                        cim = v >> 8;
+                    }
                 } else {
                     const uint32_t* w = reinterpret_cast<const uint32_t*>(cwin + (code_base + 4u * (p >> 5) - start));
-                    const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
-                    const uint32_t sh = p & 31u, q = sh + (uint32_t)bits;
-                    const uint64_t w01 = (uint64_t)w0 | ((uint64_t)w1 << 32), w12 = (uint64_t)w1 | ((uint64_t)w2 << 32);
                     const uint32_t keep = bits == 32 ? 0xFFFFFFFFu : ((1u << bits) - 1u);
-                    cre = (uint32_t)(w01 >> sh) & keep;
-                    cim = (uint32_t)((q >= 32u ? w12 : w01) >> (q & 31u)) & keep;
+                    const uint32_t sh = p & 31u;
+                    if constexpr (REAL) {
+                        const uint64_t w01 = (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+                        cre = (uint32_t)(w01 >> sh) & keep;
+                    } else {
+                        const uint32_t w0 = w[0], w1 = w[1], w2 = w[2];
+                        const uint32_t q = sh + (uint32_t)bits;
+                        const uint64_t w01 = (uint64_t)w0 | ((uint64_t)w1 << 32), w12 = (uint64_t)w1 | ((uint64_t)w2 << 32);
+                        cre = (uint32_t)(w01 >> sh) & keep;
+                        cim = (uint32_t)((q >= 32u ? w12 : w01) >> (q & 31u)) & keep;
+                    }
                 }
-                out.x = __uint_as_float(dequantize(cre, h.pbase, bits, shift));
-                out.y = __uint_as_float(dequantize(cim, h.pbase, bits, shift));
+                if constexpr (REAL) {
+                    out = __uint_as_float(dequantize(cre, h.pbase, bits, shift));
+                } else {
+                    out.x = __uint_as_float(dequantize(cre, h.pbase, bits, shift));
+                    out.y = __uint_as_float(dequantize(cim, h.pbase, bits, shift));
+                }
             }
             const uint32_t j = j0 + r * 64;
             if (j < B) stage[slot_of(slots, r, j0, tbase, pair_log)] = out;
         }
         __syncthreads();
-        float2* X = spec + (size_t)(t / Tn) * (size_t)sstride;
-        const uint32_t count = B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile;
-        if constexpr (VEC) {
-            float4* dst = reinterpret_cast<float4*>(X + tbase);
-            const float4* src = reinterpret_cast<const float4*>(stage);
+        E* X = spec + (size_t)(t / Tn) * (size_t)sstride;
+        if constexpr (REAL) {
+            // samples of this tile that exist in the gradient (the last chunk may end inside or before the tile)
+            const uint32_t present = present_of<REAL>(n, t / Tn, B);
+            const uint32_t count = present > tbase ? (present - tbase < (uint32_t)kTile ? present - tbase : (uint32_t)kTile) : 0u;
+            if (VEC && count == (uint32_t)kTile) {
+                float4* dst = reinterpret_cast<float4*>(X + tbase);
+                const float4* src = reinterpret_cast<const float4*>(stage);
 #pragma unroll
-            for (int i = 0; i < kTile / 2 / NT; ++i) {
-                const uint32_t idx = (uint32_t)(tid + i * NT);
-                if (2u * idx < count) dst[idx] = src[idx];
+                for (int i = 0; i < kTile / 4 / NT; ++i) dst[tid + i * NT] = src[tid + i * NT];
+            } else {
+                for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = stage[i];
             }
         } else {
-            for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = stage[i];
+            const uint32_t count = B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile;
+            if constexpr (VEC) {
+                float4* dst = reinterpret_cast<float4*>(X + tbase);
+                const float4* src = reinterpret_cast<const float4*>(stage);
+#pragma unroll
+                for (int i = 0; i < kTile / 2 / NT; ++i) {
+                    const uint32_t idx = (uint32_t)(tid + i * NT);
+                    if (2u * idx < count) dst[idx] = src[idx];
+                }
+            } else {
+                for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = stage[i];
+            }
         }
     };
 
@@ -1177,25 +1313,37 @@ static hipError_t launch_zero_hist(uint8_t* ws_base, const Workspace& w, size_t 
 hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
                          uint8_t* ws_base, const Workspace& w, int hist_ready, hipStream_t s)
 {
-    const uint32_t B = a.L / 2 + 1, Tn = tiles_per_chunk(a.L), W = (B + 31) / 32;
+    const uint32_t B = codec_bins(a.L, a.time_domain), Tn = codec_tiles(a.L, a.time_domain), W = (B + 31) / 32;
     const float2* X = reinterpret_cast<const float2*>(spec);
     uint32_t* hist = reinterpret_cast<uint32_t*>(ws_base + w.hist);
     uint32_t* sel = reinterpret_cast<uint32_t*>(ws_base + w.sel);
     uint32_t* tinfo = reinterpret_cast<uint32_t*>(ws_base + w.tinfo);
     uint32_t* tscan = reinterpret_cast<uint32_t*>(ws_base + w.tscan);
     uint2* cand = reinterpret_cast<uint2*>(ws_base + w.cand);
-    if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
+    if (a.C * (size_t)Tn > 0x7fffffffu || Tn > (uint32_t)MAX_TILES) return hipErrorInvalidValue;
+    if (a.time_domain && (a.tab || a.pair_log || hist_ready)) return hipErrorInvalidValue;
 
     if (!hist_ready) {
         hipError_t e = launch_zero_hist(ws_base, w, a.C, s);
         if (e != hipSuccess) return e;
         const uint32_t groups = (Tn + HIST_TILES - 1) / HIST_TILES;
-        FFTSP_LAUNCH("hist", k_hist, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B, groups, hist);
+        if (a.time_domain)
+            FFTSP_LAUNCH("hist", k_hist<true>, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, spec, a.sstride, 0, B,
+                         groups, hist, a.n);
+        else
+            FFTSP_LAUNCH("hist", k_hist<false>, dim3((unsigned)(a.C * groups)), dim3(NT), 0, s, X, a.sstride, a.pair_log,
+                         B, groups, hist, a.n);
     }
     FFTSP_LAUNCH("find_bucket", k_find_bucket, dim3((unsigned)a.C), dim3(NT), 0, s, hist, a.k, sel);
-    FFTSP_LAUNCH("collect", k_collect, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B, Tn, sel, tinfo, cand);
+    if (a.time_domain)
+        FFTSP_LAUNCH("collect", k_collect<true>, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, spec, a.sstride, 0, B, Tn,
+                     sel, tinfo, cand, a.n);
+    else
+        FFTSP_LAUNCH("collect", k_collect<false>, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B,
+                     Tn, sel, tinfo, cand, a.n);
     HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
-                 a.hdr_theta};
+                 a.hdr_theta, a.time_domain ? 1u : 0u};
+    const uint32_t codes_per_bin = a.time_domain ? 1u : 2u;
     // up to 12 Ki candidates (96 KiB) are staged in LDS by the per-chunk workgroup
     constexpr uint32_t kStageCap = 12 * 1024;
     static bool lds_set = false;
@@ -1209,19 +1357,25 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
         lds_set = true;
     }
     if (a.tab && a.C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
-#define FFTSP_ENCODE_TAIL(TABLE)                                                                                       \
-    do {                                                                                                               \
-        FFTSP_LAUNCH("resolve", k_resolve<TABLE>, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k, \
-                     a.bits, a.m, W, a.S, a.word3, kStageCap, a.static_vmax, sel, tinfo, tscan, cand, records,         \
-                     stream_base, h, table_arg<TABLE>(a.tab));                                                         \
-        FFTSP_LAUNCH("emit", k_emit<TABLE>, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B,   \
-                     Tn, W, a.bits, a.m, a.S, sel, tscan, records, table_arg<TABLE>(a.tab));                           \
-    } while (0)
-    if (a.tab)
-        FFTSP_ENCODE_TAIL(true);
-    else
-        FFTSP_ENCODE_TAIL(false);
-#undef FFTSP_ENCODE_TAIL
+#define FFTSP_RESOLVE(TABLE)                                                                                          \
+    FFTSP_LAUNCH("resolve", k_resolve<TABLE>, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k,   \
+                 a.bits, a.m, W, a.S, a.word3, kStageCap, a.static_vmax, codes_per_bin, sel, tinfo, tscan, cand,      \
+                 records, stream_base, h, table_arg<TABLE>(a.tab))
+#define FFTSP_EMIT(TABLE, REAL, src)                                                                                  \
+    FFTSP_LAUNCH("emit", (k_emit<TABLE, REAL>), dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, src, a.sstride,           \
+                 a.pair_log, B, Tn, W, a.bits, a.m, a.S, sel, tscan, records, table_arg<TABLE>(a.tab), a.n)
+    if (a.tab) {
+        FFTSP_RESOLVE(true);
+        FFTSP_EMIT(true, false, X);
+    } else {
+        FFTSP_RESOLVE(false);
+        if (a.time_domain)
+            FFTSP_EMIT(false, true, spec);
+        else
+            FFTSP_EMIT(false, false, X);
+    }
+#undef FFTSP_RESOLVE
+#undef FFTSP_EMIT
     return hipGetLastError();
 }
 
@@ -1231,7 +1385,7 @@ static hipError_t launch_decode_kernel(const PeerList& recs, uint32_t npeers, co
                                        const uint32_t* gprefix, const uint32_t* verd, uint32_t* status, bool peers_layout,
                                        hipStream_t s)
 {
-    const uint32_t B = a.L / 2 + 1, W = (B + 31) / 32, Tn = tiles_per_chunk(a.L);
+    const uint32_t B = codec_bins(a.L, a.time_domain), W = (B + 31) / 32, Tn = codec_tiles(a.L, a.time_domain);
     // persistent grid: about two rounds of the workgroups a chip holds at once (six to eight per compute unit);
     // measured best at 4096 (2048: +10 %, one workgroup per tile: +8 %)
     const uint32_t total = (uint32_t)(a.C * Tn);
@@ -1243,14 +1397,36 @@ static hipError_t launch_decode_kernel(const PeerList& recs, uint32_t npeers, co
                          a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                                  \
                          reinterpret_cast<float2*>(spec), a.sstride, a.pair_log);                                  \
         else if (a.tab)                                                                                            \
-            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, true>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W,    \
-                         a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                                  \
-                         reinterpret_cast<float2*>(spec), a.sstride, a.pair_log, table_arg<true>(a.tab));          \
+            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, true, false>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S,   \
+                         B, W, a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                            \
+                         reinterpret_cast<float2*>(spec), a.sstride, a.pair_log, table_arg<true>(a.tab), a.n);     \
         else                                                                                                       \
-            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W,   \
-                         a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                                  \
-                         reinterpret_cast<float2*>(spec), a.sstride, a.pair_log, table_arg<false>(a.tab));         \
+            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false, false>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S,  \
+                         B, W, a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                            \
+                         reinterpret_cast<float2*>(spec), a.sstride, a.pair_log, table_arg<false>(a.tab), a.n);    \
     } while (0)
+    if (a.time_domain) {
+        // one code per sample: a wave's 512 samples are at most 1 KiB of codes up to 16 bits, 2 KiB at 32
+        if (peers_layout || a.tab || a.pair_log) return hipErrorInvalidValue;
+        const bool vec16 = (reinterpret_cast<uintptr_t>(spec) & 15u) == 0;
+#define FFTSP_DECODE_REAL(NL, VEC)                                                                                 \
+    FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false, true>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W,     \
+                 a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status, spec, a.sstride, 0,                      \
+                 table_arg<false>(nullptr), a.n)
+        if (a.bits <= 16) {
+            if (vec16)
+                FFTSP_DECODE_REAL(1, true);
+            else
+                FFTSP_DECODE_REAL(1, false);
+        } else {
+            if (vec16)
+                FFTSP_DECODE_REAL(2, true);
+            else
+                FFTSP_DECODE_REAL(2, false);
+        }
+#undef FFTSP_DECODE_REAL
+        return hipGetLastError();
+    }
     const bool vec = a.sstride == padded_bins(a.L) && (reinterpret_cast<uintptr_t>(spec) & 15u) == 0;
     // code widths are 3..16 or 32 bits
     const int nl = a.bits <= 8 ? 1 : a.bits <= 16 ? 2 : 4;
@@ -1269,13 +1445,13 @@ static hipError_t launch_decode_kernel(const PeerList& recs, uint32_t npeers, co
 hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
                          uint8_t* ws_base, const Workspace& w, int check_header, int reset_status, hipStream_t s)
 {
-    const uint32_t B = a.L / 2 + 1, W = (B + 31) / 32, Tn = tiles_per_chunk(a.L);
+    const uint32_t B = codec_bins(a.L, a.time_domain), W = (B + 31) / 32, Tn = codec_tiles(a.L, a.time_domain);
     uint32_t* status = reinterpret_cast<uint32_t*>(ws_base + w.status);
     uint32_t* sel = reinterpret_cast<uint32_t*>(ws_base + w.sel);
     uint32_t* gprefix = reinterpret_cast<uint32_t*>(ws_base + w.prefix);
     if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
     HeaderInfo h{check_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
-                 a.hdr_theta};
+                 a.hdr_theta, a.time_domain ? 1u : 0u};
     if (a.tab && a.C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
     if (a.tab)
         FFTSP_LAUNCH("group_prefix", k_group_prefix<true>, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S,
@@ -1297,7 +1473,7 @@ hipError_t launch_decode_peers(const PeerList& streams, int npeers, const CodecA
     uint32_t* verd = reinterpret_cast<uint32_t*>(ws_base + pw.verd);
     if (npeers < 1 || npeers > kMaxPeers) return hipErrorInvalidValue;
     if (a.C * (size_t)Tn > 0x7fffffffu || a.C * (size_t)npeers > 0x7fffffffu) return hipErrorInvalidValue;
-    HeaderInfo h{1, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S, a.hdr_theta};
+    HeaderInfo h{1, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S, a.hdr_theta, 0u};
     FFTSP_LAUNCH("group_prefix", k_group_prefix_peers, dim3((unsigned)(a.C * (size_t)npeers)), dim3(RT), 0, s, streams,
                  (uint32_t)a.C, a.S, W, a.k, h, gprefix, verd, status);
     PeerList recs{};

@@ -84,10 +84,18 @@ static inline uint32_t tiles_per_chunk(uint32_t L) { return ((L / 2 + 1) + kTile
 // chunk stride of the codec's own spectrum buffer, in complex bins: L/2+1 rounded up to a 128-byte multiple
 static inline uint32_t padded_bins(uint32_t L) { return (L / 2 + 1 + 15u) & ~15u; }
 
-static inline Workspace make_workspace(size_t C, uint32_t L)
+// What a chunk's record describes: L/2+1 frequency bins, or (time-domain Top-k) the L samples themselves.
+static inline uint32_t codec_bins(uint32_t L, int time_domain) { return time_domain ? L : L / 2 + 1; }
+static inline uint32_t codec_tiles(uint32_t L, int time_domain)
+{
+    return (codec_bins(L, time_domain) + kTile - 1) / kTile;
+}
+
+// time_domain != 0: no spectrum and no FFT intermediate (the codec kernels read and write the gradient itself)
+static inline Workspace make_workspace(size_t C, uint32_t L, int time_domain = 0)
 {
     Workspace w;
-    size_t B = (size_t)L / 2 + 1, Tn = tiles_per_chunk(L), W = (B + 31) / 32;
+    size_t B = codec_bins(L, time_domain), Tn = codec_tiles(L, time_domain), W = (B + 31) / 32;
     size_t off = 0;
     w.status = off; off += 256;
     w.hist = off;   off = align256(off + C * kHistBins * 4);
@@ -96,8 +104,8 @@ static inline Workspace make_workspace(size_t C, uint32_t L)
     w.tscan = off;  off = align256(off + C * Tn * 8);
     w.cand = off;   off = align256(off + C * Tn * kTile * 8);
     w.prefix = off; off = align256(off + C * W * 4);
-    w.spec = off;   off = align256(off + C * (size_t)padded_bins(L) * 8);
-    w.mid = off;    off = align256(off + C * (size_t)L * 4);
+    w.spec = off;   off = align256(off + (time_domain ? 0 : C * (size_t)padded_bins(L) * 8));
+    w.mid = off;    off = align256(off + (time_domain ? 0 : C * (size_t)L * 4));
     w.total = off;
     return w;
 }
@@ -163,6 +171,8 @@ struct CodecArgs {
     uint32_t static_vmax;  // != 0: bit pattern of the caller's fixed range maximum (instead of the largest survivor)
     uint32_t sstride;   // distance between consecutive chunks' spectra, in complex bins
     const ChunkTable* tab;  // per-tensor launches: where each chunk's record lives (host pointer); else nullptr
+    int time_domain;    // != 0: records describe the gradient's samples; `spec` of the launchers is the gradient
+    size_t n;           // time domain: samples in the gradient (the last chunk may be short)
     int pair_log;       // 0: spectrum in natural bin order; log2(N1): paired order (see spec_index)
     // stream header (written iff write_header)
     int write_header;

@@ -33,6 +33,13 @@ SIGNATURES = {
                                  C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_decompress": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fftsp_topk_kept_per_chunk": (C.c_int, [C.c_uint32, C.c_float, C.POINTER(C.c_uint32)]),
+    "fftsp_topk_packed_bytes": (C.c_size_t, [C.c_size_t, C.c_uint32, C.c_float, C.c_int]),
+    "fftsp_topk_workspace_bytes": (C.c_size_t, [C.c_size_t, C.c_uint32, C.c_int]),
+    "fftsp_topk_compress": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_void_p, C.c_size_t,
+                                      C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fftsp_topk_decompress": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float,
+                                        C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_compress_q": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_void_p, C.c_size_t,
                                    C.c_void_p, C.c_size_t, _qp, C.c_void_p]),
     "fftsp_decompress_q": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
@@ -161,6 +168,32 @@ def compress(grad, chunk_len: int, theta: float, bits: int, packed, workspace, s
 def decompress(packed, packed_nbytes: int, grad_out, chunk_len: int, theta: float, bits: int, workspace, stream=None):
     _check(load().fftsp_decompress(_ptr(packed), packed_nbytes, _ptr(grad_out), grad_out.numel(), chunk_len, theta,
                                    bits, _ptr(workspace), _nbytes(workspace), _stream(stream)), "fftsp_decompress")
+
+
+def topk_kept_per_chunk(chunk_len: int, theta: float) -> int:
+    k = C.c_uint32()
+    _check(load().fftsp_topk_kept_per_chunk(chunk_len, theta, C.byref(k)), "fftsp_topk_kept_per_chunk")
+    return k.value
+
+
+def topk_packed_bytes(n: int, chunk_len: int, theta: float, bits: int) -> int:
+    return load().fftsp_topk_packed_bytes(n, chunk_len, theta, bits)
+
+
+def topk_workspace_bytes(n: int, chunk_len: int, bits: int) -> int:
+    return load().fftsp_topk_workspace_bytes(n, chunk_len, bits)
+
+
+def topk_compress(grad, chunk_len: int, theta: float, bits: int, packed, workspace, stream=None):
+    _check(load().fftsp_topk_compress(_ptr(grad), grad.numel(), chunk_len, theta, bits, _ptr(packed), _nbytes(packed),
+                                      _ptr(workspace), _nbytes(workspace), _stream(stream)), "fftsp_topk_compress")
+
+
+def topk_decompress(packed, packed_nbytes: int, grad_out, chunk_len: int, theta: float, bits: int, workspace,
+                    stream=None):
+    _check(load().fftsp_topk_decompress(_ptr(packed), packed_nbytes, _ptr(grad_out), grad_out.numel(), chunk_len,
+                                        theta, bits, _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "fftsp_topk_decompress")
 
 
 def compress_q(grad, chunk_len: int, theta: float, bits: int, packed, workspace, mantissa_bits=0, range_max=0.0,

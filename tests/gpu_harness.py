@@ -138,6 +138,26 @@ class Device:
         st = self.f.device_status(ws)
         return out.cpu().numpy(), st
 
+    def topk_compress(self, g, L, theta, bits):
+        n = g.size
+        gd = self.to_dev(g.astype(np.float32))
+        nb = self.f.topk_packed_bytes(n, L, theta, bits)
+        assert nb > 0
+        packed = self.torch.full((nb,), 0xEE, dtype=self.torch.uint8, device=self.dev)
+        self.f.topk_compress(gd, L, theta, bits, packed, self.workspace(self.f.topk_workspace_bytes(n, L, bits)))
+        self.sync()
+        return packed.cpu().numpy()
+
+    def topk_decompress(self, packed, n, L, theta, bits, pad=0):
+        """returns (reconstruction, status, tail): `pad` extra floats behind the output must come back untouched"""
+        pd = self.to_dev(np.asarray(packed, np.uint8))
+        out = self.torch.full((n + pad,), float("nan"), dtype=self.torch.float32, device=self.dev)
+        ws = self.workspace(self.f.topk_workspace_bytes(n, L, bits))
+        self.f.topk_decompress(pd, pd.numel(), out[:n], L, theta, bits, ws)
+        st = self.f.device_status(ws)
+        res = out.cpu().numpy()
+        return res[:n], st, res[n:]
+
     def compress_segments(self, g, offs, theta, bits):
         gd = self.to_dev(g.astype(np.float32))
         nb = self.f.packed_bytes_segments(offs, theta, bits)

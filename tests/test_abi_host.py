@@ -114,6 +114,38 @@ def test_argument_errors_come_back_before_any_launch(lib):
     assert lib.fftsp_strerror(fftsp.EFORMAT).decode().startswith("packed stream")
 
 
+def test_topk_host_arithmetic_and_argument_errors(lib, ref):
+    for L in (32, 1 << 10, 1 << 16, 1 << 21):
+        for theta in (0.0, 0.15, 0.5, 1.0, 0.123456):
+            assert fftsp.topk_kept_per_chunk(L, theta) == ref.topk_kept_per_chunk(L, theta)
+            for bits in (3, 8, 10, 32):
+                for n in (1, L - 1, L, L + 1, 5 * L + 3):
+                    assert fftsp.topk_packed_bytes(n, L, theta, bits) == ref.topk_packed_bytes(n, L, theta, bits)
+    # the time-domain workspace holds no spectrum and no FFT intermediate
+    n, L = 1 << 22, 1 << 20
+    assert 0 < fftsp.topk_workspace_bytes(n, L, 8) < fftsp.workspace_bytes(n, L, 8)
+    a = 4096
+    call = lambda **kw: lib.fftsp_topk_compress(kw.get("g", a), kw.get("n", 100), kw.get("L", 64), kw.get("theta", 0.5),
+                                                kw.get("bits", 8), kw.get("p", a), kw.get("cap", 1 << 20),
+                                                kw.get("ws", a), kw.get("wsb", 1 << 30), None)
+    assert call(n=0) == fftsp.EINVAL
+    assert call(g=None) == fftsp.EINVAL
+    assert call(g=a + 4) == fftsp.EINVAL
+    assert call(L=48) == fftsp.EUNSUPPORTED
+    assert call(L=1 << 22) == fftsp.EUNSUPPORTED              # one chunk's selection state is sized for 2^21 samples
+    assert call(theta=1.5) == fftsp.EINVAL
+    assert call(bits=2) == fftsp.EINVAL
+    assert call(cap=10) == fftsp.ENOSPC
+    assert call(wsb=10) == fftsp.EWORKSPACE
+    dec = lambda **kw: lib.fftsp_topk_decompress(kw.get("p", a), kw.get("pb", 1 << 20), kw.get("g", a), kw.get("n", 100),
+                                                 kw.get("L", 64), 0.5, kw.get("bits", 8), kw.get("ws", a),
+                                                 kw.get("wsb", 1 << 30), None)
+    assert dec(pb=10) == fftsp.EFORMAT
+    assert dec(g=None) == fftsp.EINVAL
+    assert dec(L=1 << 22) == fftsp.EUNSUPPORTED
+    assert dec(wsb=10) == fftsp.EWORKSPACE
+
+
 def test_product_does_not_import_the_oracle():
     """The GPU package and its C sources must not use oracle/ (and vice versa)."""
     pkg = os.path.join(ROOT, "paper_1811_08596_amd")
