@@ -107,7 +107,11 @@ static void fft_rec(const cplx* in, size_t stride, cplx* out, size_t len, const 
 /* Forward real DFT of one chunk (Sec. 3.1.1 sum, sign -, no normalisation):
  * x has `valid` real samples, zeros up to L; spec receives bins 0..L/2 as
  * (re,im) float pairs, each component rounded once from double. */
-static int rfft_chunk(const float* x, size_t valid, uint32_t L, float* spec)
+static float round_half(double v);
+
+/* to_half != 0: every component is scaled by 2^scale_log2 and rounded ONCE from double to binary16 (returned as the
+ * binary32 number of the same value) instead of to binary32 */
+static int rfft_chunk_ex(const float* x, size_t valid, uint32_t L, float* spec, int to_half, int scale_log2)
 {
     cplx* in = (cplx*)malloc(sizeof(cplx) * L);
     cplx* out = (cplx*)malloc(sizeof(cplx) * L);
@@ -124,8 +128,13 @@ static int rfft_chunk(const float* x, size_t valid, uint32_t L, float* spec)
     fft_rec(in, 1, out, L, W, 1);
     size_t half = L / 2;
     for (size_t j = 0; j <= half; ++j) {
-        spec[2 * j] = (float)out[j].re;
-        spec[2 * j + 1] = (float)out[j].im;
+        if (to_half) {
+            spec[2 * j] = round_half(ldexp(out[j].re, scale_log2));
+            spec[2 * j + 1] = round_half(ldexp(out[j].im, scale_log2));
+        } else {
+            spec[2 * j] = (float)out[j].re;
+            spec[2 * j + 1] = (float)out[j].im;
+        }
     }
     /* a real signal has real DC and Nyquist bins: store +0 exactly */
     spec[1] = 0.0f;
@@ -134,10 +143,15 @@ static int rfft_chunk(const float* x, size_t valid, uint32_t L, float* spec)
     return REF_OK;
 }
 
+static int rfft_chunk(const float* x, size_t valid, uint32_t L, float* spec)
+{
+    return rfft_chunk_ex(x, valid, L, spec, 0, 0);
+}
+
 /* Inverse: x[t] = (1/L) sum_{j<L} Xfull[j] exp(+2 pi i j t / L), Xfull the
  * Hermitian extension of bins 0..L/2 (imaginary parts of bins 0 and L/2 are
  * ignored).  Only the first `valid` samples are written. */
-static int irfft_chunk(const float* spec, size_t valid, uint32_t L, float* x)
+static int irfft_chunk_ex(const float* spec, size_t valid, uint32_t L, float* x, int scale_log2)
 {
     cplx* in = (cplx*)malloc(sizeof(cplx) * L);
     cplx* out = (cplx*)malloc(sizeof(cplx) * L);
@@ -159,9 +173,14 @@ static int irfft_chunk(const float* spec, size_t valid, uint32_t L, float* x)
     }
     make_twiddles(W, L, +1);
     fft_rec(in, 1, out, L, W, 1);
-    for (size_t t = 0; t < valid; ++t) x[t] = (float)(out[t].re / (double)L);
+    for (size_t t = 0; t < valid; ++t) x[t] = (float)ldexp(out[t].re / (double)L, -scale_log2);
     free(in); free(out); free(W);
     return REF_OK;
+}
+
+static int irfft_chunk(const float* spec, size_t valid, uint32_t L, float* x)
+{
+    return irfft_chunk_ex(spec, valid, L, x, 0);
 }
 
 static size_t chunk_count(size_t n, uint32_t L) { return (n + L - 1) / L; }
@@ -549,8 +568,19 @@ static int check_stream_header(const uint8_t* p, size_t bytes, uint64_t n, uint3
     return REF_OK;
 }
 
+/* frequency-domain decoder; the stream must carry the given spectrum scale (header word 12; 0 for every sender but
+ * the half-precision one) */
+static int decode_spectrum_scaled(const uint8_t* packed, size_t bytes, size_t n, uint32_t L, float theta, int bits,
+                                  int m_opt, int scale_log2, float* spec, int nthreads);
+
 int fftsp_ref_decode_spectrum_q(const uint8_t* packed, size_t bytes, size_t n, uint32_t L, float theta, int bits,
                                 int m_opt, float* spec, int nthreads)
+{
+    return decode_spectrum_scaled(packed, bytes, n, L, theta, bits, m_opt, 0, spec, nthreads);
+}
+
+static int decode_spectrum_scaled(const uint8_t* packed, size_t bytes, size_t n, uint32_t L, float theta, int bits,
+                                  int m_opt, int scale_log2, float* spec, int nthreads)
 {
     uint32_t k;
     int m = quantizer_m(bits, m_opt);
@@ -561,6 +591,7 @@ int fftsp_ref_decode_spectrum_q(const uint8_t* packed, size_t bytes, size_t n, u
     if (bytes < STREAM_HEADER_BYTES + (size_t)C * S) return REF_EFORMAT;
     int e0 = check_stream_header(packed, bytes, n, L, (uint32_t)C, bits, m, k, (uint32_t)S);
     if (e0) return e0;
+    if (get_u32(packed + 44) != 0 || get_u32(packed + 48) != (uint32_t)scale_log2) return REF_EFORMAT;
     int err = 0;
 #pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
     for (long c = 0; c < C; ++c) {
@@ -946,6 +977,98 @@ int fftsp_ref_topk_decompress(const uint8_t* packed, size_t bytes, float* out, s
         }
     }
     return err;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Half-precision variant (Sec. 3.1.1, "Our approach": the gradients go to 16  */
+/* bits for the transform, whose loss is negligible because gradients are      */
+/* bounded).  What the variant computes, as a definition: the exact DFT of the */
+/* chunk, scaled by a caller-chosen power of two 2^s (so that small gradients  */
+/* do not fall into binary16's subnormals) and each component rounded ONCE to  */
+/* binary16, round-to-nearest-even, saturating at +-65504; selection,          */
+/* Algorithm 1 and packing then work on those binary16 values; the receiver    */
+/* inverts exactly and divides by 2^s.  Where an implementation rounds inside  */
+/* its transform is its own affair: it is held to this definition within the   */
+/* variant's error bound, not bit for bit.  Header word 12 (offset 48) carries */
+/* s, and a decoder accepts only the scale it was asked for.                   */
+/* ------------------------------------------------------------------------ */
+static float round_half(double v)
+{
+    if (v != v) return (float)v;
+    double a = fabs(v);
+    double r;
+    if (a >= 65504.0) {
+        r = 65504.0;
+    } else if (a == 0.0) {
+        r = 0.0;
+    } else {
+        int e;
+        frexp(a, &e); /* a = f * 2^e, f in [0.5, 1): floor(log2 a) = e - 1 */
+        double q = (e - 1 < -14) ? ldexp(1.0, -24) : ldexp(1.0, e - 1 - 10);
+        r = nearbyint(a / q) * q; /* a/q is exact; default rounding mode: ties to even */
+        if (r > 65504.0) r = 65504.0;
+    }
+    return (float)(signbit(v) ? -r : r);
+}
+
+float fftsp_ref_round_half(double v) { return round_half(v); }
+
+static int half_scale_ok(int s) { return s >= -24 && s <= 24; }
+
+int fftsp_ref_rfft_h(const float* g, size_t n, uint32_t L, int scale_log2, float* spec, int nthreads)
+{
+    if (!g || !spec || n == 0 || L < 2 || !is_pow2(L) || !half_scale_ok(scale_log2)) return REF_EINVAL;
+    long C = (long)chunk_count(n, L);
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
+    for (long c = 0; c < C; ++c) {
+        int e = rfft_chunk_ex(g + (size_t)c * L, chunk_valid(n, L, (size_t)c), L, spec + (size_t)c * (L + 2), 1,
+                              scale_log2);
+        if (e) {
+#pragma omp atomic write
+            err = e;
+        }
+    }
+    return err;
+}
+
+int fftsp_ref_compress_h(const float* g, size_t n, uint32_t L, float theta, int bits, int scale_log2, uint8_t* packed,
+                         size_t cap, int nthreads)
+{
+    if (!g || !packed || n == 0 || L < 2 || !is_pow2(L) || !half_scale_ok(scale_log2)) return REF_EINVAL;
+    size_t C = chunk_count(n, L);
+    float* spec = (float*)malloc(sizeof(float) * C * ((size_t)L + 2));
+    if (!spec) return REF_ENOSPC;
+    int e = fftsp_ref_rfft_h(g, n, L, scale_log2, spec, nthreads);
+    if (!e) e = fftsp_ref_encode_spectrum(spec, n, L, theta, bits, packed, cap, nthreads);
+    if (!e) put_u32(packed + 48, (uint32_t)scale_log2);
+    free(spec);
+    return e;
+}
+
+int fftsp_ref_decompress_h(const uint8_t* packed, size_t bytes, float* out, size_t n, uint32_t L, float theta, int bits,
+                           int scale_log2, int nthreads)
+{
+    if (!out || !packed || n == 0 || L < 2 || !is_pow2(L) || !half_scale_ok(scale_log2)) return REF_EINVAL;
+    size_t C = chunk_count(n, L);
+    float* spec = (float*)malloc(sizeof(float) * C * ((size_t)L + 2));
+    if (!spec) return REF_ENOSPC;
+    int e = decode_spectrum_scaled(packed, bytes, n, L, theta, bits, 0, scale_log2, spec, nthreads);
+    if (!e) {
+        int err = 0;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(nthreads > 0 ? nthreads : 1)
+        for (long c = 0; c < (long)C; ++c) {
+            int ec = irfft_chunk_ex(spec + (size_t)c * (L + 2), chunk_valid(n, L, (size_t)c), L, out + (size_t)c * L,
+                                    scale_log2);
+            if (ec) {
+#pragma omp atomic write
+                err = ec;
+            }
+        }
+        e = err;
+    }
+    free(spec);
+    return e;
 }
 
 int fftsp_ref_max_threads(void)

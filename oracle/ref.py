@@ -72,6 +72,10 @@ def lib():
             "fftsp_ref_topk_packed_bytes": (C.c_size_t, [C.c_size_t, C.c_uint32, C.c_float, C.c_int]),
             "fftsp_ref_topk_compress": (C.c_int, [fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, u8p, C.c_size_t, C.c_int]),
             "fftsp_ref_topk_decompress": (C.c_int, [u8p, C.c_size_t, fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int]),
+            "fftsp_ref_round_half": (C.c_float, [C.c_double]),
+            "fftsp_ref_rfft_h": (C.c_int, [fp, C.c_size_t, C.c_uint32, C.c_int, fp, C.c_int]),
+            "fftsp_ref_compress_h": (C.c_int, [fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int, u8p, C.c_size_t, C.c_int]),
+            "fftsp_ref_decompress_h": (C.c_int, [u8p, C.c_size_t, fp, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int, C.c_int]),
             "fftsp_ref_max_threads": (C.c_int, []),
         }
         for name, (res, args) in sig.items():
@@ -329,6 +333,37 @@ def decompress_segments(packed, seg_offsets, theta, bits, nthreads=1):
     return out
 
 
+# ---- half-precision variant (Sec. 3.1.1, "Our approach"): spectrum scaled by 2^scale_log2, rounded once to binary16
+def round_half(v) -> float:
+    return float(lib().fftsp_ref_round_half(float(v)))
+
+
+def rfft_h(g, L, scale_log2=0, nthreads=1):
+    g, gp = _f32(g)
+    spec = np.empty(n_chunks(g.size, L) * (L + 2), dtype=np.float32)
+    _chk(lib().fftsp_ref_rfft_h(gp, g.size, L, scale_log2, spec.ctypes.data_as(C.POINTER(C.c_float)), nthreads), "rfft_h")
+    return spec
+
+
+def compress_h(g, L, theta, bits, scale_log2=0, nthreads=1):
+    g, gp = _f32(g)
+    nb = packed_bytes(g.size, L, theta, bits)
+    if nb == 0:
+        raise OracleError(EINVAL, "compress_h")
+    out = np.empty(nb, dtype=np.uint8)
+    _chk(lib().fftsp_ref_compress_h(gp, g.size, L, np.float32(theta), bits, scale_log2,
+                                    out.ctypes.data_as(C.POINTER(C.c_uint8)), nb, nthreads), "compress_h")
+    return out
+
+
+def decompress_h(packed, n, L, theta, bits, scale_log2=0, nthreads=1):
+    packed, pp = _u8(packed)
+    out = np.empty(n, dtype=np.float32)
+    _chk(lib().fftsp_ref_decompress_h(pp, packed.size, out.ctypes.data_as(C.POINTER(C.c_float)), n, L,
+                                      np.float32(theta), bits, scale_log2, nthreads), "decompress_h")
+    return out
+
+
 # ---- time-domain Top-k (Sec. 4, "Choice of Algorithms"): same selector, quantizer and packing, no transform ----
 def topk_kept_per_chunk(L, theta) -> int:
     k = C.c_uint32(0)
@@ -380,7 +415,7 @@ def parse_header(packed):
     u32 = lambda o: int(p[o:o + 4].view("<u4")[0])
     return dict(magic=bytes(p[0:4]), version=u32(4), n=int(p[8:16].view("<u8")[0]), L=u32(16), C=u32(20),
                 bits=u32(24), m=u32(28), k=u32(32), S=u32(36), theta=float(p[40:44].view("<f4")[0]),
-                domain=u32(44))
+                domain=u32(44), scale_log2=int(p[48:52].view("<i4")[0]))
 
 
 def record_fields(packed, L, c=0):

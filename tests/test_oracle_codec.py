@@ -73,7 +73,7 @@ def test_layout_and_roundtrip_of_codes(ref, bits, L, theta):
     assert S == -(-(16 + 4 * W + 4 * (-(-2 * k * bits // 32))) // 16) * 16
     assert packed.size == ref.packed_bytes(n, L, theta, bits) == 64 + C * S
     assert h == dict(magic=b"FSP1", version=1, n=n, L=L, C=C, bits=bits, m=m, k=k, S=S, theta=float(np.float32(theta)),
-                     domain=0)
+                     domain=0, scale_log2=0)
     assert not packed[44:64].any()
     X = as_complex(spec, L)
     dec = as_complex(ref.decode_spectrum(packed, n, L, theta, bits), L)
