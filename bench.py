@@ -108,6 +108,65 @@ def measure_topk(fftsp, torch, gd, out, n, L, theta, bits, steps, stream):
                     "here; tests/test_oracle_topk.py pins the ordering of the paper's figure on a signal with a trend"}
 
 
+def half_kernel_bytes(name: str, n: int, L: int, theta: float, bits: int) -> float:
+    """The same for the half-precision variant: intermediate and spectrum are binary16 pairs (4 bytes per value)."""
+    C = (n + L - 1) // L
+    bins = C * (L // 2 + 1)
+    spec, mid = 4.0 * bins, 2.0 * C * L
+    payload = bins / 8.0 + 2.0 * C * round(theta * (L // 2 + 1)) * bits / 8.0
+    table = {"rfft_pass_a": 4.0 * n + mid, "rfft_pass_b": mid + spec, "collect": spec, "emit": spec + payload,
+             "group_prefix": bins / 8.0 + bins / (8.0 * 16), "decode": payload + spec, "irfft_pass_b": spec + mid,
+             "irfft_pass_a": mid + 4.0 * n}
+    return table.get(name, 0.0)
+
+
+def measure_half(fftsp, torch, gd, out, n, L, theta, bits, scale_log2, steps, stream):
+    """Half-precision variant (Sec. 3.1.1: the gradients go to 16 bits for the transform): the same step with the
+    two-pass intermediate and the spectrum stored as binary16 pairs."""
+    import numpy as np
+    dev = gd[0].device
+    nb = fftsp.packed_bytes(n, L, theta, bits)
+    ws = torch.empty(fftsp.workspace_bytes(n, L, bits), dtype=torch.uint8, device=dev)
+    packed = [torch.empty(nb, dtype=torch.uint8, device=dev) for _ in gd]
+
+    def step(i):
+        s = i % len(gd)
+        fftsp.compress_h(gd[s], L, theta, bits, scale_log2, packed[s], ws, stream)
+        fftsp.decompress_h(packed[s], nb, out[s], L, theta, bits, scale_log2, ws, stream)
+
+    for i in range(3):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / steps
+    assert fftsp.device_status(ws) == 0
+    fftsp.profile_enable(True)
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    kern = fftsp.profile_report()
+    fftsp.profile_enable(False)
+    us = {k: v[1] * 1e3 / v[0] for k, v in kern.items()}
+    dom = max(us, key=us.get)
+    dom_bytes = half_kernel_bytes(dom, n, L, theta, bits)
+    s = (steps - 1) % len(gd)
+    src = gd[s].cpu().numpy().astype(np.float64)
+    alpha = float(np.linalg.norm(out[s].cpu().numpy() - src) / np.linalg.norm(src))
+    p = theta * bits / 8.0 + 1.0 / 16.0
+    return {"theta_kept": theta, "bits": bits, "scale_log2": scale_log2, "ms_per_step": round(sec * 1e3, 4),
+            "GBps": round(4.0 * n / sec / 1e9, 2),
+            "hbm_frac_whole_path": round((8.0 + 2.0 * p) * n / sec / 1e9 / HBM_PEAK_GBS, 4),
+            "kernels_avg_us": {k: round(v, 2) for k, v in us.items()},
+            "roofline": {"bound": "hbm", "kernel": dom, "achieved": round(dom_bytes / us[dom] / 1e3, 1),
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dom_bytes / us[dom] / 1e3 / HBM_PEAK_GBS, 4),
+                         "algorithmic_bytes_per_launch": int(dom_bytes)},
+            "alpha": round(alpha, 5),
+            "note": "own parity bound 1.5e-3 (two binary16 roundings), not the 1e-5 of the headline path"}
+
+
 def measured_traffic_bytes(kernel: str):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE + WRITE_SIZE, each
     scaled by the plain-copy calibration stated in that file), or None if the summary does not cover it."""
@@ -135,6 +194,8 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true", help="also time theta in {.1,.3,.7,.9} (extra keys)")
     ap.add_argument("--topk", action="store_true",
                     help="time only the time-domain Top-k baseline at --theta/--bits and print its own line")
+    ap.add_argument("--half", action="store_true",
+                    help="time only the half-precision variant at --theta/--bits (scale 2^10) and print its own line")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra timings (static-range sender, eight-peer receiver): only the headline path runs")
     args = ap.parse_args()
@@ -169,6 +230,15 @@ def main() -> int:
                   "value": r["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": 3,
                   "higher_is_better": True, "dtype": "u32", "data": "synthetic", "vs_baseline": None,
                   "config": {"workload": "config3 gradient, chunk 2^20, time-domain Top-k"}})
+        print(json.dumps(r))
+        return 0
+
+    if args.half:
+        r = measure_half(fftsp, torch, gd, out, n, L, args.theta, bits, 10, args.steps, stream)
+        r.update({"metric": "half-precision-variant codec GB/s of fp32 gradient (compress+decompress), AlexNet-shaped 61M",
+                  "value": r["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": 3,
+                  "higher_is_better": True, "dtype": "f16 storage, f32 arithmetic", "data": "synthetic",
+                  "vs_baseline": None, "config": {"workload": "config3 gradient, chunk 2^20, half-precision variant"}})
         print(json.dumps(r))
         return 0
 
@@ -316,6 +386,10 @@ def main() -> int:
                                          "packed_GBps_in": round(peers * nbytes / t_acc / 1e9, 2),
                                          "gradient_GBps_equivalent": round(peers * 4.0 * n / t_acc / 1e9, 2)}
         del peer_packed, ws_acc
+
+        # the paper's own half-precision transform (Sec. 3.1.1), same kept fraction and code width as the headline
+        result["half_precision_variant"] = measure_half(fftsp, torch, gd, out, n, L, args.theta, bits, 10,
+                                                        max(3, args.steps // 2), stream)
 
         # the sparsifier the paper compares against, at its setting (Sec. 4: 85 % dropped, 32-bit values)
         result["time_domain_topk"] = measure_topk(fftsp, torch, gd, out, n, L, 0.15, 32, max(3, args.steps // 2), stream)

@@ -157,6 +157,27 @@ int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, u
                           float theta, int bits, float* d_spec,
                           void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
 
+/* ---- half-precision variant (Sec. 3.1.1, "Our approach": the gradients go to 16 bits for the transform, a loss
+ *      the paper calls negligible because gradients are bounded).  Definition: the chunk's DFT times 2^scale_log2,
+ *      each component rounded to binary16 (nearest even, saturating at +-65504); selection, Algorithm 1 and packing
+ *      as in fftsp_compress on those values; the receiver inverts and divides by 2^scale_log2.  Here the arithmetic
+ *      stays binary32 and it is the stored intermediate of the two-pass transform and the stored spectrum that are
+ *      binary16 (these kernels are bound by bytes, not by arithmetic), so a result differs from the definition by
+ *      one more binary16 rounding inside the transform: about 5e-4 relative L2 on a spectrum, against the 1e-5 of
+ *      the binary32 path.  scale_log2 in [-24, 24] is the caller's: choose it so that spectrum magnitudes
+ *      (about 2^scale_log2 * sigma * sqrt(chunk_len)) sit well inside binary16's normal range [6e-5, 65504].
+ *      The stream layout is that of fftsp_compress with header word 12 (offset 48) = scale_log2; fftsp_decompress
+ *      rejects a stream with a non-zero scale and fftsp_decompress_h one with another scale (status
+ *      FFTSP_EFORMAT).  chunk_len: power of two in [2^15, 2^22] (FFTSP_EUNSUPPORTED below: one workgroup
+ *      transforms such a chunk without touching memory in between).  Everything else as fftsp_compress /
+ *      fftsp_decompress, including packed and workspace sizes (fftsp_packed_bytes, fftsp_workspace_bytes). ---- */
+int fftsp_compress_h(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, int scale_log2,
+                     void* d_packed, size_t packed_capacity,
+                     void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+int fftsp_decompress_h(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n,
+                       uint32_t chunk_len, float theta, int bits, int scale_log2,
+                       void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
+
 /* ---- time-domain Top-k, the sparsifier the paper measures its own against (Sec. 4, "Choice of Algorithms";
  *      the Sec. 3.1.1 figure sets it beside FFT Top-k): the magnitude selection (Sec. 3.1.1), Algorithm 1 and the
  *      packing of Sec. 3.2 applied to the gradient's samples themselves, no transform.  Chunk c is samples

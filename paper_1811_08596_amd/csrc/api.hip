@@ -494,6 +494,76 @@ int fftsp_decompress_accumulate(const void* const* d_packed, int npeers, size_t 
     return hip_status(e);
 }
 
+/* ---------------- half-precision variant: binary16 between the passes and in the spectrum ---------------- */
+
+namespace {
+constexpr int kHalfMinLogL = 15;  // the two-pass FFT starts here; shorter chunks do not need the variant
+bool half_scale_ok(int s) { return s >= -24 && s <= 24; }
+}  // namespace
+
+int fftsp_compress_h(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, int scale_log2,
+                     void* d_packed, size_t packed_capacity, void* d_workspace, size_t workspace_bytes,
+                     fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    if (p.logL < kHalfMinLogL) return FFTSP_EUNSUPPORTED;
+    if (!half_scale_ok(scale_log2)) return FFTSP_EINVAL;
+    if (!d_grad || !d_packed || !d_workspace || !aligned16(d_grad) || !aligned16(d_packed) || !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_capacity < kStreamHeader + p.C * p.S) return FFTSP_ENOSPC;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    uint8_t* out = static_cast<uint8_t*>(d_packed);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    CodecArgs a = codec_args(p, theta);
+    a.sstride = padded_bins(p.L);
+    a.half = 1;
+    a.hdr_scale = scale_log2;
+    hipError_t e = launch_rfft_half(d_grad, n, p.logL, p.C, ws + p.ws.spec, a.sstride, ws + p.ws.mid, t,
+                                    reinterpret_cast<uint32_t*>(ws + p.ws.hist),
+                                    reinterpret_cast<uint32_t*>(ws + p.ws.status),
+                                    (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, std::ldexp(1.0f, scale_log2),
+                                    &a.pair_log, s);
+    if (e == hipSuccess)
+        e = launch_encode(reinterpret_cast<const float*>(ws + p.ws.spec), a, out, out + kStreamHeader, ws, p.ws, 1, s);
+    return hip_status(e);
+}
+
+int fftsp_decompress_h(const void* d_packed, size_t packed_bytes, float* d_grad_out, size_t n, uint32_t chunk_len,
+                       float theta, int bits, int scale_log2, void* d_workspace, size_t workspace_bytes,
+                       fftsp_stream_t stream)
+{
+    Plan p;
+    int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    if (p.logL < kHalfMinLogL) return FFTSP_EUNSUPPORTED;
+    if (!half_scale_ok(scale_log2)) return FFTSP_EINVAL;
+    if (!d_grad_out || !d_packed || !d_workspace || !aligned16(d_grad_out) || !aligned16(d_packed) ||
+        !aligned16(d_workspace))
+        return FFTSP_EINVAL;
+    if (packed_bytes < kStreamHeader + p.C * p.S) return FFTSP_EFORMAT;
+    if (workspace_bytes < p.ws.total) return FFTSP_EWORKSPACE;
+    Tables t;
+    if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
+    uint8_t* ws = static_cast<uint8_t*>(d_workspace);
+    const uint8_t* in = static_cast<const uint8_t*>(d_packed);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    CodecArgs a = codec_args(p, theta);
+    a.sstride = padded_bins(p.L);
+    a.pair_log = fft_pair_log(p.logL);
+    a.half = 1;
+    a.hdr_scale = scale_log2;
+    hipError_t e = launch_decode(in, in + kStreamHeader, a, reinterpret_cast<float*>(ws + p.ws.spec), ws, p.ws, 1, 1, s);
+    if (e == hipSuccess)
+        e = launch_irfft_half(ws + p.ws.spec, a.sstride, n, p.logL, p.C, d_grad_out, ws + p.ws.mid, t,
+                              std::ldexp(1.0f, -scale_log2), s);
+    return hip_status(e);
+}
+
 /* ---------------- time-domain Top-k: the same select / quantize / pack kernels, no transform ---------------- */
 
 int fftsp_topk_kept_per_chunk(uint32_t chunk_len, float theta, uint32_t* k_out)

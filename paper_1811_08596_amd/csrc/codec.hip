@@ -86,6 +86,36 @@ __device__ __forceinline__ void tile_to_lds(const float2* __restrict__ X, uint32
     }
 }
 
+// The same from a spectrum stored as binary16 pairs (half-precision variant): converted on the way into LDS, so
+// everything behind it works on binary32 values as before.
+__device__ __forceinline__ void tile_to_lds(const uint32_t* __restrict__ X, uint32_t tbase, uint32_t count,
+                                            uint32_t sstride, float2* stage, int tid)
+{
+    if (count == (uint32_t)kTile && (sstride & 3u) == 0) {  // four bins per 16 bytes
+        const uint4* src = reinterpret_cast<const uint4*>(X + tbase);
+        float4* dst = reinterpret_cast<float4*>(stage);
+#pragma unroll
+        for (int i = 0; i < kTile / 4 / kTileThreads; ++i) {
+            const int idx = tid + i * kTileThreads;
+            const uint4 v = src[idx];
+            dst[2 * idx] = cx_load(make_uint2(v.x, v.y));
+            dst[2 * idx + 1] = cx_load(make_uint2(v.z, v.w));
+        }
+    } else {
+        for (uint32_t i = tid; i < count; i += kTileThreads) stage[i] = unpack_half2(X[tbase + i]);
+    }
+}
+
+// What a kernel's input or output array holds: samples (time domain), or complex bins as binary32 or binary16 pairs.
+template <bool REAL, bool HALF>
+struct Stored {
+    using T = typename Cx<HALF>::One;
+};
+template <bool HALF>
+struct Stored<true, HALF> {
+    using T = float;
+};
+
 // Time domain: samples [tbase, tbase + kTile) of a chunk, zeros from `present` on.
 __device__ __forceinline__ void tile_to_lds(const float* __restrict__ X, uint32_t tbase, uint32_t present, float* stage,
                                             int tid)
@@ -313,9 +343,9 @@ __global__ __launch_bounds__(NT) void k_find_bucket(const uint32_t* __restrict__
 
 // --------------------------------------------------------------- collect ----
 // Per tile: count and range of the bins kept outright, and the candidates in bin order.
-template <bool REAL>
-__global__ __launch_bounds__(NT) void k_collect(const typename Elem<REAL>::T* __restrict__ spec, uint32_t sstride, int pair_log,
-                                                uint32_t B, uint32_t Tn, const uint32_t* __restrict__ sel,
+template <bool REAL, bool HALF>
+__global__ __launch_bounds__(NT) void k_collect(const typename Stored<REAL, HALF>::T* __restrict__ spec, uint32_t sstride,
+                                                int pair_log, uint32_t B, uint32_t Tn, const uint32_t* __restrict__ sel,
                                                 uint32_t* __restrict__ tinfo, uint2* __restrict__ cand, size_t n)
 {
     using E = typename Elem<REAL>::T;
@@ -324,7 +354,7 @@ __global__ __launch_bounds__(NT) void k_collect(const typename Elem<REAL>::T* __
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const size_t c = blockIdx.x / Tn;
     const uint32_t tile = blockIdx.x % Tn;
-    const E* X = spec + c * (size_t)sstride;
+    const typename Stored<REAL, HALF>::T* X = spec + c * (size_t)sstride;
     const uint32_t tbase = tile * kTile;
     if constexpr (REAL)
         tile_to_lds(X, tbase, present_of<REAL>(n, c, B), stage, tid);
@@ -453,6 +483,7 @@ struct HeaderInfo {
     uint32_t L, C, N, m, k, S;
     float theta;
     uint32_t domain;  // 0: records hold frequency bins, 1: samples (time-domain Top-k)
+    uint32_t scale;   // log2 of the factor on the spectrum (two's complement; half-precision variant), else 0
 };
 
 // One workgroup per chunk: finish the radix select on the candidates, break ties by bin order,
@@ -729,6 +760,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             case 9: v = hdr.S; break;
             case 10: v = __float_as_uint(hdr.theta); break;
             case 11: v = hdr.domain; break;
+            case 12: v = hdr.scale; break;
             default: break;
         }
         reinterpret_cast<uint32_t*>(stream)[tid] = v;
@@ -737,8 +769,8 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
 
 // ------------------------------------------------------------------ emit ----
 // Per tile: flags, ranks, Algorithm 1 codes, bit-packing, bitmap words.
-template <bool TABLE, bool REAL>
-__global__ __launch_bounds__(NT) void k_emit(const typename Elem<REAL>::T* __restrict__ spec, uint32_t sstride, int pair_log,
+template <bool TABLE, bool REAL, bool HALF>
+__global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::T* __restrict__ spec, uint32_t sstride, int pair_log,
                                              uint32_t B, uint32_t Tn, uint32_t W, int bits, int m, size_t S,
                                              const uint32_t* __restrict__ sel, const uint32_t* __restrict__ tscan,
                                              uint8_t* __restrict__ records, TableArg<TABLE> tab, size_t n)
@@ -758,7 +790,7 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Elem<REAL>::T* __res
     const uint32_t lds_words = (uint32_t)kTile * twoN / 32u + 2u;
 
     // the spectrum tile is staged in the LDS words that later hold the packed codes
-    const E* X = spec + c * (size_t)sstride;
+    const typename Stored<REAL, HALF>::T* X = spec + c * (size_t)sstride;
     E* stage = reinterpret_cast<E*>(cw);
     static_assert(sizeof(cw) >= kTile * sizeof(float2), "the code buffer doubles as the tile staging area");
     const uint32_t tbase = tile * kTile;
@@ -937,7 +969,7 @@ __device__ __forceinline__ void group_prefix_chunk(const uint8_t* __restrict__ s
             const uint32_t* h = reinterpret_cast<const uint32_t*>(stream);
             bad = bad || h[0] != 0x31505346u || h[1] != 1u || h[2] != (uint32_t)hdr.n ||
                   h[3] != (uint32_t)(hdr.n >> 32) || h[4] != hdr.L || h[5] != hdr.C || h[6] != hdr.N ||
-                  h[7] != hdr.m || h[8] != hdr.k || h[9] != hdr.S || h[11] != hdr.domain;
+                  h[7] != hdr.m || h[8] != hdr.k || h[9] != hdr.S || h[11] != hdr.domain || h[12] != hdr.scale;
         }
         *verdict = bad ? 6u : 0u;
     }
@@ -1004,12 +1036,14 @@ struct DecItem {
 // One stream.
 // REAL: time-domain records (one code per kept sample); `spec` is then the gradient itself, chunk stride B = L
 // samples, written up to sample n only.
-template <int NL, bool VEC, bool TABLE, bool REAL>
+// HALF: the spectrum is written as binary16 pairs (half-precision variant).
+template <int NL, bool VEC, bool TABLE, bool REAL, bool HALF>
 __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ records, size_t S, uint32_t B, uint32_t W,
                                                uint32_t k, int bits, int m, uint32_t Tn, uint32_t total, size_t C,
                                                const uint32_t* __restrict__ gprefix, const uint32_t* __restrict__ sel,
-                                               uint32_t* __restrict__ status, typename Elem<REAL>::T* __restrict__ spec,
-                                               uint32_t sstride, int pair_log, TableArg<TABLE> tab, size_t n)
+                                               uint32_t* __restrict__ status,
+                                               typename Stored<REAL, HALF>::T* __restrict__ spec, uint32_t sstride,
+                                               int pair_log, TableArg<TABLE> tab, size_t n)
 {
     using E = typename Elem<REAL>::T;
     constexpr uint32_t CODES = Elem<REAL>::kCodes;
@@ -1124,7 +1158,7 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
             if (j < B) stage[slot_of(slots, r, j0, tbase, pair_log)] = out;
         }
         __syncthreads();
-        E* X = spec + (size_t)(t / Tn) * (size_t)sstride;
+        typename Stored<REAL, HALF>::T* X = spec + (size_t)(t / Tn) * (size_t)sstride;
         if constexpr (REAL) {
             // samples of this tile that exist in the gradient (the last chunk may end inside or before the tile)
             const uint32_t present = present_of<REAL>(n, t / Tn, B);
@@ -1136,6 +1170,22 @@ __global__ __launch_bounds__(NT) void k_decode(const uint8_t* __restrict__ recor
                 for (int i = 0; i < kTile / 4 / NT; ++i) dst[tid + i * NT] = src[tid + i * NT];
             } else {
                 for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = stage[i];
+            }
+        } else if constexpr (HALF) {
+            const uint32_t count = B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile;
+            if constexpr (VEC) {  // four bins per 16-byte store; up to three land in the chunk's padding
+                uint4* dst = reinterpret_cast<uint4*>(X + tbase);
+                const float4* src = reinterpret_cast<const float4*>(stage);
+#pragma unroll
+                for (int i = 0; i < kTile / 4 / NT; ++i) {
+                    const uint32_t idx = (uint32_t)(tid + i * NT);
+                    if (4u * idx < count) {
+                        const uint2 a = cx_store<true>(src[2 * idx]), b = cx_store<true>(src[2 * idx + 1]);
+                        dst[idx] = make_uint4(a.x, a.y, b.x, b.y);
+                    }
+                }
+            } else {
+                for (uint32_t i = tid; i < count; i += NT) X[tbase + i] = pack_half2(stage[i]);
             }
         } else {
             const uint32_t count = B - tbase < (uint32_t)kTile ? B - tbase : (uint32_t)kTile;
@@ -1373,6 +1423,9 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     uint2* cand = reinterpret_cast<uint2*>(ws_base + w.cand);
     if (a.C * (size_t)Tn > 0x7fffffffu || Tn > (uint32_t)MAX_TILES) return hipErrorInvalidValue;
     if (a.time_domain && (a.tab || a.pair_log || hist_ready)) return hipErrorInvalidValue;
+    // binary16 spectra come from the two-pass FFT only, which also fills the histogram
+    if (a.half && (a.tab || a.time_domain || !a.pair_log || !hist_ready)) return hipErrorInvalidValue;
+    const uint32_t* Xh = reinterpret_cast<const uint32_t*>(spec);
 
     if (!hist_ready) {
         hipError_t e = launch_zero_hist(ws_base, w, a.C, s);
@@ -1388,13 +1441,16 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     }
     FFTSP_LAUNCH("find_bucket", k_find_bucket, dim3((unsigned)a.C), dim3(NT), 0, s, hist, a.k, sel);
     if (a.time_domain)
-        FFTSP_LAUNCH("collect", k_collect<true>, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, spec, a.sstride, 0, B, Tn,
-                     sel, tinfo, cand, a.n);
+        FFTSP_LAUNCH("collect", (k_collect<true, false>), dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, spec, a.sstride, 0,
+                     B, Tn, sel, tinfo, cand, a.n);
+    else if (a.half)
+        FFTSP_LAUNCH("collect", (k_collect<false, true>), dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, Xh, a.sstride,
+                     a.pair_log, B, Tn, sel, tinfo, cand, a.n);
     else
-        FFTSP_LAUNCH("collect", k_collect<false>, dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride, a.pair_log, B,
-                     Tn, sel, tinfo, cand, a.n);
+        FFTSP_LAUNCH("collect", (k_collect<false, false>), dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, X, a.sstride,
+                     a.pair_log, B, Tn, sel, tinfo, cand, a.n);
     HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
-                 a.hdr_theta, a.time_domain ? 1u : 0u};
+                 a.hdr_theta, a.time_domain ? 1u : 0u, (uint32_t)a.hdr_scale};
     const uint32_t codes_per_bin = a.time_domain ? 1u : 2u;
     // up to 12 Ki candidates (96 KiB) are staged in LDS by the per-chunk workgroup
     constexpr uint32_t kStageCap = 12 * 1024;
@@ -1413,18 +1469,20 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     FFTSP_LAUNCH("resolve", k_resolve<TABLE>, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k,   \
                  a.bits, a.m, W, a.S, a.word3, kStageCap, a.static_vmax, codes_per_bin, sel, tinfo, tscan, cand,      \
                  records, stream_base, h, table_arg<TABLE>(a.tab))
-#define FFTSP_EMIT(TABLE, REAL, src)                                                                                  \
-    FFTSP_LAUNCH("emit", (k_emit<TABLE, REAL>), dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, src, a.sstride,           \
+#define FFTSP_EMIT(TABLE, REAL, HALF, src)                                                                            \
+    FFTSP_LAUNCH("emit", (k_emit<TABLE, REAL, HALF>), dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, src, a.sstride,     \
                  a.pair_log, B, Tn, W, a.bits, a.m, a.S, sel, tscan, records, table_arg<TABLE>(a.tab), a.n)
     if (a.tab) {
         FFTSP_RESOLVE(true);
-        FFTSP_EMIT(true, false, X);
+        FFTSP_EMIT(true, false, false, X);
     } else {
         FFTSP_RESOLVE(false);
         if (a.time_domain)
-            FFTSP_EMIT(false, true, spec);
+            FFTSP_EMIT(false, true, false, spec);
+        else if (a.half)
+            FFTSP_EMIT(false, false, true, Xh);
         else
-            FFTSP_EMIT(false, false, X);
+            FFTSP_EMIT(false, false, false, X);
     }
 #undef FFTSP_RESOLVE
 #undef FFTSP_EMIT
@@ -1449,20 +1507,25 @@ static hipError_t launch_decode_kernel(const PeerList& recs, uint32_t npeers, co
                          a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                                  \
                          reinterpret_cast<float2*>(spec), a.sstride, a.pair_log);                                  \
         else if (a.tab)                                                                                            \
-            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, true, false>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S,   \
-                         B, W, a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                            \
+            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, true, false, false>), dim3(grid), dim3(NT), 0, s, recs.p[0], \
+                         a.S, B, W, a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                       \
                          reinterpret_cast<float2*>(spec), a.sstride, a.pair_log, table_arg<true>(a.tab), a.n);     \
+        else if (a.half)                                                                                           \
+            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false, false, true>), dim3(grid), dim3(NT), 0, s, recs.p[0], \
+                         a.S, B, W, a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                       \
+                         reinterpret_cast<uint32_t*>(spec), a.sstride, a.pair_log, table_arg<false>(a.tab), a.n);  \
         else                                                                                                       \
-            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false, false>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S,  \
-                         B, W, a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,                            \
+            FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false, false, false>), dim3(grid), dim3(NT), 0, s,           \
+                         recs.p[0], a.S, B, W, a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status,            \
                          reinterpret_cast<float2*>(spec), a.sstride, a.pair_log, table_arg<false>(a.tab), a.n);    \
     } while (0)
+    if (a.half && (peers_layout || a.tab || a.time_domain)) return hipErrorInvalidValue;
     if (a.time_domain) {
         // one code per sample: a wave's 512 samples are at most 1 KiB of codes up to 16 bits, 2 KiB at 32
         if (peers_layout || a.tab || a.pair_log) return hipErrorInvalidValue;
         const bool vec16 = (reinterpret_cast<uintptr_t>(spec) & 15u) == 0;
 #define FFTSP_DECODE_REAL(NL, VEC)                                                                                 \
-    FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false, true>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W,     \
+    FFTSP_LAUNCH("decode", (k_decode<NL, VEC, false, true, false>), dim3(grid), dim3(NT), 0, s, recs.p[0], a.S, B, W, \
                  a.k, a.bits, a.m, Tn, total, a.C, gprefix, verd, status, spec, a.sstride, 0,                      \
                  table_arg<false>(nullptr), a.n)
         if (a.bits <= 16) {
@@ -1503,7 +1566,7 @@ hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, con
     uint32_t* gprefix = reinterpret_cast<uint32_t*>(ws_base + w.prefix);
     if (a.C * (size_t)Tn > 0x7fffffffu) return hipErrorInvalidValue;
     HeaderInfo h{check_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
-                 a.hdr_theta, a.time_domain ? 1u : 0u};
+                 a.hdr_theta, a.time_domain ? 1u : 0u, (uint32_t)a.hdr_scale};
     if (a.tab && a.C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
     if (a.tab)
         FFTSP_LAUNCH("group_prefix", k_group_prefix<true>, dim3((unsigned)a.C), dim3(RT), 0, s, stream_base, records, a.S,
@@ -1525,7 +1588,7 @@ hipError_t launch_decode_peers(const PeerList& streams, int npeers, const CodecA
     uint32_t* verd = reinterpret_cast<uint32_t*>(ws_base + pw.verd);
     if (npeers < 1 || npeers > kMaxPeers) return hipErrorInvalidValue;
     if (a.C * (size_t)Tn > 0x7fffffffu || a.C * (size_t)npeers > 0x7fffffffu) return hipErrorInvalidValue;
-    HeaderInfo h{1, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S, a.hdr_theta, 0u};
+    HeaderInfo h{1, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S, a.hdr_theta, 0u, 0u};
     FFTSP_LAUNCH("group_prefix", k_group_prefix_peers, dim3((unsigned)(a.C * (size_t)npeers)), dim3(RT), 0, s, streams,
                  (uint32_t)a.C, a.S, W, a.k, h, gprefix, verd, status);
     PeerList recs{};

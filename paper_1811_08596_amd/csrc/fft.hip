@@ -21,6 +21,7 @@
 // an XOR swizzle that keeps both "b fastest" and "i fastest" wave accesses spread
 // over all banks without padding.
 #include "internal.h"
+#include <cmath>
 
 namespace fftsp {
 namespace {
@@ -430,10 +431,11 @@ __device__ __forceinline__ uint32_t mirror_row(uint32_t kp, uint32_t N1) { retur
 // 16-byte aligned: two columns per 16-byte load, no guards.  Otherwise every element is loaded under a guard
 // (ragged last chunk, unaligned tensors); the two variants are separate loops so that the guarded one does
 // not put branches between the fast one's loads and their use.
-template <int LOGN1, bool FAST, bool TABLE>
-__device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n, int logM, float2* __restrict__ mid,
-                                          const Tables& tb, int aligned, uint32_t t, uint32_t tend, uint32_t tstep, float2* d,
-                                          const float2* tw, int tid0, const TableArg<TABLE>& tab)
+template <int LOGN1, bool FAST, bool TABLE, bool HALF>
+__device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n, int logM,
+                                          typename Cx<HALF>::One* __restrict__ mid, const Tables& tb, int aligned,
+                                          uint32_t t, uint32_t tend, uint32_t tstep, float2* d, const float2* tw, int tid0,
+                                          const TableArg<TABLE>& tab, float in_scale)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT;
@@ -493,11 +495,15 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
             ratio_b[kk] = twiddle(tb, ((uint32_t)DC * kb) << sh);
             cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
             cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
+            if constexpr (HALF) {  // the variant's power-of-two factors ride on the twiddles (exact)
+                cur_a[kk] = make_float2(cur_a[kk].x * in_scale, cur_a[kk].y * in_scale);
+                cur_b[kk] = make_float2(cur_b[kk].x * in_scale, cur_b[kk].y * in_scale);
+            }
         }
         const bool more = t + tstep < tend;
         load_tile(more ? t + tstep : t, tid, more);
         run_fft<LOGN1, LOGT, NT, false>(d, tw, tid);
-        float4* out = reinterpret_cast<float4*>(mid + (size_t)(t / tiles) * (size_t)M);
+        typename Cx<HALF>::Two* out = reinterpret_cast<typename Cx<HALF>::Two*>(mid + (size_t)(t / tiles) * (size_t)M);
 #pragma unroll
         for (int kk = 0; kk < KN; ++kk) {
             const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);  // pair of paired positions (2kp, 2kp+1)
@@ -508,7 +514,7 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
                 const uint32_t col = cfirst + j * DC, n2 = col0 + col;
                 const float2 va = cmul(d[sw_idx<LOGT>((int)ka, (int)col)], cur_a[kk]);
                 const float2 vb = cmul(d[sw_idx<LOGT>((int)kb, (int)col)], cur_b[kk]);
-                out[n2 * (uint32_t)HP + kp] = join(va, vb);
+                out[n2 * (uint32_t)HP + kp] = cx_store<HALF>(join(va, vb));
                 cur_a[kk] = cmul(cur_a[kk], ratio_a[kk]);
                 cur_b[kk] = cmul(cur_b[kk], ratio_b[kk]);
             }
@@ -522,11 +528,11 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
 }
 
 // `aligned`: bit 0 = input is 8-byte aligned, bit 1 = 16-byte aligned.
-template <int LOGN1, bool TABLE>
+template <int LOGN1, bool TABLE, bool HALF>
 __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, size_t n, int logM,
-                                               float2* __restrict__ mid, Tables tb, int aligned, uint32_t total,
-                                               uint32_t per_wg, int glog, uint32_t* __restrict__ zero_ptr, uint32_t zero_words,
-                                               TableArg<TABLE> tab)
+                                               typename Cx<HALF>::One* __restrict__ mid, Tables tb, int aligned,
+                                               uint32_t total, uint32_t per_wg, int glog, uint32_t* __restrict__ zero_ptr,
+                                               uint32_t zero_words, TableArg<TABLE> tab, float in_scale)
 {
     constexpr int NT = kNT, ELEMS = 1 << kLogE;
     // clears the status words and key histograms the next kernels of the sender accumulate into
@@ -549,9 +555,11 @@ __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, siz
         fast = fast && last_chunk_end <= n;
     }
     if (fast)
-        fwd_a_run<LOGN1, true, TABLE>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0, tab);
+        fwd_a_run<LOGN1, true, TABLE, HALF>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0, tab,
+                                            in_scale);
     else
-        fwd_a_run<LOGN1, false, TABLE>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0, tab);
+        fwd_a_run<LOGN1, false, TABLE, HALF>(in, n, logM, mid, tb, aligned, t, tend, 1u << glog, d, tw, tid0, tab,
+                                             in_scale);
 }
 
 __device__ __forceinline__ uint32_t fft_key_of(float2 z)
@@ -565,11 +573,16 @@ __device__ __forceinline__ uint32_t fft_key_of(float2 z)
 // counted into the 12-bit histogram of the chunk (hist); otherwise natural bin order and no histogram.
 // The store loop is free of branches (partner addresses and the rare self-mirrored rows are handled with
 // selects) so that its LDS reads can be issued ahead in batches instead of one wait per read.
-template <int LOGN2, bool CODEC>
-__global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, int logM, float2* __restrict__ spec,
-                                               uint32_t sstride, Tables tb, uint32_t* __restrict__ hist,
-                                               uint32_t total, uint32_t per_wg)
+// HALF (CODEC only): the intermediate is read and the spectrum written as binary16 pairs; the histogram counts
+// the keys of the values as stored, which are the ones the selection will see.
+template <int LOGN2, bool CODEC, bool HALF>
+__global__ __launch_bounds__(kNT) void k_fwd_b(const typename Cx<HALF>::One* __restrict__ mid, int logM,
+                                               typename Cx<HALF>::One* __restrict__ spec, uint32_t sstride, Tables tb,
+                                               uint32_t* __restrict__ hist, uint32_t total, uint32_t per_wg,
+                                               float mid_scale)
 {
+    static_assert(CODEC || !HALF, "binary16 storage is the codec's own");
+    using Two = typename Cx<HALF>::Two;
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, ELEMS = 1 << LOGE;
     constexpr int LOGP = LOGT - 1, P = 1 << LOGP;  // slot pairs per tile
@@ -594,10 +607,10 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
     constexpr int BATCH = 4;  // pairs whose LDS reads are issued together
     static_assert(PER2 % BATCH == 0, "batches divide the store loop");
 
-    float4 r[PER2];
+    Two r[PER2];
     auto load_tile = [&](uint32_t tile, int tid, bool live) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
-        const float4* src = reinterpret_cast<const float4*>(mid + (live ? (size_t)(tile / tiles) * (size_t)M : 0));
+        const Two* src = reinterpret_cast<const Two*>(mid + (live ? (size_t)(tile / tiles) * (size_t)M : 0));
         const uint32_t pp = tile_in_chunk(tile, tiles) * P + p;
 #pragma unroll
         for (int q = 0; q < PER2; ++q) r[q] = src[live ? (uint32_t)(kq0 + q * DK) * (N1 >> 1) + pp : 0u];
@@ -605,7 +618,12 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
     auto fill = [&](int tid) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
 #pragma unroll
-        for (int q = 0; q < PER2; ++q) lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, r[q]);
+        for (int q = 0; q < PER2; ++q) {
+            float4 v = cx_load(r[q]);
+            if constexpr (HALF)  // undo the factor that kept the intermediate inside binary16's range
+                v = make_float4(v.x * mid_scale, v.y * mid_scale, v.z * mid_scale, v.w * mid_scale);
+            lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, v);
+        }
     };
     // one key into the 16-bit LDS histogram (bucket b: word b/2, half b%2); on = false adds nothing
     auto count = [&](float2 x, bool on) {
@@ -629,7 +647,7 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
         load_tile(more ? t + 1 : t, tid, more);
         run_fft<LOGN2, LOGT, NT, false>(d, tw, tid);
         const size_t c = t / tiles;
-        float2* out = spec + c * (size_t)sstride;
+        typename Cx<HALF>::One* out = spec + c * (size_t)sstride;
 #pragma unroll
         for (int q0 = 0; q0 < PER2; q0 += BATCH) {
             float2 a0[BATCH], a1[BATCH], pa[BATCH], pb[BATCH];
@@ -653,17 +671,19 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
                 const float2 xb = split_fwd(a1[u], pb[u], cmul(base_b, wq));
                 if (q == 0) {  // k2 = 0 only here: bin 0 and the Nyquist bin come from Z[0] alone
                     const bool dc = self && kq0 == 0;
-                    const float2 xm = make_float2(a0[u].x - a0[u].y, 0.f);
+                    const typename Cx<HALF>::One xm_st = cx_store<HALF>(make_float2(a0[u].x - a0[u].y, 0.f));
                     if (dc) {
                         xa = make_float2(a0[u].x + a0[u].y, 0.f);
-                        out[M] = xm;
+                        out[M] = xm_st;
                     }
-                    if (CODEC) count(xm, dc);
+                    if (CODEC) count(cx_load(xm_st), dc);
                 }
-                if (CODEC) {
-                    reinterpret_cast<float4*>(out)[((uint32_t)k2 << (logN1 - 1)) + pp] = join(xa, xb);
-                    count(xa, true);
-                    count(xb, true);
+                if constexpr (CODEC) {
+                    const Two st = cx_store<HALF>(join(xa, xb));
+                    reinterpret_cast<Two*>(out)[((uint32_t)k2 << (logN1 - 1)) + pp] = st;
+                    const float4 seen = cx_load(st);  // what the selection will read back
+                    count(lo2(seen), true);
+                    count(hi2(seen), true);
                 } else {
                     out[ka + ((uint32_t)k2 << logN1)] = xa;
                     out[kb + ((uint32_t)k2 << logN1)] = xb;
@@ -694,10 +714,15 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const float2* __restrict__ mid, i
 
 // Inverse pass B: undo the split, inverse N2-point FFTs over k2, times conj W_M^(n2 k1).
 // PAIR: the spectrum is read in the paired order (the codec's own buffer), otherwise in natural bin order.
-template <int LOGN2, bool PAIR>
-__global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, uint32_t sstride, int logM,
-                                               float2* __restrict__ mid, Tables tb, uint32_t total, uint32_t per_wg)
+// HALF (PAIR only): spectrum and intermediate are binary16 pairs.
+template <int LOGN2, bool PAIR, bool HALF>
+__global__ __launch_bounds__(kNT) void k_inv_b(const typename Cx<HALF>::One* __restrict__ spec, uint32_t sstride, int logM,
+                                               typename Cx<HALF>::One* __restrict__ mid, Tables tb, uint32_t total,
+                                               uint32_t per_wg, float mid_scale)
 {
+    static_assert(PAIR || !HALF, "binary16 storage is the codec's own");
+    using One = typename Cx<HALF>::One;
+    using Two = typename Cx<HALF>::Two;
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N2 = 1 << LOGN2, LOGT = LOGE - LOGN2, ELEMS = 1 << LOGE;
     constexpr int LOGP = LOGT - 1, P = 1 << LOGP;
@@ -715,17 +740,18 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
     constexpr int DK = NT >> LOGP;
     static_assert(PER2 <= 8, "twiddle recurrence is anchored once");
 
-    float4 r[PER2];
-    float2 xnyq, base_a, base_b;  // Nyquist bin and split twiddles of the tile held in r
+    Two r[PER2];
+    One xnyq;                // Nyquist bin of the chunk of the tile held in r
+    float2 base_a, base_b;   // split twiddles of that tile
     auto load_tile = [&](uint32_t tile, int tid, bool live) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
-        const float2* X = spec + (live ? (size_t)(tile / tiles) * (size_t)sstride : 0);
+        const One* X = spec + (live ? (size_t)(tile / tiles) * (size_t)sstride : 0);
         const uint32_t pp = tile_in_chunk(tile, tiles) * P + p;
         const uint32_t ka = pp, kb = mirror_row(pp, N1);
         base_a = twiddle(tb, (ka + ((uint32_t)kq0 << logN1)) << (21 - logM));
         base_b = twiddle(tb, (kb + ((uint32_t)kq0 << logN1)) << (21 - logM));
-        if (PAIR) {
-            const float4* X4 = reinterpret_cast<const float4*>(X);
+        if constexpr (PAIR) {
+            const Two* X4 = reinterpret_cast<const Two*>(X);
 #pragma unroll
             for (int q = 0; q < PER2; ++q) r[q] = X4[live ? ((uint32_t)(kq0 + q * DK) << (logN1 - 1)) + pp : 0u];
         } else {
@@ -740,7 +766,7 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
     auto fill = [&](int tid) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
 #pragma unroll
-        for (int q = 0; q < PER2; ++q) lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, r[q]);
+        for (int q = 0; q < PER2; ++q) lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, cx_load(r[q]));
     };
     load_tile(t, tid0, true);
     fill(tid0);
@@ -765,13 +791,14 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
             const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
-            float2 a0 = lo2(r[q]), b0 = pa[q];
+            const float4 rq = cx_load(r[q]);
+            float2 a0 = lo2(rq), b0 = pa[q];
             if (q == 0) {  // k2 = 0 only here; imaginary parts of the DC and Nyquist bins are ignored
                 const bool dc = self && kq0 == 0;
-                b0 = dc ? make_float2(xnyq.x, 0.f) : b0;
+                b0 = dc ? make_float2(cx_load(xnyq).x, 0.f) : b0;
                 a0.y = dc ? 0.f : a0.y;
             }
-            z[q] = join(split_inv(a0, b0, cmul(base_a, wq)), split_inv(hi2(r[q]), pb[q], cmul(base_b, wq)));
+            z[q] = join(split_inv(a0, b0, cmul(base_a, wq)), split_inv(hi2(rq), pb[q], cmul(base_b, wq)));
         }
         __syncthreads();
 #pragma unroll
@@ -783,15 +810,19 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
         const float2 ratio_b = twiddle(tb, ((uint32_t)DK * kb) << sh);
         float2 cur_a = twiddle(tb, ((uint32_t)kq0 * ka) << sh);
         float2 cur_b = twiddle(tb, ((uint32_t)kq0 * kb) << sh);
+        if constexpr (HALF) {  // keeps the unnormalised partial sums inside binary16's range (exact power of two)
+            cur_a = make_float2(cur_a.x * mid_scale, cur_a.y * mid_scale);
+            cur_b = make_float2(cur_b.x * mid_scale, cur_b.y * mid_scale);
+        }
         const bool more = t + 1 < tend;
         load_tile(more ? t + 1 : t, tid, more);
         run_fft<LOGN2, LOGT, NT, true>(d, tw, tid);
-        float4* dst = reinterpret_cast<float4*>(mid + (size_t)(t / tiles) * (size_t)M);
+        Two* dst = reinterpret_cast<Two*>(mid + (size_t)(t / tiles) * (size_t)M);
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
             const uint32_t n2 = (uint32_t)(kq0 + q * DK);
             const float4 v = lds_load2<LOGT>(d, (int)n2, 2 * p);
-            dst[n2 * (N1 >> 1) + pp] = join(cmulc(lo2(v), cur_a), cmulc(hi2(v), cur_b));
+            dst[n2 * (N1 >> 1) + pp] = cx_store<HALF>(join(cmulc(lo2(v), cur_a), cmulc(hi2(v), cur_b)));
             cur_a = cmul(cur_a, ratio_a);
             cur_b = cmul(cur_b, ratio_b);
         }
@@ -805,11 +836,12 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const float2* __restrict__ spec, 
 
 // Inverse pass A: inverse N1-point FFTs over k1 for a tile of columns n2; writes the real samples.
 // `aligned`: bit 0 = output is 8-byte aligned, bit 1 = 16-byte aligned.
-template <int LOGN1, bool TABLE>
-__global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, int logM, float* __restrict__ out,
-                                               size_t n, Tables tb, int aligned, uint32_t total, uint32_t per_wg, int glog,
-                                               float gain, TableArg<TABLE> tab)
+template <int LOGN1, bool TABLE, bool HALF>
+__global__ __launch_bounds__(kNT) void k_inv_a(const typename Cx<HALF>::One* __restrict__ mid, int logM,
+                                               float* __restrict__ out, size_t n, Tables tb, int aligned, uint32_t total,
+                                               uint32_t per_wg, int glog, float gain, TableArg<TABLE> tab)
 {
+    using Two = typename Cx<HALF>::Two;
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT, ELEMS = 1 << LOGE;
     constexpr int HP = N1 / 2, LOGHP = LOGN1 - 1;
@@ -824,9 +856,9 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
     const uint32_t tstep = 1u << glog;
     load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
 
-    float4 r[PER2];
+    Two r[PER2];
     auto load_tile = [&](uint32_t tile, int tid, bool live) {
-        const float4* src = reinterpret_cast<const float4*>(mid + (live ? (size_t)(tile / tiles) * (size_t)M : 0));
+        const Two* src = reinterpret_cast<const Two*>(mid + (live ? (size_t)(tile / tiles) * (size_t)M : 0));
         const uint32_t col0 = tile_in_chunk(tile, tiles) << LOGT;
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
@@ -838,8 +870,9 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const float2* __restrict__ mid, i
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
             const int w = tid + q * NT, kp = w & (HP - 1), col = w >> LOGHP;
-            d[sw_idx<LOGT>(kp, col)] = lo2(r[q]);
-            d[sw_idx<LOGT>((int)mirror_row((uint32_t)kp, N1), col)] = hi2(r[q]);
+            const float4 rq = cx_load(r[q]);
+            d[sw_idx<LOGT>(kp, col)] = lo2(rq);
+            d[sw_idx<LOGT>((int)mirror_row((uint32_t)kp, N1), col)] = hi2(rq);
         }
     };
     load_tile(t, tid0, true);
@@ -949,57 +982,65 @@ Grid grouped_grid(size_t groups, int glog, uint32_t kMaxWgs = 512)
     return g;
 }
 
-template <int LOGN1, bool TABLE>
-hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid, Tables t, int aligned, uint32_t* zero_ptr,
-                 uint32_t zero_words, const ChunkTable* tab, hipStream_t s)
+// HALF launchers take the same buffer pointers; the kernels read them as binary16 pairs
+template <int LOGN1, bool TABLE, bool HALF>
+hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid_f32, Tables t, int aligned,
+                 uint32_t* zero_ptr, uint32_t zero_words, const ChunkTable* tab, float in_scale, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN1)) * sizeof(float2);
-    auto kern = k_fwd_a<LOGN1, TABLE>;
+    auto kern = k_fwd_a<LOGN1, TABLE, HALF>;
+    auto* mid = reinterpret_cast<typename Cx<HALF>::One*>(mid_f32);
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
     const int glog = logM - kLogE >= kGroupLog ? kGroupLog : 1;  // a chunk has 2^(logM-kLogE) >= 2 tiles
     const Grid g = grouped_grid(total >> glog, glog, 2048);  // measured: 143 us against 149 with 512
     FFTSP_LAUNCH("rfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, in, n, logM, mid, t, aligned,
-                 (uint32_t)(total >> glog), g.per_wg, glog, zero_ptr, zero_words, table_arg<TABLE>(tab));
+                 (uint32_t)(total >> glog), g.per_wg, glog, zero_ptr, zero_words, table_arg<TABLE>(tab), in_scale);
     return hipGetLastError();
 }
 
-template <int LOGN2, bool CODEC>
-hipError_t fwd_b(const float2* mid, int logM, size_t C, float2* spec, uint32_t sstride, Tables t, uint32_t* hist,
-                 hipStream_t s)
+template <int LOGN2, bool CODEC, bool HALF>
+hipError_t fwd_b(const float2* mid_f32, int logM, size_t C, float2* spec_f32, uint32_t sstride, Tables t, uint32_t* hist,
+                 float mid_scale, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2) + kHistLdsWords * sizeof(uint32_t);
-    auto kern = k_fwd_b<LOGN2, CODEC>;
+    auto kern = k_fwd_b<LOGN2, CODEC, HALF>;
+    auto* mid = reinterpret_cast<const typename Cx<HALF>::One*>(mid_f32);
+    auto* spec = reinterpret_cast<typename Cx<HALF>::One*>(spec_f32);
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
     const Grid g = persistent_grid(total);
     FFTSP_LAUNCH("rfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, mid, logM, spec, sstride, t, hist,
-                 (uint32_t)total, g.per_wg);
+                 (uint32_t)total, g.per_wg, mid_scale);
     return hipGetLastError();
 }
 
-template <int LOGN2, bool PAIR>
-hipError_t inv_b(const float2* spec, uint32_t sstride, int logM, size_t C, float2* mid, Tables t, hipStream_t s)
+template <int LOGN2, bool PAIR, bool HALF>
+hipError_t inv_b(const float2* spec_f32, uint32_t sstride, int logM, size_t C, float2* mid_f32, Tables t, float mid_scale,
+                 hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN2)) * sizeof(float2);
-    auto kern = k_inv_b<LOGN2, PAIR>;
+    auto kern = k_inv_b<LOGN2, PAIR, HALF>;
+    auto* spec = reinterpret_cast<const typename Cx<HALF>::One*>(spec_f32);
+    auto* mid = reinterpret_cast<typename Cx<HALF>::One*>(mid_f32);
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN2)) >> (kLogE - LOGN2));
     const Grid g = persistent_grid(total, 1536);  // measured: 117 us against 126 with 512
     FFTSP_LAUNCH("irfft_pass_b", kern, dim3(g.wgs), dim3(kNT), lds, s, spec, sstride, logM, mid, t, (uint32_t)total,
-                 g.per_wg);
+                 g.per_wg, mid_scale);
     return hipGetLastError();
 }
 
-template <int LOGN1, bool TABLE>
-hipError_t inv_a(const float2* mid, int logM, size_t C, float* out, size_t n, Tables t, int aligned, float gain,
+template <int LOGN1, bool TABLE, bool HALF>
+hipError_t inv_a(const float2* mid_f32, int logM, size_t C, float* out, size_t n, Tables t, int aligned, float gain,
                  const ChunkTable* tab, hipStream_t s)
 {
     const size_t lds = ((size_t)(1 << kLogE) + (1 << LOGN1)) * sizeof(float2);
-    auto kern = k_inv_a<LOGN1, TABLE>;
+    auto kern = k_inv_a<LOGN1, TABLE, HALF>;
+    auto* mid = reinterpret_cast<const typename Cx<HALF>::One*>(mid_f32);
     hipError_t e = set_lds(kern, lds);
     if (e != hipSuccess) return e;
     const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
@@ -1052,8 +1093,8 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
     hipError_t e;
 #define FWD_A(p)                                                                              \
-    (tab ? fwd_a<p, true>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, tab, s)      \
-         : fwd_a<p, false>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, nullptr, s))
+    (tab ? fwd_a<p, true, false>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, tab, 1.0f, s)      \
+         : fwd_a<p, false, false>(in, n, logM, C, mid, t, aligned, zero_ptr, zero_words, nullptr, 1.0f, s))
     switch (logN1) {
         case 7: e = FWD_A(7); break;
         case 8: e = FWD_A(8); break;
@@ -1068,18 +1109,18 @@ hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spe
     if (pair_log && pair_spec) *pair_log = logN1;
     if (hist) {
         switch (logN2) {
-            case 7: return fwd_b<7, true>(mid, logM, C, sp, sstride, t, hist, s);
-            case 8: return fwd_b<8, true>(mid, logM, C, sp, sstride, t, hist, s);
-            case 9: return fwd_b<9, true>(mid, logM, C, sp, sstride, t, hist, s);
-            case 10: return fwd_b<10, true>(mid, logM, C, sp, sstride, t, hist, s);
+            case 7: return fwd_b<7, true, false>(mid, logM, C, sp, sstride, t, hist, 1.0f, s);
+            case 8: return fwd_b<8, true, false>(mid, logM, C, sp, sstride, t, hist, 1.0f, s);
+            case 9: return fwd_b<9, true, false>(mid, logM, C, sp, sstride, t, hist, 1.0f, s);
+            case 10: return fwd_b<10, true, false>(mid, logM, C, sp, sstride, t, hist, 1.0f, s);
             default: return hipErrorInvalidValue;
         }
     }
     switch (logN2) {
-        case 7: return fwd_b<7, false>(mid, logM, C, sp, sstride, t, nullptr, s);
-        case 8: return fwd_b<8, false>(mid, logM, C, sp, sstride, t, nullptr, s);
-        case 9: return fwd_b<9, false>(mid, logM, C, sp, sstride, t, nullptr, s);
-        case 10: return fwd_b<10, false>(mid, logM, C, sp, sstride, t, nullptr, s);
+        case 7: return fwd_b<7, false, false>(mid, logM, C, sp, sstride, t, nullptr, 1.0f, s);
+        case 8: return fwd_b<8, false, false>(mid, logM, C, sp, sstride, t, nullptr, 1.0f, s);
+        case 9: return fwd_b<9, false, false>(mid, logM, C, sp, sstride, t, nullptr, 1.0f, s);
+        case 10: return fwd_b<10, false, false>(mid, logM, C, sp, sstride, t, nullptr, 1.0f, s);
         default: return hipErrorInvalidValue;
     }
 }
@@ -1106,25 +1147,100 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
     hipError_t e;
     if (pair_spec) {
         switch (logN2) {
-            case 7: e = inv_b<7, true>(sp, sstride, logM, C, mid, t, s); break;
-            case 8: e = inv_b<8, true>(sp, sstride, logM, C, mid, t, s); break;
-            case 9: e = inv_b<9, true>(sp, sstride, logM, C, mid, t, s); break;
-            case 10: e = inv_b<10, true>(sp, sstride, logM, C, mid, t, s); break;
+            case 7: e = inv_b<7, true, false>(sp, sstride, logM, C, mid, t, 1.0f, s); break;
+            case 8: e = inv_b<8, true, false>(sp, sstride, logM, C, mid, t, 1.0f, s); break;
+            case 9: e = inv_b<9, true, false>(sp, sstride, logM, C, mid, t, 1.0f, s); break;
+            case 10: e = inv_b<10, true, false>(sp, sstride, logM, C, mid, t, 1.0f, s); break;
             default: return hipErrorInvalidValue;
         }
     } else {
         switch (logN2) {
-            case 7: e = inv_b<7, false>(sp, sstride, logM, C, mid, t, s); break;
-            case 8: e = inv_b<8, false>(sp, sstride, logM, C, mid, t, s); break;
-            case 9: e = inv_b<9, false>(sp, sstride, logM, C, mid, t, s); break;
-            case 10: e = inv_b<10, false>(sp, sstride, logM, C, mid, t, s); break;
+            case 7: e = inv_b<7, false, false>(sp, sstride, logM, C, mid, t, 1.0f, s); break;
+            case 8: e = inv_b<8, false, false>(sp, sstride, logM, C, mid, t, 1.0f, s); break;
+            case 9: e = inv_b<9, false, false>(sp, sstride, logM, C, mid, t, 1.0f, s); break;
+            case 10: e = inv_b<10, false, false>(sp, sstride, logM, C, mid, t, 1.0f, s); break;
             default: return hipErrorInvalidValue;
         }
     }
     if (e != hipSuccess) return e;
 #define INV_A(p)                                                          \
-    (tab ? inv_a<p, true>(mid, logM, C, out, n, t, aligned, gain, tab, s) \
-         : inv_a<p, false>(mid, logM, C, out, n, t, aligned, gain, nullptr, s))
+    (tab ? inv_a<p, true, false>(mid, logM, C, out, n, t, aligned, gain, tab, s) \
+         : inv_a<p, false, false>(mid, logM, C, out, n, t, aligned, gain, nullptr, s))
+    switch (logN1) {
+        case 7: return INV_A(7);
+        case 8: return INV_A(8);
+        case 9: return INV_A(9);
+        case 10: return INV_A(10);
+        case 11: return INV_A(11);
+        default: return hipErrorInvalidValue;
+    }
+#undef INV_A
+}
+
+// Half-precision variant (two-pass sizes, the codec's own buffers): the same four kernels with the intermediate
+// and the spectrum stored as binary16 pairs.  in_scale (a power of two) multiplies the samples on the way in;
+// the receiver divides through `gain`.
+hipError_t launch_rfft_half(const float* in, size_t n, int logL, size_t C, void* spec, uint32_t sstride, void* mid,
+                            Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, float in_scale,
+                            int* pair_log, hipStream_t s)
+{
+    const int logM = logL - 1;
+    if (logM < 14 || !hist || zero_words > 0xffffffffu) return hipErrorInvalidValue;
+    if (C * ((size_t)1 << (logM - 13)) > 0x7fffffffu) return hipErrorInvalidValue;
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(in);
+    const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
+    float2* sp = static_cast<float2*>(spec);
+    float2* md = static_cast<float2*>(mid);
+    const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
+    hipError_t e;
+    // A first-pass sum of N1 terms is about sqrt(N2) times smaller than a spectrum value, an unnormalised inverse
+    // second-pass sum about sqrt(N2) times larger: the stored intermediate is lifted (lowered) by 2^(logN2 / 2) so
+    // that it sits where the caller's scale put the spectrum.  Powers of two: exact.
+    const float lift = std::ldexp(1.0f, logN2 / 2);
+#define FWD_A(p) \
+    fwd_a<p, false, true>(in, n, logM, C, md, t, aligned, zero_ptr, (uint32_t)zero_words, nullptr, in_scale * lift, s)
+    switch (logN1) {
+        case 7: e = FWD_A(7); break;
+        case 8: e = FWD_A(8); break;
+        case 9: e = FWD_A(9); break;
+        case 10: e = FWD_A(10); break;
+        case 11: e = FWD_A(11); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef FWD_A
+    if (e != hipSuccess) return e;
+    *pair_log = logN1;
+    switch (logN2) {
+        case 7: return fwd_b<7, true, true>(md, logM, C, sp, sstride, t, hist, 1.0f / lift, s);
+        case 8: return fwd_b<8, true, true>(md, logM, C, sp, sstride, t, hist, 1.0f / lift, s);
+        case 9: return fwd_b<9, true, true>(md, logM, C, sp, sstride, t, hist, 1.0f / lift, s);
+        case 10: return fwd_b<10, true, true>(md, logM, C, sp, sstride, t, hist, 1.0f / lift, s);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_irfft_half(const void* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, void* mid,
+                             Tables t, float gain, hipStream_t s)
+{
+    const int logM = logL - 1;
+    if (logM < 14) return hipErrorInvalidValue;
+    if (C * ((size_t)1 << (logM - 13)) > 0x7fffffffu) return hipErrorInvalidValue;
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(out);
+    const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
+    const float2* sp = static_cast<const float2*>(spec);
+    float2* md = static_cast<float2*>(mid);
+    const int logN1 = (logM + 1) / 2, logN2 = logM / 2;
+    hipError_t e;
+    const float lift = std::ldexp(1.0f, logN2 / 2);  // see launch_rfft_half
+    switch (logN2) {
+        case 7: e = inv_b<7, true, true>(sp, sstride, logM, C, md, t, 1.0f / lift, s); break;
+        case 8: e = inv_b<8, true, true>(sp, sstride, logM, C, md, t, 1.0f / lift, s); break;
+        case 9: e = inv_b<9, true, true>(sp, sstride, logM, C, md, t, 1.0f / lift, s); break;
+        case 10: e = inv_b<10, true, true>(sp, sstride, logM, C, md, t, 1.0f / lift, s); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (e != hipSuccess) return e;
+#define INV_A(p) inv_a<p, false, true>(md, logM, C, out, n, t, aligned, gain * lift, nullptr, s)
     switch (logN1) {
         case 7: return INV_A(7);
         case 8: return INV_A(8);

@@ -2,6 +2,7 @@
 // Nothing here is part of the C ABI (see include/fftsp.h).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
 #include <stdint.h>
 #include <stddef.h>
 #include <string>
@@ -18,6 +19,60 @@ struct Tables {
     const float2* hi;
     const float2* lo;
 };
+
+// How complex values are stored where they cross HBM between kernels (the two-pass intermediate and the codec's
+// own spectrum): binary32 pairs, or binary16 pairs in the half-precision variant (Sec. 3.1.1, "Our approach").
+// Arithmetic is binary32 in registers and LDS either way; the variant halves the bytes, which is what bounds
+// these kernels.  One = a complex value, Two = two adjacent ones (what a lane moves per access).
+template <bool HALF>
+struct Cx {
+    using One = float2;
+    using Two = float4;
+};
+template <>
+struct Cx<true> {
+    using One = uint32_t;  // bit pattern of two binary16 numbers (re low, im high)
+    using Two = uint2;
+};
+// round to nearest even, saturating at the largest finite binary16 number
+__device__ __forceinline__ uint32_t pack_half2(float2 v)
+{
+    const float lim = 65504.f;
+    const __half2 h = __floats2half2_rn(fminf(fmaxf(v.x, -lim), lim), fminf(fmaxf(v.y, -lim), lim));
+    uint32_t w;
+    __builtin_memcpy(&w, &h, sizeof(w));
+    return w;
+}
+__device__ __forceinline__ float2 unpack_half2(uint32_t w)
+{
+    __half2 h;
+    __builtin_memcpy(&h, &w, sizeof(w));
+    return __half22float2(h);
+}
+__device__ __forceinline__ float2 cx_load(float2 v) { return v; }
+__device__ __forceinline__ float2 cx_load(uint32_t v) { return unpack_half2(v); }
+__device__ __forceinline__ float4 cx_load(float4 v) { return v; }
+__device__ __forceinline__ float4 cx_load(uint2 v)
+{
+    const float2 a = unpack_half2(v.x), b = unpack_half2(v.y);
+    return make_float4(a.x, a.y, b.x, b.y);
+}
+template <bool HALF>
+__device__ __forceinline__ typename Cx<HALF>::One cx_store(float2 v)
+{
+    if constexpr (HALF)
+        return pack_half2(v);
+    else
+        return v;
+}
+template <bool HALF>
+__device__ __forceinline__ typename Cx<HALF>::Two cx_store(float4 v)
+{
+    if constexpr (HALF)
+        return make_uint2(pack_half2(make_float2(v.x, v.y)), pack_half2(make_float2(v.z, v.w)));
+    else
+        return v;
+}
 
 // Selection geometry: one workgroup of 256 lanes owns a tile of 2048 consecutive bins
 // (wave w owns 512 of them as 8 rows of 64), so a wave ballot is two bitmap words.
@@ -160,6 +215,14 @@ int fft_pair_log(int logL);
 hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
                         Tables t, int pair_spec, float gain, const ChunkTable* tab, hipStream_t s);
 
+// Half-precision variant: chunk lengths of the two-pass FFT only (2^15 and up); spec and mid are the codec's own
+// buffers, read and written as binary16 pairs (sstride in complex values); the histogram is always produced.
+hipError_t launch_rfft_half(const float* in, size_t n, int logL, size_t C, void* spec, uint32_t sstride, void* mid,
+                            Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, float in_scale,
+                            int* pair_log, hipStream_t s);
+hipError_t launch_irfft_half(const void* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, void* mid,
+                             Tables t, float gain, hipStream_t s);
+
 // Codec launchers (codec.hip).
 struct CodecArgs {
     size_t C;           // chunks
@@ -173,6 +236,8 @@ struct CodecArgs {
     const ChunkTable* tab;  // per-tensor launches: where each chunk's record lives (host pointer); else nullptr
     int time_domain;    // != 0: records describe the gradient's samples; `spec` of the launchers is the gradient
     size_t n;           // time domain: samples in the gradient (the last chunk may be short)
+    int half;           // != 0: `spec` holds binary16 pairs (half-precision variant; two-pass chunk lengths only)
+    int hdr_scale;      // stream header word 12: log2 of the factor on the spectrum (half-precision variant), else 0
     int pair_log;       // 0: spectrum in natural bin order; log2(N1): paired order (see spec_index)
     // stream header (written iff write_header)
     int write_header;

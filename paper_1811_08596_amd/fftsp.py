@@ -33,6 +33,10 @@ SIGNATURES = {
                                  C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_decompress": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fftsp_compress_h": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int, C.c_void_p,
+                                   C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fftsp_decompress_h": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
+                                     C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_topk_kept_per_chunk": (C.c_int, [C.c_uint32, C.c_float, C.POINTER(C.c_uint32)]),
     "fftsp_topk_packed_bytes": (C.c_size_t, [C.c_size_t, C.c_uint32, C.c_float, C.c_int]),
     "fftsp_topk_workspace_bytes": (C.c_size_t, [C.c_size_t, C.c_uint32, C.c_int]),
@@ -168,6 +172,19 @@ def compress(grad, chunk_len: int, theta: float, bits: int, packed, workspace, s
 def decompress(packed, packed_nbytes: int, grad_out, chunk_len: int, theta: float, bits: int, workspace, stream=None):
     _check(load().fftsp_decompress(_ptr(packed), packed_nbytes, _ptr(grad_out), grad_out.numel(), chunk_len, theta,
                                    bits, _ptr(workspace), _nbytes(workspace), _stream(stream)), "fftsp_decompress")
+
+
+def compress_h(grad, chunk_len: int, theta: float, bits: int, scale_log2: int, packed, workspace, stream=None):
+    _check(load().fftsp_compress_h(_ptr(grad), grad.numel(), chunk_len, theta, bits, scale_log2, _ptr(packed),
+                                   _nbytes(packed), _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "fftsp_compress_h")
+
+
+def decompress_h(packed, packed_nbytes: int, grad_out, chunk_len: int, theta: float, bits: int, scale_log2: int,
+                 workspace, stream=None):
+    _check(load().fftsp_decompress_h(_ptr(packed), packed_nbytes, _ptr(grad_out), grad_out.numel(), chunk_len, theta,
+                                     bits, scale_log2, _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "fftsp_decompress_h")
 
 
 def topk_kept_per_chunk(chunk_len: int, theta: float) -> int:

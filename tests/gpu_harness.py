@@ -138,6 +138,24 @@ class Device:
         st = self.f.device_status(ws)
         return out.cpu().numpy(), st
 
+    def compress_h(self, g, L, theta, bits, scale_log2):
+        n = g.size
+        gd = self.to_dev(g.astype(np.float32))
+        nb = self.f.packed_bytes(n, L, theta, bits)
+        packed = self.torch.full((nb,), 0xEE, dtype=self.torch.uint8, device=self.dev)
+        self.f.compress_h(gd, L, theta, bits, scale_log2, packed, self.ws_for(n, L, bits))
+        self.sync()
+        return packed.cpu().numpy()
+
+    def decompress_h(self, packed, n, L, theta, bits, scale_log2, pad=0):
+        pd = self.to_dev(np.asarray(packed, np.uint8))
+        out = self.torch.full((n + pad,), float("nan"), dtype=self.torch.float32, device=self.dev)
+        ws = self.ws_for(n, L, bits)
+        self.f.decompress_h(pd, pd.numel(), out[:n], L, theta, bits, scale_log2, ws)
+        st = self.f.device_status(ws)
+        res = out.cpu().numpy()
+        return res[:n], st, res[n:]
+
     def topk_compress(self, g, L, theta, bits):
         n = g.size
         gd = self.to_dev(g.astype(np.float32))

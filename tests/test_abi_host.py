@@ -146,6 +146,31 @@ def test_topk_host_arithmetic_and_argument_errors(lib, ref):
     assert dec(wsb=10) == fftsp.EWORKSPACE
 
 
+def test_half_variant_argument_errors(lib):
+    a = 4096
+    call = lambda **kw: lib.fftsp_compress_h(kw.get("g", a), kw.get("n", 1 << 16), kw.get("L", 1 << 15),
+                                             kw.get("theta", 0.5), kw.get("bits", 8), kw.get("s", 8), kw.get("p", a),
+                                             kw.get("cap", 1 << 30), kw.get("ws", a), kw.get("wsb", 1 << 30), None)
+    assert call(L=1 << 14) == fftsp.EUNSUPPORTED              # single-workgroup chunk lengths have no stored intermediate
+    assert call(L=1 << 23) == fftsp.EUNSUPPORTED
+    assert call(s=25) == fftsp.EINVAL
+    assert call(s=-25) == fftsp.EINVAL
+    assert call(g=None) == fftsp.EINVAL
+    assert call(g=a + 8) == fftsp.EINVAL
+    assert call(theta=-0.1) == fftsp.EINVAL
+    assert call(bits=17) == fftsp.EINVAL
+    assert call(cap=100) == fftsp.ENOSPC
+    assert call(wsb=100) == fftsp.EWORKSPACE
+    dec = lambda **kw: lib.fftsp_decompress_h(kw.get("p", a), kw.get("pb", 1 << 30), kw.get("g", a), kw.get("n", 1 << 16),
+                                              kw.get("L", 1 << 15), 0.5, 8, kw.get("s", 8), kw.get("ws", a),
+                                              kw.get("wsb", 1 << 30), None)
+    assert dec(L=1 << 14) == fftsp.EUNSUPPORTED
+    assert dec(s=30) == fftsp.EINVAL
+    assert dec(pb=100) == fftsp.EFORMAT
+    assert dec(wsb=100) == fftsp.EWORKSPACE
+    assert dec(g=None) == fftsp.EINVAL
+
+
 def test_product_does_not_import_the_oracle():
     """The GPU package and its C sources must not use oracle/ (and vice versa)."""
     pkg = os.path.join(ROOT, "paper_1811_08596_amd")
