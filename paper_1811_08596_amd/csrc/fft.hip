@@ -416,6 +416,24 @@ __device__ __forceinline__ bool grouped_run(uint32_t groups, uint32_t per_wg, in
 // rows held by pair kp of a run of N1 paired positions: (kp, N1-kp), and (0, N1/2) for kp = 0
 __device__ __forceinline__ uint32_t mirror_row(uint32_t kp, uint32_t N1) { return kp ? N1 - kp : N1 / 2; }
 
+// The first radix-8 stage of an R-point Stockham chain, done in registers: a lane that holds rows j + t*R/8
+// (t = 0..7) of two adjacent columns has all inputs of two butterflies, so the stage needs no LDS round trip and
+// no barrier of its own.  The outputs go to rows 8j + t, where the next stage (NS = 8) reads them.
+template <int LOGT, bool INV>
+__device__ __forceinline__ void first_stage_store(float2* d, int j, int col_even, const float4 (&x)[8])
+{
+    float2 a[8], b[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        a[t] = lo2(x[t]);
+        b[t] = hi2(x[t]);
+    }
+    bf8<INV>(a);
+    bf8<INV>(b);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) lds_store2<LOGT>(d, 8 * j + t, col_even, join(a[t], b[t]));
+}
+
 // Software pipeline of the persistent two-pass kernels.  Vector-memory results return in issue order and are
 // counted by a single counter, so the order of issue decides what a wait really waits for.  Per tile t:
 //     [table lookups for tile t's store loop, lookups for tile t+1's split, loads of tile t+1]   one batch
@@ -471,13 +489,9 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
             }
         }
     };
-    auto fill = [&](int tid) {
-#pragma unroll
-        for (int q = 0; q < PER2; ++q) {
-            const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
-            lds_store2<LOGT>(d, n1, 2 * bp, r[q]);
-        }
-    };
+    // r[q] holds rows (tid >> (LOGT-1)) + q * N1/8 of one column pair: the first stage runs on the way into LDS
+    static_assert(PER2 == 8 && (NT >> (LOGT - 1)) == N1 / 8, "a lane's loads are the inputs of two radix-8 butterflies");
+    auto fill = [&](int tid) { first_stage_store<LOGT, false>(d, tid >> (LOGT - 1), 2 * (tid & (TA / 2 - 1)), r); };
     load_tile(t, tid0, true);
     fill(tid0);
     __syncthreads();
@@ -502,7 +516,7 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
         }
         const bool more = t + tstep < tend;
         load_tile(more ? t + tstep : t, tid, more);
-        run_fft<LOGN1, LOGT, NT, false>(d, tw, tid);
+        run_fft<LOGN1, LOGT, NT, false, 3>(d, tw, tid);
         typename Cx<HALF>::Two* out = reinterpret_cast<typename Cx<HALF>::Two*>(mid + (size_t)(t / tiles) * (size_t)M);
 #pragma unroll
         for (int kk = 0; kk < KN; ++kk) {
@@ -615,15 +629,18 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const typename Cx<HALF>::One* __r
 #pragma unroll
         for (int q = 0; q < PER2; ++q) r[q] = src[live ? (uint32_t)(kq0 + q * DK) * (N1 >> 1) + pp : 0u];
     };
+    // r[q] holds rows kq0 + q * N2/8 of one slot pair: the first radix-8 stage runs on the way into LDS
+    static_assert(PER2 == 8 && DK == N2 / 8, "a lane's loads are the inputs of two radix-8 butterflies");
     auto fill = [&](int tid) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        float4 v[PER2];
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
-            float4 v = cx_load(r[q]);
+            v[q] = cx_load(r[q]);
             if constexpr (HALF)  // undo the factor that kept the intermediate inside binary16's range
-                v = make_float4(v.x * mid_scale, v.y * mid_scale, v.z * mid_scale, v.w * mid_scale);
-            lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, v);
+                v[q] = make_float4(v[q].x * mid_scale, v[q].y * mid_scale, v[q].z * mid_scale, v[q].w * mid_scale);
         }
+        first_stage_store<LOGT, false>(d, kq0, 2 * p, v);
     };
     // one key into the 16-bit LDS histogram (bucket b: word b/2, half b%2); on = false adds nothing
     auto count = [&](float2 x, bool on) {
@@ -645,7 +662,7 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const typename Cx<HALF>::One* __r
         const float2 base_b = twiddle(tb, (kb + ((uint32_t)kq0 << logN1)) << (21 - logM));
         const bool more = t + 1 < tend;
         load_tile(more ? t + 1 : t, tid, more);
-        run_fft<LOGN2, LOGT, NT, false>(d, tw, tid);
+        run_fft<LOGN2, LOGT, NT, false, 3>(d, tw, tid);
         const size_t c = t / tiles;
         typename Cx<HALF>::One* out = spec + c * (size_t)sstride;
 #pragma unroll
@@ -801,8 +818,9 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const typename Cx<HALF>::One* __r
             z[q] = join(split_inv(a0, b0, cmul(base_a, wq)), split_inv(hi2(rq), pb[q], cmul(base_b, wq)));
         }
         __syncthreads();
-#pragma unroll
-        for (int q = 0; q < PER2; ++q) lds_store2<LOGT>(d, kq0 + q * DK, 2 * p, z[q]);
+        // z[q] are rows kq0 + q * N2/8 of this lane's slot pair: the first inverse radix-8 stage runs here
+        static_assert(PER2 == 8 && DK == N2 / 8, "a lane's values are the inputs of two radix-8 butterflies");
+        first_stage_store<LOGT, true>(d, kq0, 2 * p, z);
         __syncthreads();
         // store-loop twiddles of this tile, then split twiddles and data of the next one
         const int sh = 22 - logM;
@@ -816,7 +834,7 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const typename Cx<HALF>::One* __r
         }
         const bool more = t + 1 < tend;
         load_tile(more ? t + 1 : t, tid, more);
-        run_fft<LOGN2, LOGT, NT, true>(d, tw, tid);
+        run_fft<LOGN2, LOGT, NT, true, 3>(d, tw, tid);
         Two* dst = reinterpret_cast<Two*>(mid + (size_t)(t / tiles) * (size_t)M);
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
