@@ -1454,15 +1454,13 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     const uint32_t codes_per_bin = a.time_domain ? 1u : 2u;
     // up to 12 Ki candidates (96 KiB) are staged in LDS by the per-chunk workgroup
     constexpr uint32_t kStageCap = 12 * 1024;
-    static bool lds_set = false;
-    if (!lds_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_resolve<false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kStageCap * sizeof(uint2)));
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(k_resolve<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kStageCap * sizeof(uint2)));
+    {
+        // set on every call (a host-side table write): the attribute belongs to the current device, and a flag
+        // remembered across calls would be neither per device nor safe between host threads
+        const void* fn = a.tab ? reinterpret_cast<const void*>(k_resolve<true>) : reinterpret_cast<const void*>(k_resolve<false>);
+        const hipError_t e =
+            hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kStageCap * sizeof(uint2)));
         if (e != hipSuccess) return e;
-        lds_set = true;
     }
     if (a.tab && a.C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
 #define FFTSP_RESOLVE(TABLE)                                                                                          \

@@ -1,0 +1,59 @@
+"""The library's calls enqueue kernels only (no allocation, no memset, no host synchronisation after the first call
+on a device), so a caller can record them into a HIP graph.  A graph is replayed several times with eager work and
+synchronisations in between, and every replay is checked against the eager result."""
+import numpy as np
+import pytest
+
+from paper_1811_08596_amd import workloads
+from tests.gpu_harness import Device
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return Device()
+
+
+def test_per_tensor_round_trip_replays_from_a_graph(dev):
+    torch, f = dev.torch, dev.f
+    w = workloads.config2()                                # ResNet-20-shaped: 22 tensors
+    offs = [int(v) for v in w.seg_offsets]
+    theta, bits = w.theta, w.bits
+    n = offs[-1]
+    nb = f.packed_bytes_segments(offs, theta, bits)
+    ws = dev.workspace(f.workspace_bytes_segments(offs, bits))
+    g = dev.to_dev(w.grad)
+    packed = torch.zeros(nb, dtype=torch.uint8, device=dev.dev)
+    out = torch.zeros(n, dtype=torch.float32, device=dev.dev)
+
+    def step():
+        f.compress_segments(g, offs, theta, bits, packed, ws)
+        f.decompress_segments(packed, nb, out, offs, theta, bits, ws)
+
+    step()                                                 # first call on the device builds the twiddle tables
+    torch.cuda.synchronize()
+    want_packed, want_out = packed.clone(), out.clone()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    for replay in range(4):
+        # new input each time, eager result first, then the graph on the same buffers
+        g.copy_(dev.to_dev(w.grad * np.float32(rng.uniform(0.5, 2.0))))
+        step()
+        torch.cuda.synchronize()
+        want_packed.copy_(packed)
+        want_out.copy_(out)
+        packed.fill_(0xEE)
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert f.device_status(ws) == 0
+        assert torch.equal(packed, want_packed), replay
+        assert torch.equal(out.view(torch.int32), want_out.view(torch.int32)), replay
