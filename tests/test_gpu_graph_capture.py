@@ -57,3 +57,50 @@ def test_per_tensor_round_trip_replays_from_a_graph(dev):
         assert f.device_status(ws) == 0
         assert torch.equal(packed, want_packed), replay
         assert torch.equal(out.view(torch.int32), want_out.view(torch.int32)), replay
+
+
+def test_uniform_round_trip_replays_from_a_graph(dev, ref):
+    """the uniform-chunk path at a two-pass chunk length (fused histogram, persistent kernels) from a graph"""
+    torch, f = dev.torch, dev.f
+    L, theta, bits = 1 << 15, 0.4, 8
+    n = 14 * L - 5
+    nb = f.packed_bytes(n, L, theta, bits)
+    ws = dev.ws_for(n, L, bits)
+    g0 = workloads.small_mixed(n, seed=8)
+    g = dev.to_dev(g0)
+    packed = torch.zeros(nb, dtype=torch.uint8, device=dev.dev)
+    out = torch.zeros(n, dtype=torch.float32, device=dev.dev)
+
+    def step():
+        f.compress(g, L, theta, bits, packed, ws)
+        f.decompress(packed, nb, out, L, theta, bits, ws)
+
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for replay in range(4):
+        g.copy_(dev.to_dev(g0 * np.float32(rng.uniform(0.5, 2.0))))
+        step()
+        torch.cuda.synchronize()
+        want_packed, want_out = packed.clone(), out.clone()
+        packed.fill_(0xEE)
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert f.device_status(ws) == 0
+        assert torch.equal(packed, want_packed), replay
+        assert torch.equal(out.view(torch.int32), want_out.view(torch.int32)), replay
+    # and the eager result is the one the oracle explains: receiver on the oracle's bytes within the bound
+    por = ref.compress(g.cpu().numpy(), L, theta, bits, nthreads=8)
+    back, st = dev.decompress(por, n, L, theta, bits, want_status=True)
+    assert st == 0
+    want = ref.decompress(por, n, L, theta, bits, nthreads=8)
+    assert np.linalg.norm(back - want) <= 1e-5 * np.linalg.norm(want)
