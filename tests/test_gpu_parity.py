@@ -104,6 +104,31 @@ def test_every_code_width(dev, ref, bits):
     full_parity(dev, ref, g, 8192, 0.41, bits)
 
 
+def test_seeded_sweep_of_shapes(dev, ref):
+    """forty cases drawn from a fixed seed: chunk length, tail length, kept fraction, code width and the share of
+    exact zeros all vary together, which the hand-picked cases above do not"""
+    rng = np.random.default_rng(20181108)
+    widths = [3, 4, 5, 6, 7, 8, 9, 10, 12, 13, 16, 32]
+    for case in range(40):
+        logL = int(rng.integers(5, 19))
+        L = 1 << logL
+        chunks = int(rng.integers(1, 5)) if logL >= 14 else int(rng.integers(1, 40))
+        tail = int(rng.integers(1, L + 1))
+        n = (chunks - 1) * L + tail
+        theta = float(rng.choice([0.0, 1.0, rng.uniform(0.0, 1.0), rng.uniform(0.0, 0.1), rng.uniform(0.9, 1.0)]))
+        bits = int(rng.choice(widths))
+        zeros = float(rng.choice([0.0, 0.0, 0.5, 0.95]))
+        print(f"sweep {case}: L=2^{logL} n={n} theta={theta:.4f} bits={bits} zeros={zeros}", flush=True)
+        g = workloads.small_mixed(n, seed=1000 + case, zeros=zeros)
+        full_parity(dev, ref, g, L, theta, bits, end_to_end=zeros == 0.0)
+        # time-domain Top-k on the same case (bit for bit), where its chunk length allows
+        packed_or = ref.topk_compress(g, L, theta, bits, nthreads=8)
+        assert np.array_equal(dev.topk_compress(g, L, theta, bits), packed_or)
+        out, st, _ = dev.topk_decompress(packed_or, n, L, theta, bits)
+        assert st == 0
+        assert np.array_equal(out.view(np.uint32), ref.topk_decompress(packed_or, n, L, theta, bits, nthreads=8).view(np.uint32))
+
+
 def test_degenerate_inputs(dev, ref):
     """ties everywhere (zeros, impulse), a single non-zero bin, repeated values, subnormal magnitudes"""
     for L in (256, 1 << 15):
