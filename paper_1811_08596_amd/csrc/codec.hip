@@ -489,7 +489,9 @@ struct HeaderInfo {
 // One workgroup per chunk: finish the radix select on the candidates, break ties by bin order,
 // scan the tiles, find the survivors' largest component, write the record header and zero the
 // code words that two tiles will share.
-template <bool TABLE>
+// KEYS: a candidate's second word equals its key (time domain: both are the pattern of |x|), so only keys are
+// staged and the stage holds twice as many candidates.
+template <bool TABLE, bool KEYS>
 __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bits, int m, uint32_t W, size_t S,
                                                 uint32_t word3, uint32_t stage_cap, uint32_t static_vmax,
                                                 uint32_t codes_per_bin,
@@ -515,6 +517,13 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     // stage[toff[t] ..).  Otherwise every pass reads them from global memory.
     extern __shared__ float2 smem[];
     uint2* stage = reinterpret_cast<uint2*>(smem);
+    uint32_t* stage_keys = reinterpret_cast<uint32_t*>(smem);
+    auto staged_key = [&](uint32_t i) __attribute__((always_inline)) {
+        if constexpr (KEYS)
+            return stage_keys[i];
+        else
+            return stage[i].x;
+    };
     if (tid == 0) s_carry[0] = 0;
     __syncthreads();
     for (uint32_t base = 0; base < Tn; base += RT) {
@@ -560,7 +569,12 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
 #pragma unroll
             for (int u = 0; u < kStageBatch; ++u) {
                 const uint32_t i = base + (uint32_t)u * RT + tid;
-                if (i < total) stage[i] = v[u];
+                if (i < total) {
+                    if constexpr (KEYS)
+                        stage_keys[i] = v[u].x;
+                    else
+                        stage[i] = v[u];
+                }
             }
         }
     }
@@ -578,7 +592,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             if (staged) {
                 const uint32_t total = s_carry[0];
                 for (uint32_t i = tid; i < total; i += RT) {
-                    const uint32_t key = stage[i].x;
+                    const uint32_t key = staged_key(i);
                     if ((key & pmask) == prefix) atomicAdd(&h[(key >> shift) & dmask], 1u);
                 }
             } else {
@@ -626,7 +640,7 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             const uint32_t nc = tnc[t], o = toff[t];
             uint32_t gt = 0, eq = 0;
             for (uint32_t i = 0; i < nc; ++i) {
-                const uint32_t key = stage[o + i].x;
+                const uint32_t key = staged_key(o + i);
                 gt += key > tau;
                 eq += key == tau;
             }
@@ -690,7 +704,11 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             if (tdef[t]) vm = tvd[t] > vm ? tvd[t] : vm;
             uint32_t eqrun = 0;  // candidates equal to tau seen so far, in bin order
             for (uint32_t i = 0; i < nc; ++i) {
-                const uint2 e = stage[o + i];
+                uint2 e;
+                if constexpr (KEYS)
+                    e = make_uint2(stage_keys[o + i], stage_keys[o + i]);
+                else
+                    e = stage[o + i];
                 const bool iseq = e.x == tau;
                 const bool kept = e.x > tau || (iseq && eqrun < take);
                 eqrun += iseq;
@@ -1452,29 +1470,35 @@ hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_
     HeaderInfo h{a.write_header, a.hdr_n, a.hdr_L, a.hdr_C, (uint32_t)a.bits, (uint32_t)a.m, a.hdr_k, a.hdr_S,
                  a.hdr_theta, a.time_domain ? 1u : 0u, (uint32_t)a.hdr_scale};
     const uint32_t codes_per_bin = a.time_domain ? 1u : 2u;
-    // up to 12 Ki candidates (96 KiB) are staged in LDS by the per-chunk workgroup
+    // up to 12 Ki candidates (96 KiB) are staged in LDS by the per-chunk workgroup, 24 Ki where keys alone suffice
     constexpr uint32_t kStageCap = 12 * 1024;
+    const uint32_t stage_cap = a.time_domain ? 2 * kStageCap : kStageCap;
     {
         // set on every call (a host-side table write): the attribute belongs to the current device, and a flag
         // remembered across calls would be neither per device nor safe between host threads
-        const void* fn = a.tab ? reinterpret_cast<const void*>(k_resolve<true>) : reinterpret_cast<const void*>(k_resolve<false>);
+        const void* fn = a.tab           ? reinterpret_cast<const void*>(k_resolve<true, false>)
+                         : a.time_domain ? reinterpret_cast<const void*>(k_resolve<false, true>)
+                                         : reinterpret_cast<const void*>(k_resolve<false, false>);
         const hipError_t e =
             hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kStageCap * sizeof(uint2)));
         if (e != hipSuccess) return e;
     }
     if (a.tab && a.C > (size_t)kMaxTableChunks) return hipErrorInvalidValue;
-#define FFTSP_RESOLVE(TABLE)                                                                                          \
-    FFTSP_LAUNCH("resolve", k_resolve<TABLE>, dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, a.k,   \
-                 a.bits, a.m, W, a.S, a.word3, kStageCap, a.static_vmax, codes_per_bin, sel, tinfo, tscan, cand,      \
+#define FFTSP_RESOLVE(TABLE, KEYS)                                                                                    \
+    FFTSP_LAUNCH("resolve", (k_resolve<TABLE, KEYS>), dim3((unsigned)a.C), dim3(RT), kStageCap * sizeof(uint2), s, Tn, \
+                 a.k, a.bits, a.m, W, a.S, a.word3, stage_cap, a.static_vmax, codes_per_bin, sel, tinfo, tscan, cand,  \
                  records, stream_base, h, table_arg<TABLE>(a.tab))
 #define FFTSP_EMIT(TABLE, REAL, HALF, src)                                                                            \
     FFTSP_LAUNCH("emit", (k_emit<TABLE, REAL, HALF>), dim3((unsigned)(a.C * Tn)), dim3(NT), 0, s, src, a.sstride,     \
                  a.pair_log, B, Tn, W, a.bits, a.m, a.S, sel, tscan, records, table_arg<TABLE>(a.tab), a.n)
     if (a.tab) {
-        FFTSP_RESOLVE(true);
+        FFTSP_RESOLVE(true, false);
         FFTSP_EMIT(true, false, false, X);
     } else {
-        FFTSP_RESOLVE(false);
+        if (a.time_domain)
+            FFTSP_RESOLVE(false, true);
+        else
+            FFTSP_RESOLVE(false, false);
         if (a.time_domain)
             FFTSP_EMIT(false, true, false, spec);
         else if (a.half)
