@@ -171,6 +171,15 @@ def test_half_variant_argument_errors(lib):
     assert dec(g=None) == fftsp.EINVAL
 
 
+def test_bench_refuses_more_than_one_gpu():
+    """one GPU per box: the bench says so instead of starting a multi-rank run"""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "single-GPU" in r.stderr and not r.stdout.strip()
+
+
 def test_product_does_not_import_the_oracle():
     """The GPU package and its C sources must not use oracle/ (and vice versa)."""
     pkg = os.path.join(ROOT, "paper_1811_08596_amd")
