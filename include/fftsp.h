@@ -203,7 +203,10 @@ int fftsp_topk_decompress(const void* d_packed, size_t packed_bytes, float* d_gr
  *      and is consumed before the call returns.  Sizes above 2^22 are FFTSP_EUNSUPPORTED.
  *      Records follow tensor order in the stream.  Tensors that pad to the same L_i run together as the chunks
  *      of shared launches (up to 64 at a time), so the cost grows with the number of distinct lengths rather
- *      than with the number of tensors; the workspace is sized for the largest such group. ---- */
+ *      than with the number of tensors.  These launch sets run on up to four streams at once (the caller's and
+ *      streams of the library's own that fork from and join back into it, so the call is still one unit of work
+ *      on the caller's stream and can be captured into a graph); the workspace holds one region per stream, each
+ *      sized for the largest group. ---- */
 size_t fftsp_packed_bytes_segments(const size_t* seg_offsets, int nseg, float theta, int bits);
 size_t fftsp_workspace_bytes_segments(const size_t* seg_offsets, int nseg, int bits);
 int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int nseg, float theta, int bits,

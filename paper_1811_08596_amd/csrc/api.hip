@@ -698,15 +698,126 @@ static std::vector<SegBatch> plan_segments(const size_t* off, int nseg, float th
     return out;
 }
 
-size_t fftsp_workspace_bytes_segments(const size_t* seg_offsets, int nseg, int bits)
+// The launch sets of a per-tensor call are independent chains of short kernels (most tensors are small), so they
+// run on up to kSegLanes streams at once: the caller's and streams of the library's own that fork from and join
+// back into the caller's through events.  The call stays one unit of work on the caller's stream and can be
+// captured into a graph.  Every lane works in a workspace region of its own, sized for the largest launch set.
+constexpr int kSegLanes = 4;
+struct SegLanes {
+    bool ready = false;
+    hipStream_t s[kSegLanes - 1];
+    hipEvent_t fork, join[kSegLanes - 1];
+};
+static SegLanes g_seg_lanes[64];
+static std::mutex g_seg_mutex;  // held while a call enqueues: the events are shared by all calls on a device
+
+static size_t segment_region_bytes(const std::vector<SegBatch>& batches)
 {
-    if (segments_ok(seg_offsets, nseg) != FFTSP_OK || mantissa(bits) < 0) return 0;
     size_t best = 0;
-    for (const SegBatch& b : plan_segments(seg_offsets, nseg, 0.5f, bits, false)) {
+    for (const SegBatch& b : batches) {
         const size_t t = make_workspace(b.count, b.L).total;
         best = t > best ? t : best;
     }
-    return best;
+    return align256(best);
+}
+
+static int segment_lanes(size_t nbatches)
+{
+    return (int)(nbatches < (size_t)kSegLanes ? nbatches : (size_t)kSegLanes);
+}
+
+size_t fftsp_workspace_bytes_segments(const size_t* seg_offsets, int nseg, int bits)
+{
+    if (segments_ok(seg_offsets, nseg) != FFTSP_OK || mantissa(bits) < 0) return 0;
+    const std::vector<SegBatch> batches = plan_segments(seg_offsets, nseg, 0.5f, bits, false);
+    return (size_t)segment_lanes(batches.size()) * segment_region_bytes(batches);
+}
+
+// Heaviest launch set first, each onto the lane with the least work so far (work = samples); lane 0 is the caller's
+// stream.  Returns the lane of every launch set.
+static std::vector<int> assign_lanes(const std::vector<SegBatch>& batches, int lanes)
+{
+    std::vector<size_t> order(batches.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) {
+        return batches[a].count * (size_t)batches[a].L > batches[b].count * (size_t)batches[b].L;
+    });
+    std::vector<size_t> load((size_t)lanes, 0);
+    std::vector<int> lane_of(batches.size(), 0);
+    for (size_t i : order) {
+        int best = 0;
+        for (int l = 1; l < lanes; ++l)
+            if (load[(size_t)l] < load[(size_t)best]) best = l;
+        lane_of[i] = best;
+        // a launch set costs its samples plus a fixed price for its ten or so launches
+        load[(size_t)best] += batches[i].count * (size_t)batches[i].L + ((size_t)1 << 18);
+    }
+    return lane_of;
+}
+
+}  // extern "C" (a template cannot have C linkage)
+
+// body(launch set index, stream, lane) enqueues one launch set; sets of one lane run in index order on its stream
+template <typename F>
+static hipError_t run_on_lanes(hipStream_t user, const std::vector<int>& lane_of, int lanes, F&& body)
+{
+    if (lanes <= 1) {
+        for (size_t bi = 0; bi < lane_of.size(); ++bi) {
+            const hipError_t e = body(bi, user, 0);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_seg_mutex);
+    SegLanes& ln = g_seg_lanes[dev];
+    if (!ln.ready) {
+        for (int i = 0; i < kSegLanes - 1; ++i) {
+            e = hipStreamCreateWithFlags(&ln.s[i], hipStreamNonBlocking);  // default priority
+            if (e == hipSuccess) e = hipEventCreateWithFlags(&ln.join[i], hipEventDisableTiming);
+            if (e != hipSuccess) return e;
+        }
+        e = hipEventCreateWithFlags(&ln.fork, hipEventDisableTiming);
+        if (e != hipSuccess) return e;
+        ln.ready = true;
+    }
+    e = hipEventRecord(ln.fork, user);
+    for (int l = 1; l < lanes && e == hipSuccess; ++l) e = hipStreamWaitEvent(ln.s[l - 1], ln.fork, 0);
+    if (e != hipSuccess) return e;
+    // every lane that was forked is joined again, whatever happens in between
+    hipError_t first = hipSuccess;
+    for (int l = 0; l < lanes; ++l) {
+        hipStream_t st = l == 0 ? user : ln.s[l - 1];
+        for (size_t bi = 0; bi < lane_of.size() && first == hipSuccess; ++bi)
+            if (lane_of[bi] == l) first = body(bi, st, l);
+        if (l > 0) {
+            hipError_t j = hipEventRecord(ln.join[l - 1], st);
+            if (j == hipSuccess) j = hipStreamWaitEvent(user, ln.join[l - 1], 0);
+            if (first == hipSuccess) first = j;
+        }
+    }
+    return first;
+}
+
+extern "C" {
+
+// a lane's workspace: the usual layout, moved to the lane's region
+static Workspace region_workspace(size_t count, uint32_t L, size_t region_offset)
+{
+    Workspace w = make_workspace(count, L);
+    w.status += region_offset;
+    w.hist += region_offset;
+    w.sel += region_offset;
+    w.tinfo += region_offset;
+    w.tscan += region_offset;
+    w.cand += region_offset;
+    w.prefix += region_offset;
+    w.spec += region_offset;
+    w.mid += region_offset;
+    return w;
 }
 
 static CodecArgs segment_args(const SegBatch& b, const size_t* seg_offsets, int nseg, float theta, int bits, int m)
@@ -748,22 +859,27 @@ int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int 
     uint8_t* out = static_cast<uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     const std::vector<SegBatch> batches = plan_segments(seg_offsets, nseg, theta, bits, true);
-    for (size_t bi = 0; bi < batches.size(); ++bi) {
+    const size_t region = segment_region_bytes(batches);
+    const int lanes = prof::enabled() ? 1 : segment_lanes(batches.size());  // per-kernel timing wants one chain
+    const std::vector<int> lane_of = assign_lanes(batches, lanes);
+    const hipError_t e = run_on_lanes(s, lane_of, lanes, [&](size_t bi, hipStream_t st, int lane) {
         const SegBatch& b = batches[bi];
-        const Workspace w = make_workspace(b.count, b.L);
+        // every lane clears and uses the status words and histograms of its own region; nothing on the sender
+        // raises a status, and the caller reads the first region's word
+        const Workspace w = region_workspace(b.count, b.L, (size_t)lane * region);
         CodecArgs a = segment_args(b, seg_offsets, nseg, theta, bits, m);
         a.write_header = (bi == 0);
         float* spec = reinterpret_cast<float*>(ws + w.spec);
         int hist_done = 0;
-        hipError_t e = launch_rfft(d_grad, 0, log2_exact(b.L), b.count, spec, a.sstride,
-                                   reinterpret_cast<float2*>(ws + w.mid), t, reinterpret_cast<uint32_t*>(ws + w.hist),
-                                   reinterpret_cast<uint32_t*>(ws + w.status),
-                                   (w.hist - w.status) / 4 + b.count * (size_t)kHistBins, &hist_done, 1, &a.pair_log,
-                                   &b.tab, s);
-        if (e == hipSuccess) e = launch_encode(spec, a, out, out + kStreamHeader, ws, w, hist_done, s);
-        if (e != hipSuccess) return FFTSP_EHIP;
-    }
-    return FFTSP_OK;
+        hipError_t pe = launch_rfft(d_grad, 0, log2_exact(b.L), b.count, spec, a.sstride,
+                                    reinterpret_cast<float2*>(ws + w.mid), t, reinterpret_cast<uint32_t*>(ws + w.hist),
+                                    reinterpret_cast<uint32_t*>(ws + w.status),
+                                    (w.hist - w.status) / 4 + b.count * (size_t)kHistBins, &hist_done, 1, &a.pair_log,
+                                    &b.tab, st);
+        if (pe == hipSuccess) pe = launch_encode(spec, a, out, out + kStreamHeader, ws, w, hist_done, st);
+        return pe;
+    });
+    return hip_status(e);
 }
 
 int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* d_grad_out, const size_t* seg_offsets,
@@ -784,21 +900,28 @@ int fftsp_decompress_segments(const void* d_packed, size_t packed_bytes, float* 
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     const uint8_t* in = static_cast<const uint8_t*>(d_packed);
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    // every launch set raises the same status word; it is cleared once, by the first set's kernels
     const std::vector<SegBatch> batches = plan_segments(seg_offsets, nseg, theta, bits, true);
-    for (size_t bi = 0; bi < batches.size(); ++bi) {
-        const SegBatch& b = batches[bi];
-        const Workspace w = make_workspace(b.count, b.L);
-        CodecArgs a = segment_args(b, seg_offsets, nseg, theta, bits, m);
-        a.pair_log = fft_pair_log(log2_exact(b.L));
-        float* spec = reinterpret_cast<float*>(ws + w.spec);
-        hipError_t e = launch_decode(in, in + kStreamHeader, a, spec, ws, w, bi == 0, bi == 0, s);
-        if (e == hipSuccess)
-            e = launch_irfft(spec, a.sstride, 0, log2_exact(b.L), b.count, d_grad_out,
-                             reinterpret_cast<float2*>(ws + w.mid), t, a.pair_log != 0, 1.0f, &b.tab, s);
-        if (e != hipSuccess) return FFTSP_EHIP;
-    }
-    return FFTSP_OK;
+    const size_t region = segment_region_bytes(batches);
+    const int lanes = prof::enabled() ? 1 : segment_lanes(batches.size());
+    const std::vector<int> lane_of = assign_lanes(batches, lanes);
+    // every launch set raises the one status word at the start of the workspace, from whatever lane it runs on:
+    // it is cleared here, before the lanes fork
+    hipError_t e = launch_clear_status(ws, make_workspace(1, 32), s);
+    if (e == hipSuccess)
+        e = run_on_lanes(s, lane_of, lanes, [&](size_t bi, hipStream_t st, int lane) {
+            const SegBatch& b = batches[bi];
+            Workspace w = region_workspace(b.count, b.L, (size_t)lane * region);
+            w.status = 0;
+            CodecArgs a = segment_args(b, seg_offsets, nseg, theta, bits, m);
+            a.pair_log = fft_pair_log(log2_exact(b.L));
+            float* spec = reinterpret_cast<float*>(ws + w.spec);
+            hipError_t pe = launch_decode(in, in + kStreamHeader, a, spec, ws, w, bi == 0, 0, st);
+            if (pe == hipSuccess)
+                pe = launch_irfft(spec, a.sstride, 0, log2_exact(b.L), b.count, d_grad_out,
+                                  reinterpret_cast<float2*>(ws + w.mid), t, a.pair_log != 0, 1.0f, &b.tab, st);
+            return pe;
+        });
+    return hip_status(e);
 }
 
 int fftsp_device_status(const void* d_workspace, int* status_out)

@@ -1429,6 +1429,13 @@ static hipError_t launch_zero_hist(uint8_t* ws_base, const Workspace& w, size_t 
     return hipGetLastError();
 }
 
+hipError_t launch_clear_status(uint8_t* ws_base, const Workspace& w, hipStream_t s)
+{
+    FFTSP_LAUNCH("zero_fill", k_zero_u32, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(ws_base + w.status),
+                 (size_t)1);
+    return hipGetLastError();
+}
+
 hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
                          uint8_t* ws_base, const Workspace& w, int hist_ready, hipStream_t s)
 {

@@ -260,6 +260,9 @@ static inline PeerWorkspace make_peer_workspace(const Workspace& w, size_t C, ui
 hipError_t launch_encode(const float* spec, const CodecArgs& a, uint8_t* stream_base, uint8_t* records,
                          uint8_t* ws_base, const Workspace& w, int hist_ready, hipStream_t s);
 
+// clears the device status word (for callers that decode a stream as several concurrent launch sets)
+hipError_t launch_clear_status(uint8_t* ws_base, const Workspace& w, hipStream_t s);
+
 // reset_status != 0: this call also clears the device status word (first record set of a stream)
 hipError_t launch_decode(const uint8_t* stream_base, const uint8_t* records, const CodecArgs& a, float* spec,
                          uint8_t* ws_base, const Workspace& w, int check_header, int reset_status, hipStream_t s);
