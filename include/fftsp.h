@@ -1,16 +1,18 @@
 /*
  * fftsp.h -- C ABI of the MI355X (gfx950) FFT-sparsifying gradient codec.
  *
- * The codec is the per-worker sender/receiver pair of arXiv 1811.08596, Sec. 3.1
- * ("The Compression Framework"): linearized gradient -> FFT -> keep the largest
+ * The codec is the per-worker sender/receiver pair of arXiv 1811.08596, Sec. 3.1:
+ * linearized gradient -> FFT -> keep the largest
  * frequency components -> range-based N-bit float -> pack; the receiver applies
  * the inverse operations in reverse order.
  *
  * Conventions shared by every entry point
  *   - Pointers named d_* are DEVICE pointers (hipMalloc / torch CUDA memory),
  *     16-byte aligned.  seg_offsets is a HOST pointer.  The caller owns every
- *     buffer; the library allocates nothing per call (two 16 KiB twiddle tables
- *     are created once per device on first use and kept until process exit).
+ *     buffer; the library allocates nothing (its two 16 KiB twiddle tables are
+ *     constants inside the code object).  The per-tensor entry points create
+ *     three streams and four events per device on their first call, which
+ *     therefore must not sit inside a stream capture.
  *   - Calls only enqueue work on `stream` and return; they never synchronise and
  *     never touch the null stream.  Input buffers are not modified.  Output
  *     regions are written completely (padding bytes zero), so results are
@@ -64,7 +66,7 @@ typedef enum {
 
 /* k = clamp(floor((double)theta * B + 1/2), 0, B): kept bins per chunk (selection rule of Sec. 3.1.1). */
 int fftsp_kept_per_chunk(uint32_t chunk_len, float theta, uint32_t* k_out);
-/* default mantissa width m of the N-bit float (Sec. 3.2.1: "m bits left for the mantissa"); -1 if bits invalid. */
+/* default mantissa width m of the N-bit float (Sec. 3.2.1, the split of the N bits); -1 if bits invalid. */
 int fftsp_mantissa_bits(int bits);
 /* exact size of the packed stream, 0 on invalid arguments. */
 size_t fftsp_packed_bytes(size_t n, uint32_t chunk_len, float theta, int bits);
@@ -85,7 +87,7 @@ int fftsp_decompress(const void* d_packed, size_t packed_bytes,
                      float* d_grad_out, size_t n, uint32_t chunk_len, float theta, int bits,
                      void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
 
-/* ---- quantizer options (Sec. 3.2.1: "we tune m and eps"; "manual setting of a representation range") ----
+/* ---- quantizer options (Sec. 3.2.1: the choice of m and eps; the static [min, max] range) ----
  *
  * The entry points above fix m from the code width and fit the range of every chunk to its largest surviving
  * component.  The _q variants take both from the caller; quantizer == NULL means the defaults.

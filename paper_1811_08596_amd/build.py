@@ -9,13 +9,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfftsp.so")
 SOURCES = ["fft.hip", "codec.hip", "api.hip", "prof.hip"]
-HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(os.path.dirname(HERE), "include", "fftsp.h")]
+HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "twiddle_table.h"), os.path.join(os.path.dirname(HERE), "include", "fftsp.h")]
 
 # no fast-math: twiddles, keys and the split must round the same way on every launch
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-function",
+    "-Wall", "-Wno-unused-function", "-fconstexpr-steps=50000000",
 ]
 
 

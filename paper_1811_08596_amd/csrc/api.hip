@@ -1,6 +1,7 @@
 // C ABI of libfftsp.so (see include/fftsp.h): argument checks, workspace carving, launch order.
 #include "../../include/fftsp.h"
 #include "internal.h"
+#include "twiddle_table.h"
 
 #include <algorithm>
 #include <cmath>
@@ -11,6 +12,11 @@
 namespace fftsp {
 
 namespace {
+// Compile-time tables in device memory (twiddle_table.h): one copy per device, loaded with the code object.
+__device__ const twtab::Table g_tw_hi = twtab::make_table<11>();
+__device__ const twtab::Table g_tw_lo = twtab::make_table<22>();
+static_assert(sizeof(twtab::Pair) == sizeof(float2), "table entries are read as float2");
+
 struct DeviceTables {
     bool ready = false;
     Tables t{nullptr, nullptr};
@@ -20,6 +26,7 @@ DeviceTables g_tables[kMaxDevices];
 std::mutex g_mutex;
 }  // namespace
 
+// Looks up this device's addresses of the two tables once; allocates nothing and enqueues nothing.
 hipError_t get_tables(Tables* out)
 {
     int dev = 0;
@@ -29,24 +36,12 @@ hipError_t get_tables(Tables* out)
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceTables& d = g_tables[dev];
     if (!d.ready) {
-        std::vector<float2> hi(2048), lo(2048);
-        const double two_pi = 6.283185307179586476925286766559;
-        for (int i = 0; i < 2048; ++i) {
-            const double a = two_pi * (double)i / 2048.0, b = two_pi * (double)i / 4194304.0;
-            hi[i] = make_float2((float)std::cos(a), (float)-std::sin(a));
-            lo[i] = make_float2((float)std::cos(b), (float)-std::sin(b));
-        }
-        float2* dev_mem = nullptr;
-        e = hipMalloc(reinterpret_cast<void**>(&dev_mem), 2 * 2048 * sizeof(float2));
+        void *hi = nullptr, *lo = nullptr;
+        e = hipGetSymbolAddress(&hi, HIP_SYMBOL(g_tw_hi));
+        if (e == hipSuccess) e = hipGetSymbolAddress(&lo, HIP_SYMBOL(g_tw_lo));
         if (e != hipSuccess) return e;
-        e = hipMemcpy(dev_mem, hi.data(), 2048 * sizeof(float2), hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = hipMemcpy(dev_mem + 2048, lo.data(), 2048 * sizeof(float2), hipMemcpyHostToDevice);
-        if (e != hipSuccess) {
-            (void)hipFree(dev_mem);
-            return e;
-        }
-        d.t.hi = dev_mem;
-        d.t.lo = dev_mem + 2048;
+        d.t.hi = static_cast<const float2*>(hi);
+        d.t.lo = static_cast<const float2*>(lo);
         d.ready = true;
     }
     *out = d.t;

@@ -24,9 +24,12 @@ constexpr int ROWS = 8;              // rows of 64 bins per wave
 constexpr int WAVE_BINS = ROWS * 64; // 512
 static_assert(kTile == 4 * WAVE_BINS, "tile geometry");
 
+// The sign bit is masked: a finite sum of squares has none, and a NaN that carries one must still land inside the
+// 31-bit key space the histogram and the radix digits are sized for (selection among non-finite bins is then
+// ordinary integer work on their bit patterns, and exactly k bins survive whatever the input holds).
 __device__ __forceinline__ uint32_t key_of(float2 z)
 {
-    return __float_as_uint(__fmaf_rn(z.x, z.x, __fmul_rn(z.y, z.y)));
+    return __float_as_uint(__fmaf_rn(z.x, z.x, __fmul_rn(z.y, z.y))) & 0x7FFFFFFFu;
 }
 __device__ __forceinline__ uint32_t vbits_of(float2 z)
 {
@@ -331,6 +334,13 @@ __global__ __launch_bounds__(NT) void k_find_bucket(const uint32_t* __restrict__
         }
         return;
     }
+    // The histogram counts every bin of the chunk, so some bucket always qualifies; should it ever not (fewer than
+    // k bins counted), the selection words still get defined values instead of the previous call's.
+    if (tid == 0) {
+        sel[c * 8 + 0] = 0;
+        sel[c * 8 + 1] = 0;
+    }
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         if (run < k && run + loc[i] >= k) {
@@ -588,6 +598,10 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             const uint32_t dmask = pass == 0 ? 1023u : 511u;
             const uint32_t pmask = pass == 0 ? (0xFFFFFFFFu << kKeyShift) : (0xFFFFFFFFu << 9);
             h[tid] = 0u;
+            if (tid == 0) {  // defined even if no digit qualifies (the counts then disagree with the histogram)
+                s_digit = 0u;
+                s_need = 0u;
+            }
             __syncthreads();
             if (staged) {
                 const uint32_t total = s_carry[0];
@@ -678,11 +692,13 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
         const uint32_t take = eqpre >= quota ? 0u : (eq < quota - eqpre ? eq : quota - eqpre);
         const uint32_t surv = in ? (tdef[t] + tgt[t] + take) : 0u;
         const uint32_t rkincl = block_scan_incl_1024(surv, tmp);
-        const uint32_t rank = crk + rkincl - surv;
+        // ranks never leave [0, k]: whatever the counts say, the code words of a tile stay inside the record
+        const uint32_t rank_raw = crk + rkincl - surv;
+        const uint32_t rank = rank_raw < k ? rank_raw : k;
         if (in) {
             ttake[t] = take;
             trank[t] = rank;
-            tsurv[t] = surv;
+            tsurv[t] = surv < k - rank ? surv : k - rank;
             tscan[(c * Tn + t) * 2 + 0] = rank;
             tscan[(c * Tn + t) * 2 + 1] = eqpre;
         }
@@ -921,7 +937,9 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::
     }
     if (total) {
         const uint32_t w1 = (twoN * (rank0 + total) - 1u) >> 5;
-        const uint32_t nw = w1 - w0 + 1u;
+        const uint32_t rec_words = (uint32_t)(S / 4) - 4u - W;  // code words the record has room for
+        const uint32_t nw_all = w1 - w0 + 1u;
+        const uint32_t nw = w0 >= rec_words ? 0u : (nw_all < rec_words - w0 ? nw_all : rec_words - w0);
         for (uint32_t i = tid; i < nw; i += NT) {
             const uint32_t v = cw[i];
             if (i == 0 || i == nw - 1u)

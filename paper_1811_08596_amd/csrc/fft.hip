@@ -578,7 +578,7 @@ __global__ __launch_bounds__(kNT) void k_fwd_a(const float* __restrict__ in, siz
 
 __device__ __forceinline__ uint32_t fft_key_of(float2 z)
 {
-    return __float_as_uint(__fmaf_rn(z.x, z.x, __fmul_rn(z.y, z.y)));
+    return __float_as_uint(__fmaf_rn(z.x, z.x, __fmul_rn(z.y, z.y))) & 0x7FFFFFFFu;  // as the codec's key_of
 }
 
 // Forward pass B: N2-point FFTs along n2 for a tile of rows and their mirrors, then the real-FFT split.
