@@ -80,6 +80,20 @@ int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float thet
                    void* d_packed, size_t packed_capacity,
                    void* d_workspace, size_t workspace_bytes, fftsp_stream_t stream);
 
+/* The sender for callers that cannot allocate device memory or pass a workspace: code recorded into a HIP graph,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same packed bytes as fftsp_compress; the
+ * workspace is a fixed array of FFTSP_STATIC_SCRATCH_BYTES inside the library's code object (every GPU the
+ * library runs on holds its own copy until the process ends).  The call allocates nothing, on the host side
+ * of HIP or on the device (keep fftsp_profile_enable off: its events are created on demand).
+ * Limit: fftsp_workspace_bytes(n, chunk_len, bits) <= FFTSP_STATIC_SCRATCH_BYTES (e.g. n = 2^20 with
+ * chunk_len = 2^16, or one chunk of 2^20); beyond that the call returns FFTSP_EWORKSPACE and enqueues nothing.
+ * All calls on one GPU share that GPU's array: two calls that may overlap in time (different streams, no event
+ * between them) race and must be ordered by the caller.  The array keeps the last call's contents; the kernels
+ * clear what they need cleared.  The device status word lives inside the array and cannot be read back. */
+#define FFTSP_STATIC_SCRATCH_BYTES (16u << 20)
+int fftsp_compress_static(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits,
+                          void* d_packed, size_t packed_capacity, fftsp_stream_t stream);
+
 /* Receiver.  The same (n, chunk_len, theta, bits) as the sender must be passed; a stream whose
  * header disagrees sets the device status word to FFTSP_EFORMAT and the output is unspecified
  * (reads stay inside d_packed[0, packed_bytes)).  d_grad_out: exactly n floats are written. */

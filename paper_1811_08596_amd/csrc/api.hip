@@ -13,8 +13,10 @@ namespace fftsp {
 
 namespace {
 // Compile-time tables in device memory (twiddle_table.h): one copy per device, loaded with the code object.
-__device__ const twtab::Table g_tw_hi = twtab::make_table<11>();
-__device__ const twtab::Table g_tw_lo = twtab::make_table<22>();
+// (not declared const: a const device variable that no device code names is dropped from the code object, and
+// the host-side lookup of its address then finds nothing)
+static __device__ twtab::Table g_tw_hi = twtab::make_table<11>();
+static __device__ twtab::Table g_tw_lo = twtab::make_table<22>();
 static_assert(sizeof(twtab::Pair) == sizeof(float2), "table entries are read as float2");
 
 struct DeviceTables {
@@ -344,8 +346,12 @@ int fftsp_decode_spectrum(const void* d_packed, size_t packed_bytes, size_t n, u
     return fftsp_decode_spectrum_q(d_packed, packed_bytes, n, chunk_len, theta, bits, d_spec, d_workspace, workspace_bytes, nullptr, stream);
 }
 
-int fftsp_compress_q(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
-                   size_t packed_capacity, void* d_workspace, size_t workspace_bytes, const fftsp_quantizer* quantizer, fftsp_stream_t stream)
+}  // extern "C"
+
+// the sender proper, shared by the entry points that differ only in where the workspace comes from
+static int compress_impl(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                         size_t packed_capacity, void* d_workspace, size_t workspace_bytes,
+                         const fftsp_quantizer* quantizer, hipStream_t s)
 {
     Plan p;
     int rc = make_plan(&p, n, chunk_len, &theta, &bits);
@@ -361,7 +367,6 @@ int fftsp_compress_q(const float* d_grad, size_t n, uint32_t chunk_len, float th
     if (get_tables(&t) != hipSuccess) return FFTSP_EHIP;
     uint8_t* ws = static_cast<uint8_t*>(d_workspace);
     uint8_t* out = static_cast<uint8_t*>(d_packed);
-    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     float* spec = reinterpret_cast<float*>(ws + p.ws.spec);
     int hist_done = 0;
     CodecArgs a = codec_args(p, theta);
@@ -374,6 +379,53 @@ int fftsp_compress_q(const float* d_grad, size_t n, uint32_t chunk_len, float th
     if (e == hipSuccess)
         e = launch_encode(spec, a, out, out + kStreamHeader, ws, p.ws, hist_done, s);
     return hip_status(e);
+}
+
+// Workspace of fftsp_compress_static: one array per device inside the code object.  Host code never uses the
+// array's name as an address: the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[FFTSP_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[64];
+static std::mutex g_scratch_mutex;
+
+static hipError_t static_scratch(void** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+extern "C" {
+
+int fftsp_compress_q(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                   size_t packed_capacity, void* d_workspace, size_t workspace_bytes, const fftsp_quantizer* quantizer, fftsp_stream_t stream)
+{
+    return compress_impl(d_grad, n, chunk_len, theta, bits, d_packed, packed_capacity, d_workspace, workspace_bytes,
+                         quantizer, reinterpret_cast<hipStream_t>(stream));
+}
+
+int fftsp_compress_static(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,
+                          size_t packed_capacity, fftsp_stream_t stream)
+{
+    // sizes first: a call that cannot fit is refused before the device is touched
+    Plan p;
+    const int rc = make_plan(&p, n, chunk_len, &theta, &bits);
+    if (rc) return rc;
+    if (p.ws.total > (size_t)FFTSP_STATIC_SCRATCH_BYTES) return FFTSP_EWORKSPACE;
+    void* ws = nullptr;
+    if (static_scratch(&ws) != hipSuccess) return FFTSP_EHIP;
+    return compress_impl(d_grad, n, chunk_len, theta, bits, d_packed, packed_capacity, ws,
+                         (size_t)FFTSP_STATIC_SCRATCH_BYTES, nullptr, reinterpret_cast<hipStream_t>(stream));
 }
 
 int fftsp_compress(const float* d_grad, size_t n, uint32_t chunk_len, float theta, int bits, void* d_packed,

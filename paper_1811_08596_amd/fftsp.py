@@ -33,6 +33,8 @@ SIGNATURES = {
                                  C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_decompress": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+    "fftsp_compress_static": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_void_p,
+                                        C.c_size_t, C.c_void_p]),
     "fftsp_compress_h": (C.c_int, [C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int, C.c_int, C.c_void_p,
                                    C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p]),
     "fftsp_decompress_h": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int,
@@ -167,6 +169,15 @@ def _nbytes(t) -> int:
 def compress(grad, chunk_len: int, theta: float, bits: int, packed, workspace, stream=None):
     _check(load().fftsp_compress(_ptr(grad), grad.numel(), chunk_len, theta, bits, _ptr(packed), _nbytes(packed),
                                  _ptr(workspace), _nbytes(workspace), _stream(stream)), "fftsp_compress")
+
+
+STATIC_SCRATCH_BYTES = 16 << 20  # FFTSP_STATIC_SCRATCH_BYTES
+
+
+def compress_static(grad, chunk_len: int, theta: float, bits: int, packed, stream=None):
+    """fftsp_compress on the library's own fixed scratch array: no workspace argument, no allocation."""
+    _check(load().fftsp_compress_static(_ptr(grad), grad.numel(), chunk_len, theta, bits, _ptr(packed),
+                                        _nbytes(packed), _stream(stream)), "fftsp_compress_static")
 
 
 def decompress(packed, packed_nbytes: int, grad_out, chunk_len: int, theta: float, bits: int, workspace, stream=None):
