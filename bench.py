@@ -32,6 +32,8 @@ def kernel_algorithmic_bytes(name: str, n: int, L: int, theta: float, bits: int)
     table = {
         "rfft_pass_a": 4.0 * n + 4.0 * C * L,     # gradient in, intermediate out
         "rfft_pass_b": 4.0 * C * L + spec,        # intermediate in, spectrum out
+        "rfft_fused": 4.0 * n + spec,             # both passes in one kernel: gradient in, spectrum out
+        "irfft_fused": spec + 4.0 * n,
         "rfft_small": 4.0 * n + spec,
         "hist": spec,
         "collect": spec,

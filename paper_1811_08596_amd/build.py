@@ -8,8 +8,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfftsp.so")
-SOURCES = ["fft.hip", "codec.hip", "api.hip", "prof.hip"]
-HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "twiddle_table.h"), os.path.join(os.path.dirname(HERE), "include", "fftsp.h")]
+SOURCES = ["fft.hip", "fused.hip", "codec.hip", "api.hip", "prof.hip"]
+HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "fft_core.h"), os.path.join(CSRC, "twiddle_table.h"), os.path.join(os.path.dirname(HERE), "include", "fftsp.h")]
 
 # no fast-math: twiddles, keys and the split must round the same way on every launch
 HIPCC_FLAGS = [

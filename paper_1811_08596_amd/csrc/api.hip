@@ -228,6 +228,24 @@ int apply_quantizer(Plan* p, const fftsp_quantizer* q, uint32_t* static_vmax)
     return FFTSP_OK;
 }
 
+// The receiver's inverse transform of the codec's own spectrum buffer (uniform chunks).  The decode kernels that
+// ran before it on this stream have cleared the control block.
+hipError_t inverse_of_decoded(const Plan& p, const float* spec, uint32_t sstride, int pair_log, float* out, uint8_t* ws,
+                              Tables t, float gain, hipStream_t s)
+{
+    float2* mid = reinterpret_cast<float2*>(ws + p.ws.mid);
+    const FusedKnobs knobs = fused_knobs();
+    if (knobs.enabled && pair_log != 0 && fused_applies(p.logL, p.C)) {
+        uint32_t* ctl = reinterpret_cast<uint32_t*>(ws + p.ws.status);
+        hipError_t e = launch_fused_irfft(reinterpret_cast<const float2*>(spec), sstride, p.n, p.logL, p.C, out, mid, t,
+                                          gain, ctl, knobs, s);
+        if (e != hipSuccess) return e;
+        // stand-by: the per-pass kernels redo the transform if the fused kernel gave up
+        return launch_irfft(spec, sstride, p.n, p.logL, p.C, out, mid, t, 1, gain, nullptr, s, ctl + kCtlGaveUpWord);
+    }
+    return launch_irfft(spec, sstride, p.n, p.logL, p.C, out, mid, t, pair_log != 0, gain, nullptr, s);
+}
+
 }  // namespace
 }  // namespace fftsp
 
@@ -372,10 +390,25 @@ static int compress_impl(const float* d_grad, size_t n, uint32_t chunk_len, floa
     CodecArgs a = codec_args(p, theta);
     a.static_vmax = static_vmax;
     a.sstride = padded_bins(p.L);
-    hipError_t e = launch_rfft(d_grad, n, p.logL, p.C, spec, a.sstride, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                               reinterpret_cast<uint32_t*>(ws + p.ws.hist),
-                               reinterpret_cast<uint32_t*>(ws + p.ws.status),
-                               (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, &hist_done, 1, &a.pair_log, nullptr, s);
+    uint32_t* ctl = reinterpret_cast<uint32_t*>(ws + p.ws.status);
+    uint32_t* hist = reinterpret_cast<uint32_t*>(ws + p.ws.hist);
+    float2* mid = reinterpret_cast<float2*>(ws + p.ws.mid);
+    const FusedKnobs knobs = fused_knobs();
+    hipError_t e;
+    if (knobs.enabled && fused_applies(p.logL, p.C)) {
+        // both passes in one kernel, the intermediate in the L2 caches (fused.hip); the per-pass kernels stand by
+        // behind it and run only if it gave up (they then clear the histograms again, not the control block)
+        e = launch_zero_control(ws, p.ws, p.C, s);
+        if (e == hipSuccess)
+            e = launch_fused_rfft(d_grad, n, p.logL, p.C, reinterpret_cast<float2*>(spec), a.sstride, mid, t, hist, ctl,
+                                  knobs, s);
+        if (e == hipSuccess)
+            e = launch_rfft(d_grad, n, p.logL, p.C, spec, a.sstride, mid, t, hist, hist, p.C * kHistBins, &hist_done, 1,
+                            &a.pair_log, nullptr, s, ctl + kCtlGaveUpWord);
+    } else {
+        e = launch_rfft(d_grad, n, p.logL, p.C, spec, a.sstride, mid, t, hist, ctl,
+                        (p.ws.hist - p.ws.status) / 4 + p.C * kHistBins, &hist_done, 1, &a.pair_log, nullptr, s);
+    }
     if (e == hipSuccess)
         e = launch_encode(spec, a, out, out + kStreamHeader, ws, p.ws, hist_done, s);
     return hip_status(e);
@@ -459,9 +492,7 @@ int fftsp_decompress_q(const void* d_packed, size_t packed_bytes, float* d_grad_
     a.sstride = padded_bins(p.L);
     a.pair_log = fft_pair_log(p.logL);
     hipError_t e = launch_decode(in, in + kStreamHeader, a, spec, ws, p.ws, 1, 1, s);
-    if (e == hipSuccess)
-        e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                         a.pair_log != 0, 1.0f, nullptr, s);
+    if (e == hipSuccess) e = inverse_of_decoded(p, spec, a.sstride, a.pair_log, d_grad_out, ws, t, 1.0f, s);
     return hip_status(e);
 }
 
@@ -535,9 +566,7 @@ int fftsp_decompress_accumulate(const void* const* d_packed, int npeers, size_t 
     a.sstride = padded_bins(p.L);
     a.pair_log = fft_pair_log(p.logL);
     hipError_t e = launch_decode_peers(peers, npeers, a, spec, ws, p.ws, pw, s);
-    if (e == hipSuccess)
-        e = launch_irfft(spec, a.sstride, n, p.logL, p.C, d_grad_out, reinterpret_cast<float2*>(ws + p.ws.mid), t,
-                         a.pair_log != 0, scale, nullptr, s);
+    if (e == hipSuccess) e = inverse_of_decoded(p, spec, a.sstride, a.pair_log, d_grad_out, ws, t, scale, s);
     return hip_status(e);
 }
 

@@ -1023,8 +1023,10 @@ __global__ __launch_bounds__(RT) void k_group_prefix(const uint8_t* __restrict__
     const uint32_t G = (W + GROUP_WORDS - 1) / GROUP_WORDS;
     group_prefix_chunk(stream, records + record_offset<TABLE>(tab, c, S), c == 0, W, k, word3, hdr, gprefix + c * G,
                        sel + c * 8 + 7);
-    // raised again by k_decode, which runs after this kernel
-    if (threadIdx.x == 0 && reset_status && c == 0) status[0] = 0u;
+    // The whole control block is cleared: the status word (raised again by k_decode, which runs after this kernel)
+    // and the hand-over words of the fused inverse transform that may follow.
+    if (reset_status && c == 0)
+        for (uint32_t i = threadIdx.x; i < (uint32_t)(kControlBytes / 4); i += RT) status[i] = 0u;
 }
 
 // The same for several peers' streams: workgroup (peer, chunk).
@@ -1037,7 +1039,8 @@ __global__ __launch_bounds__(RT) void k_group_prefix_peers(PeerList streams, uin
     const uint8_t* stream = streams.p[peer];
     group_prefix_chunk(stream, stream + 64 + (size_t)c * S, c == 0, W, k, 0u, hdr,
                        gprefix + ((size_t)peer * C + c) * G, verd + (size_t)peer * C + c);
-    if (threadIdx.x == 0 && blockIdx.x == 0) status[0] = 0u;
+    if (blockIdx.x == 0)  // the whole control block, as k_group_prefix does
+        for (uint32_t i = threadIdx.x; i < (uint32_t)(kControlBytes / 4); i += RT) status[i] = 0u;
 }
 
 // Persistent decoder.  A workgroup walks tiles of 2048 bins (blockIdx, blockIdx + grid, ...), one wave per
@@ -1445,6 +1448,11 @@ static hipError_t launch_zero_hist(uint8_t* ws_base, const Workspace& w, size_t 
     FFTSP_LAUNCH("zero_fill", k_zero_u32, dim3((unsigned)((zero_words + 255) / 256)), dim3(256), 0, s, status,
                  zero_words);
     return hipGetLastError();
+}
+
+hipError_t launch_zero_control(uint8_t* ws_base, const Workspace& w, size_t C, hipStream_t s)
+{
+    return launch_zero_hist(ws_base, w, C, s);
 }
 
 hipError_t launch_clear_status(uint8_t* ws_base, const Workspace& w, hipStream_t s)

@@ -1,0 +1,751 @@
+// The two FFT passes of a chunk fused into one persistent kernel whose intermediate never leaves the L2 cache.
+//
+// The transform is the DFT sum of arXiv 1811.08596 Sec. 3.1.1 (and its inverse on the receiver, Sec. 3.1, last
+// paragraph), factored M = N1*N2 exactly as in fft.hip.  There, pass A writes the whole intermediate to memory and
+// pass B reads it back: two sweeps of the gradient's size per direction.  Here the chip's eight L2 caches (one per
+// XCD, 4 MiB each) carry it instead.  Workgroups are dispatched to XCDs round-robin by index, so the 64 resident
+// workgroups b = x, x+8, ... of XCD x form a team that shares one L2.  A team works in turns; a turn is 64 tiles of
+// 8192 points (4 MiB of intermediate: one chunk of 2^20 samples, or several shorter chunks):
+//     pass A on the team's tiles   -> stored into the team's 4 MiB scratch region (stays dirty in L2)
+//     every member arrives         -> "stored" counter
+//     pass B on the team's tiles   <- loaded from scratch with L1-bypassing loads (hits in L2)
+//     every member arrives         -> "loaded" counter, which the next turn's stores wait for
+// The same 4 MiB are reused turn after turn, so the lines are overwritten in L2 and rarely travel to memory.
+// With two teams per XCD (32 members, two tiles each per pass) the turns of the two teams alternate on the one
+// scratch region, so that one team computes while the other waits for its hand-over.
+//
+// Hand-over protocol.  Writers: plain stores, then every wave waits until its stores are acknowledged by L2
+// (vmcnt(0)), a workgroup barrier, and one device-scope atomic increment.  Readers: poll the counter with
+// device-scope loads, a workgroup barrier, then loads that bypass the per-CU L1 (device-scope relaxed atomic
+// loads), which an earlier turn may have filled with the region's old contents.  No L2 write-back or invalidate
+// is issued: writer and reader share the L2, which is what makes the hand-over cheap (about 2 us).  That premise
+// is checked, not assumed: every workgroup publishes the XCD it runs on (XCC_ID register) and a team whose members
+// disagree gives up.  All waits are bounded; a workgroup whose wait expires, or that sees the give-up word set,
+// sets it and exits, and so does every other workgroup at its next wait.  The host always enqueues the per-pass
+// kernels of fft.hip behind a fused kernel with the give-up word as their switch: they return at once unless it
+// is set, in which case they redo the whole transform.  The result is therefore the same either way.
+#include "fft_core.h"
+#include <cstdlib>
+
+namespace fftsp {
+namespace {
+
+constexpr int kXcds = 8;         // L2 caches of the chip; workgroup b runs on XCD b % 8
+constexpr int kXcdWgs = 64;      // workgroups of this kernel resident per XCD: 32 compute units x 2
+constexpr int kTurnTiles = 64;   // tiles per turn: 64 x 64 KiB = one L2's worth of intermediate
+// stage twiddles exp(-2 pi i e / 1024): a radix-8 stage reads e < 7/8 of a turn only
+constexpr int kTwEntries = 896;
+// tile, stage twiddles, 16-bit key histogram, one word for the outcome of a wait
+constexpr size_t kFusedLds = ((size_t)(1 << kLogE) + kTwEntries) * sizeof(float2) + kHistLdsWords * sizeof(uint32_t) + 16;
+static_assert(2 * kFusedLds <= 160 * 1024, "two workgroups per compute unit (the kernel has no static LDS)");
+
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// 16 bytes read past the L1 (two device-scope 8-byte loads: they are served by L2, never by this CU's L1)
+__device__ __forceinline__ float4 ld_l2(const float4* p)
+{
+    const uint64_t* q = reinterpret_cast<const uint64_t*>(p);
+    const uint64_t a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint64_t b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float4(__uint_as_float((uint32_t)a), __uint_as_float((uint32_t)(a >> 32)), __uint_as_float((uint32_t)b),
+                       __uint_as_float((uint32_t)(b >> 32)));
+}
+
+// XCD this wave runs on (hardware register XCC_ID, bits 3:0)
+__device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & 15u; }
+
+struct TeamCtl {
+    uint32_t* stored;   // members that finished storing, over all turns of this XCD
+    uint32_t* loaded;   // members that finished loading, over all turns of this XCD
+    uint32_t* gave_up;  // != 0: some workgroup of the launch gave up; everybody leaves
+    uint32_t spin_limit;
+};
+
+// Wait (lane 0 polls) until *ctr >= target.  Returns false if the wait expired or the launch has given up; the
+// give-up word is then set.  Called by every lane of the workgroup.
+__device__ __forceinline__ bool team_wait(const uint32_t* ctr, uint32_t target, const TeamCtl& tc, uint32_t* s_ok)
+{
+    if (threadIdx.x == 0) {
+        uint32_t spins = 0;
+        bool ok = true;
+        while (ld_agent(ctr) < target) {
+            if (spins >= tc.spin_limit || ld_agent(tc.gave_up) != 0u) {
+                ok = false;
+                break;
+            }
+            ++spins;
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (ok && ld_agent(tc.gave_up) != 0u) ok = false;
+        if (!ok) __hip_atomic_store(tc.gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *s_ok = ok ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool ok = *s_ok != 0u;
+    __syncthreads();
+    return ok;
+}
+
+// Every lane's stores have reached L2, then one arrival is counted.
+__device__ __forceinline__ void team_arrive_after_stores(uint32_t* ctr)
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// stage twiddles for transforms of up to 1024 points from one table: tw[e] = exp(-2 pi i e / 1024), e < 896
+template <int NT>
+__device__ __forceinline__ void load_shared_twiddles(float2* tw, const Tables& tb, int tid)
+{
+    for (int e = tid; e < kTwEntries; e += NT) tw[e] = tb.hi[e << 1];
+}
+
+// run_fft on a table of 1024th roots: a transform of 2^LOGR points reads every 2^(10-LOGR)-th entry
+template <int LOGR, int LOGT, int NT, bool INV, int NS_LOG, int RL>
+__device__ __forceinline__ void fft_stage_1024(float2* d, const float2* tw, int tid)
+{
+    constexpr int R = 1 << LOGR, T = 1 << LOGT, RHO = 1 << RL, NS = 1 << NS_LOG;
+    constexpr int NBF = (R / RHO) * T;
+    static_assert(NBF % NT == 0, "butterflies must divide evenly over the workgroup");
+    static_assert(LOGR <= 10, "the shared table holds 1024th roots");
+    constexpr int PER = NBF / NT;
+    float2 v[PER][RHO];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int w = tid + q * NT, b = w & (T - 1), j = w >> LOGT;
+#pragma unroll
+        for (int t = 0; t < RHO; ++t) v[q][t] = d[sw_idx<LOGT>(j + t * (R / RHO), b)];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        const int w = tid + q * NT, b = w & (T - 1), j = w >> LOGT;
+        const int k = j & (NS - 1);
+        if constexpr (NS > 1) {
+#pragma unroll
+            for (int t = 1; t < RHO; ++t) {
+                const float2 c = tw[(t * k) << (10 - NS_LOG - RL)];
+                v[q][t] = INV ? cmulc(v[q][t], c) : cmul(v[q][t], c);
+            }
+        }
+        butterfly<RL, INV>(v[q]);
+        const int base = ((j >> NS_LOG) << (NS_LOG + RL)) + k;
+#pragma unroll
+        for (int t = 0; t < RHO; ++t) d[sw_idx<LOGT>(base + t * NS, b)] = v[q][t];
+    }
+    __syncthreads();
+}
+template <int LOGR, int LOGT, int NT, bool INV, int NS_LOG>
+__device__ __forceinline__ void run_fft_1024(float2* d, const float2* tw, int tid)
+{
+    if constexpr (NS_LOG < LOGR) {
+        constexpr int rem = LOGR - NS_LOG;
+        constexpr int RL = rem == 1 ? 1 : (rem % 3 == 0 ? 3 : 2);
+        fft_stage_1024<LOGR, LOGT, NT, INV, NS_LOG, RL>(d, tw, tid);
+        run_fft_1024<LOGR, LOGT, NT, INV, NS_LOG + RL>(d, tw, tid);
+    }
+}
+
+// ------------------------------------------------------------ forward ----
+// One member's walk over its team's turns.  FAST: every chunk this member reads lies wholly inside a 16-byte aligned
+// input (no guards on the loads).
+template <int LOGN1, int LOGN2, bool FAST>
+__device__ __forceinline__ void fused_fwd_run(const float* __restrict__ in, size_t n, uint32_t C, int aligned,
+                                              float2* __restrict__ scratch, float2* __restrict__ spec, uint32_t sstride,
+                                              const Tables& tb, uint32_t* __restrict__ hist, uint32_t x, uint32_t team,
+                                              uint32_t nteams, uint32_t mi, uint32_t members, const TeamCtl& tc, float2* d,
+                                              const float2* tw, uint32_t* h16, uint32_t* s_ok, int tid0)
+{
+    constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
+    constexpr int logM = LOGN1 + LOGN2;
+    constexpr uint32_t M = 1u << logM, N1 = 1u << LOGN1, N2 = 1u << LOGN2;
+    constexpr int LOGG = logM - LOGE;               // log2 of the tiles per chunk and pass
+    static_assert(LOGG >= 1 && LOGG <= 6, "a turn holds whole chunks");
+    constexpr uint32_t G = 1u << LOGG, CPR = (uint32_t)kTurnTiles >> LOGG;  // chunks per turn
+    // pass A geometry (tile = TA adjacent columns, all N1 rows)
+    constexpr int LOGTA = LOGE - LOGN1, TA = 1 << LOGTA;
+    constexpr int HP = N1 / 2, LOGHP = LOGN1 - 1;
+    static_assert(LOGTA >= 2 && (NT % (TA / 2)) == 0, "pass A tile shape");
+    constexpr int KN = HP >= NT ? HP / NT : 1;
+    constexpr int DC = HP >= NT ? 1 : NT / HP;
+    constexpr int NCOL = PER2 / KN;
+    static_assert(NCOL <= 8, "twiddle recurrence is anchored once");
+    static_assert(PER2 == 8 && (NT >> (LOGTA - 1)) == N1 / 8, "a lane's loads are the inputs of two radix-8 butterflies");
+    // pass B geometry (tile = P row pairs, all N2 columns)
+    constexpr int LOGTB = LOGE - LOGN2, LOGP = LOGTB - 1, P = 1 << LOGP;
+    static_assert(LOGTB >= 1 && NT % P == 0, "a lane keeps one slot pair");
+    constexpr int DK = NT >> LOGP;
+    static_assert(DK == (int)N2 / 8, "a lane's loads are the inputs of two radix-8 butterflies");
+    static_assert(2 * kSplitStep * (PER2 - 1) < 16, "split twiddle steps stay inside the 32nd-root table");
+    constexpr int BATCH = 4;
+
+    const uint32_t tpm = (uint32_t)kTurnTiles / members;  // tiles per member, pass and turn
+    const uint32_t groups = (C + CPR - 1) / CPR;          // turns of the whole call
+    if (groups <= x) return;                              // this XCD has nothing to do (nobody waits for it)
+    const uint32_t turns = (groups - x + (uint32_t)kXcds - 1) / (uint32_t)kXcds;
+
+    // tile i of this member in turn u: chunk, its slot in the scratch region, tile index inside the chunk
+    auto tile_of = [&](uint32_t u, uint32_t i, uint32_t& c, uint32_t& slot, uint32_t& tl) {
+        const uint32_t q = mi * tpm + i;
+        slot = q >> LOGG;
+        tl = q & (G - 1u);
+        c = (u * (uint32_t)kXcds + x) * CPR + slot;
+        return c < C;
+    };
+
+    float4 r[PER2];
+    // ---- pass A pieces ----
+    auto load_a = [&](uint32_t u, uint32_t i, int tid, bool live) {
+        uint32_t c, slot, tl;
+        const bool ok = tile_of(u, i, c, slot, tl) && live;
+        const uint32_t col0 = tl << LOGTA;
+        if constexpr (FAST) {
+            // a tile that does not exist still issues its loads, all to one valid address
+            const float4* src = ok ? reinterpret_cast<const float4*>(in + (size_t)c * (2 * (size_t)M)) + (col0 >> 1)
+                                   : reinterpret_cast<const float4*>(tb.hi);
+#pragma unroll
+            for (int q = 0; q < PER2; ++q) {
+                const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
+                r[q] = src[ok ? (uint32_t)n1 * (N2 >> 1) + bp : 0u];
+            }
+        } else {
+            if (!ok) return;
+            const size_t first = (size_t)c * (2 * (size_t)M);
+#pragma unroll
+            for (int q = 0; q < PER2; ++q) {
+                const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
+                const size_t gi = first + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
+                r[q] = join(load_pair(in, gi, n, aligned & 1), load_pair(in, gi + 2, n, aligned & 1));
+            }
+        }
+    };
+    auto fill_a = [&](int tid) { first_stage_store<LOGTA, false>(d, tid >> (LOGTA - 1), 2 * (tid & (TA / 2 - 1)), r); };
+
+    // ---- pass B pieces ----
+    auto load_b = [&](uint32_t slot, uint32_t tl, int tid) {
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        const float4* src = reinterpret_cast<const float4*>(scratch + (size_t)slot * M);
+        const uint32_t pp = tl * P + p;
+#pragma unroll
+        for (int q = 0; q < PER2; ++q) r[q] = ld_l2(src + (uint32_t)(kq0 + q * DK) * (N1 >> 1) + pp);
+    };
+    auto fill_b = [&](int tid) {
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        first_stage_store<LOGTB, false>(d, kq0, 2 * p, r);
+    };
+    auto count = [&](float2 v, bool on) {
+        const uint32_t b = fft_key_of(v) >> kKeyShift;
+        atomicAdd(&h16[b >> 1], on ? 1u << ((b & 1u) * 16u) : 0u);
+    };
+
+    // the first turn's first tile
+    load_a(team, 0, tid0, true);
+    for (uint32_t u = team; u < turns; u += nteams) {
+        uint32_t c = 0, slot = 0, tl = 0;
+        // ================= pass A =================
+        for (uint32_t i = 0; i < tpm; ++i) {
+            const int tid = opaque_lane(tid0);
+            const bool valid = tile_of(u, i, c, slot, tl);
+            if (valid) fill_a(tid);
+            __syncthreads();
+            const uint32_t col0 = tl << LOGTA;
+            constexpr int sh = 22 - logM;
+            float2 ratio_a[KN], ratio_b[KN], cur_a[KN], cur_b[KN];
+#pragma unroll
+            for (int kk = 0; kk < KN; ++kk) {
+                const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
+                const uint32_t ka = kp, kb = mirror_row(kp, N1);
+                const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
+                ratio_a[kk] = twiddle(tb, ((uint32_t)DC * ka) << sh);
+                ratio_b[kk] = twiddle(tb, ((uint32_t)DC * kb) << sh);
+                cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
+                cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
+            }
+            if (i + 1 < tpm) load_a(u, i + 1, tid, true);
+            if (valid) run_fft_1024<LOGN1, LOGTA, NT, false, 3>(d, tw, tid);
+            // the region is free once every member of the previous turn has taken its tiles out of it
+            if (i == 0 && !team_wait(tc.loaded, members * u, tc, s_ok)) return;
+            if (valid) {
+                float4* out = reinterpret_cast<float4*>(scratch + (size_t)slot * M);
+#pragma unroll
+                for (int kk = 0; kk < KN; ++kk) {
+                    const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
+                    const uint32_t ka = kp, kb = mirror_row(kp, N1);
+                    const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
+#pragma unroll
+                    for (int j = 0; j < NCOL; ++j) {
+                        const uint32_t col = cfirst + j * DC, n2 = col0 + col;
+                        const float2 va = cmul(d[sw_idx<LOGTA>((int)ka, (int)col)], cur_a[kk]);
+                        const float2 vb = cmul(d[sw_idx<LOGTA>((int)kb, (int)col)], cur_b[kk]);
+                        out[n2 * (uint32_t)HP + kp] = join(va, vb);
+                        cur_a[kk] = cmul(cur_a[kk], ratio_a[kk]);
+                        cur_b[kk] = cmul(cur_b[kk], ratio_b[kk]);
+                    }
+                }
+            }
+            __syncthreads();  // the tile has left LDS
+        }
+        team_arrive_after_stores(tc.stored);
+        // ================= pass B =================
+        if (!team_wait(tc.stored, members * (u + 1u), tc, s_ok)) return;
+        bool valid = tile_of(u, 0, c, slot, tl);
+        if (valid) load_b(slot, tl, opaque_lane(tid0));
+        for (uint32_t i = 0; i < tpm; ++i) {
+            const int tid = opaque_lane(tid0);
+            valid = tile_of(u, i, c, slot, tl);
+            if (valid) fill_b(tid);
+            __syncthreads();
+            const int p = tid & (P - 1), kq0 = tid >> LOGP;
+            const uint32_t pp = tl * P + p;
+            const uint32_t ka = pp, kb = mirror_row(pp, N1);
+            const bool self = pp == 0;
+            const float2 base_a = twiddle(tb, (ka + ((uint32_t)kq0 << LOGN1)) << (21 - logM));
+            const float2 base_b = twiddle(tb, (kb + ((uint32_t)kq0 << LOGN1)) << (21 - logM));
+            if (i + 1 < tpm) {
+                uint32_t c2, slot2, tl2;
+                if (tile_of(u, i + 1, c2, slot2, tl2)) load_b(slot2, tl2, tid);
+            } else {
+                // every lane has its last tile of the turn in LDS: the region may be overwritten
+                if (tid0 == 0) __hip_atomic_fetch_add(tc.loaded, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                load_a(u + nteams, 0, tid, u + nteams < turns);
+            }
+            if (valid) {
+                run_fft_1024<LOGN2, LOGTB, NT, false, 3>(d, tw, tid);
+                float2* out = spec + (size_t)c * (size_t)sstride;
+#pragma unroll
+                for (int q0 = 0; q0 < PER2; q0 += BATCH) {
+                    float2 a0[BATCH], a1[BATCH], pa[BATCH], pb[BATCH];
+#pragma unroll
+                    for (int v = 0; v < BATCH; ++v) {
+                        const int k2 = kq0 + (q0 + v) * DK, k2p = (int)N2 - 1 - k2;
+                        const int ia = self ? sw_idx<LOGTB>(((int)N2 - k2) & ((int)N2 - 1), 2 * p) : sw_idx<LOGTB>(k2p, 2 * p + 1);
+                        const int ib = self ? sw_idx<LOGTB>(k2p, 2 * p + 1) : sw_idx<LOGTB>(k2p, 2 * p);
+                        a0[v] = d[sw_idx<LOGTB>(k2, 2 * p)];
+                        a1[v] = d[sw_idx<LOGTB>(k2, 2 * p + 1)];
+                        pa[v] = d[ia];
+                        pb[v] = d[ib];
+                    }
+#pragma unroll
+                    for (int v = 0; v < BATCH; ++v) {
+                        const int q = q0 + v, k2 = kq0 + q * DK;
+                        const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
+                        float2 xa = split_fwd(a0[v], pa[v], cmul(base_a, wq));
+                        const float2 xb = split_fwd(a1[v], pb[v], cmul(base_b, wq));
+                        if (q == 0) {  // k2 = 0 only here: bin 0 and the Nyquist bin come from Z[0] alone
+                            const bool dc = self && kq0 == 0;
+                            const float2 xm = make_float2(a0[v].x - a0[v].y, 0.f);
+                            if (dc) {
+                                xa = make_float2(a0[v].x + a0[v].y, 0.f);
+                                out[M] = xm;
+                            }
+                            count(xm, dc);
+                        }
+                        reinterpret_cast<float4*>(out)[((uint32_t)k2 << (LOGN1 - 1)) + pp] = join(xa, xb);
+                        count(xa, true);
+                        count(xb, true);
+                    }
+                }
+            }
+            __syncthreads();  // the tile has left LDS; the LDS histogram is complete for it
+        }
+        // a member's tiles of one turn lie in one chunk: flush its keys' first digits
+        if (tile_of(u, 0, c, slot, tl)) {
+            uint32_t* g = hist + (size_t)c * kHistBins;
+            for (int i = tid0; i < kHistLdsWords; i += NT) {
+                const uint32_t v = h16[i];
+                if (v) {
+                    if (v & 0xFFFFu) atomicAdd(&g[2 * i], v & 0xFFFFu);
+                    if (v >> 16) atomicAdd(&g[2 * i + 1], v >> 16);
+                    h16[i] = 0u;
+                }
+            }
+        }
+        // (the next turn's first LDS write is behind a barrier of its own loop)
+    }
+}
+
+// Control words (u32 index into the workspace's control block; kCtlGaveUpWord is shared with the host code).
+constexpr int kCtlGaveUp = kCtlGaveUpWord;
+constexpr int kCtlXcc = 32;      // + x: XCD claimed by team slot x, plus one
+constexpr int kCtlStored = 128;  // + 64 x
+constexpr int kCtlLoaded = 160;  // + 64 x
+
+// split_log: which bit of the in-XCD workgroup index y = blockIdx / 8 picks the team when there are two
+// (0: y & 1, 5: y >> 5).
+template <int LOGN1, int LOGN2>
+__global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_fused_fwd(const float* __restrict__ in, size_t n, uint32_t C, int aligned,
+                                                   float2* __restrict__ scratch_all, float2* __restrict__ spec,
+                                                   uint32_t sstride, Tables tb, uint32_t* __restrict__ hist,
+                                                   uint32_t* __restrict__ ctl, uint32_t nteams, int split_log,
+                                                   uint32_t spin_limit)
+{
+    extern __shared__ float2 smem[];
+    float2* d = smem;
+    float2* tw = smem + (1 << kLogE);
+    uint32_t* h16 = reinterpret_cast<uint32_t*>(tw + kTwEntries);
+    uint32_t* s_ok = h16 + kHistLdsWords;
+    const int tid0 = threadIdx.x;
+    const uint32_t x = blockIdx.x & (kXcds - 1u), y = blockIdx.x >> 3;
+    const uint32_t members = (uint32_t)kXcdWgs / nteams;
+    uint32_t team = 0, mi = y;
+    if (nteams == 2) {
+        team = (y >> split_log) & 1u;
+        const uint32_t lowmask = (1u << split_log) - 1u;
+        mi = ((y >> (split_log + 1)) << split_log) | (y & lowmask);
+    }
+    TeamCtl tc;
+    tc.stored = ctl + kCtlStored + 64 * x;
+    tc.loaded = ctl + kCtlLoaded + 64 * x;
+    tc.gave_up = ctl + kCtlGaveUp;
+    tc.spin_limit = spin_limit;
+    if (tid0 == 0) {
+        // all members of a team slot must sit behind one L2: the first to arrive claims the XCD for the slot
+        const uint32_t me = xcc_id() + 1u;
+        const uint32_t prev = atomicCAS(ctl + kCtlXcc + x, 0u, me);
+        if (prev != 0u && prev != me) {
+            __hip_atomic_store(tc.gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");  // before this workgroup counts as arrived anywhere
+        }
+    }
+    load_shared_twiddles<kNT>(tw, tb, tid0);
+    for (int i = tid0; i < kHistLdsWords; i += kNT) h16[i] = 0u;
+    float2* scratch = scratch_all + (size_t)x * ((size_t)kTurnTiles << kLogE);
+    // only the gradient's last chunk can be ragged; the team that transforms it loads under guards
+    constexpr int LOGG = LOGN1 + LOGN2 - kLogE;
+    constexpr uint32_t CPR = (uint32_t)kTurnTiles >> LOGG;
+    const uint32_t last_group = (C - 1u) / CPR;
+    const bool ragged = ((size_t)C << (LOGN1 + LOGN2 + 1)) != n;
+    const bool mine = (last_group % (uint32_t)kXcds) == x && ((last_group / (uint32_t)kXcds) % nteams) == team;
+    const bool fast = (aligned & 2) != 0 && !(ragged && mine);
+    __syncthreads();
+    if (fast)
+        fused_fwd_run<LOGN1, LOGN2, true>(in, n, C, aligned, scratch, spec, sstride, tb, hist, x, team, nteams, mi,
+                                          members, tc, d, tw, h16, s_ok, tid0);
+    else
+        fused_fwd_run<LOGN1, LOGN2, false>(in, n, C, aligned, scratch, spec, sstride, tb, hist, x, team, nteams, mi,
+                                           members, tc, d, tw, h16, s_ok, tid0);
+}
+
+// ------------------------------------------------------------ inverse ----
+// The receiver's two passes in the same scheme: the split and the inverse N2-point transforms of a tile of row
+// pairs (read from the decoded spectrum, stored into the team's scratch region), hand-over, then the inverse
+// N1-point transforms of a tile of columns (loaded from the region past the L1, stored as real samples).
+template <int LOGN1, int LOGN2>
+__device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, uint32_t sstride, size_t n, uint32_t C,
+                                              int aligned, float gain, float2* __restrict__ scratch,
+                                              float* __restrict__ out, const Tables& tb, uint32_t x, uint32_t team,
+                                              uint32_t nteams, uint32_t mi, uint32_t members, const TeamCtl& tc, float2* d,
+                                              const float2* tw, uint32_t* s_ok, int tid0)
+{
+    constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
+    constexpr int logM = LOGN1 + LOGN2;
+    constexpr uint32_t M = 1u << logM, N1 = 1u << LOGN1, N2 = 1u << LOGN2;
+    constexpr int LOGG = logM - LOGE;
+    static_assert(LOGG >= 1 && LOGG <= 6, "a turn holds whole chunks");
+    constexpr uint32_t G = 1u << LOGG, CPR = (uint32_t)kTurnTiles >> LOGG;
+    // pass over k2 (tile = P row pairs, all N2 columns)
+    constexpr int LOGTB = LOGE - LOGN2, LOGP = LOGTB - 1, P = 1 << LOGP;
+    static_assert(LOGTB >= 1 && NT % P == 0, "a lane keeps one slot pair");
+    constexpr int DK = NT >> LOGP;
+    static_assert(PER2 == 8 && DK == (int)N2 / 8, "a lane's values are the inputs of two radix-8 butterflies");
+    // pass over k1 (tile = TA adjacent columns, all N1 rows)
+    constexpr int LOGTA = LOGE - LOGN1, TA = 1 << LOGTA;
+    constexpr int HP = N1 / 2, LOGHP = LOGN1 - 1;
+    static_assert(LOGTA >= 2 && (NT % (TA / 2)) == 0, "tile shape");
+
+    const uint32_t tpm = (uint32_t)kTurnTiles / members;
+    const uint32_t groups = (C + CPR - 1) / CPR;
+    if (groups <= x) return;
+    const uint32_t turns = (groups - x + (uint32_t)kXcds - 1) / (uint32_t)kXcds;
+    const float scale = gain * (1.0f / (float)(2u * M));
+
+    auto tile_of = [&](uint32_t u, uint32_t i, uint32_t& c, uint32_t& slot, uint32_t& tl) {
+        const uint32_t q = mi * tpm + i;
+        slot = q >> LOGG;
+        tl = q & (G - 1u);
+        c = (u * (uint32_t)kXcds + x) * CPR + slot;
+        return c < C;
+    };
+
+    float4 r[PER2];
+    float2 xnyq = make_float2(0.f, 0.f);  // Nyquist bin of the chunk of the spectrum tile held in r
+    float2 base_a = make_float2(1.f, 0.f), base_b = make_float2(1.f, 0.f);  // split twiddles of that tile
+    // a tile that does not exist still issues its loads, all to one valid address
+    auto load_spec = [&](uint32_t u, uint32_t i, int tid, bool live) {
+        uint32_t c, slot, tl;
+        const bool ok = tile_of(u, i, c, slot, tl) && live;
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        const float2* X = ok ? spec + (size_t)c * (size_t)sstride : reinterpret_cast<const float2*>(tb.hi);
+        const uint32_t pp = tl * P + p;
+        const uint32_t ka = pp, kb = mirror_row(pp, N1);
+        base_a = twiddle(tb, (ka + ((uint32_t)kq0 << LOGN1)) << (21 - logM));
+        base_b = twiddle(tb, (kb + ((uint32_t)kq0 << LOGN1)) << (21 - logM));
+        const float4* X4 = reinterpret_cast<const float4*>(X);
+#pragma unroll
+        for (int q = 0; q < PER2; ++q) r[q] = X4[ok ? ((uint32_t)(kq0 + q * DK) << (LOGN1 - 1)) + pp : 0u];
+        xnyq = X[ok ? M : 0u];
+    };
+    auto load_mid = [&](uint32_t slot, uint32_t tl, int tid) {
+        const float4* src = reinterpret_cast<const float4*>(scratch + (size_t)slot * M);
+        const uint32_t col0 = tl << LOGTA;
+#pragma unroll
+        for (int q = 0; q < PER2; ++q) {
+            const int w = tid + q * NT, kp = w & (HP - 1), col = w >> LOGHP;
+            r[q] = ld_l2(src + (uint32_t)(col0 + col) * HP + kp);
+        }
+    };
+
+    load_spec(team, 0, tid0, true);
+    for (uint32_t u = team; u < turns; u += nteams) {
+        uint32_t c = 0, slot = 0, tl = 0;
+        // ================= split + inverse transforms over k2 =================
+        for (uint32_t i = 0; i < tpm; ++i) {
+            const int tid = opaque_lane(tid0);
+            // a tile past the last chunk (last turn of a call whose chunks do not fill it) is transformed like any
+            // other: its loads read one valid dummy address, its stores land in the region or are dropped by the
+            // output guards, so the loop needs no branches around the arithmetic
+            (void)tile_of(u, i, c, slot, tl);
+            const int p = tid & (P - 1), kq0 = tid >> LOGP;
+            const uint32_t pp = tl * P + p;
+            const uint32_t ka = pp, kb = mirror_row(pp, N1);
+            const bool self = pp == 0;
+#pragma unroll
+            for (int q = 0; q < PER2; ++q) lds_store2<LOGTB>(d, kq0 + q * DK, 2 * p, r[q]);
+            __syncthreads();
+            float4 z[PER2];
+            {
+                // partners of all pairs first (one batch of LDS reads), then the arithmetic
+                float2 pa[PER2], pb[PER2];
+#pragma unroll
+                for (int q = 0; q < PER2; ++q) {
+                    const int k2 = kq0 + q * DK, k2p = (int)N2 - 1 - k2;
+                    const int ia = self ? sw_idx<LOGTB>(((int)N2 - k2) & ((int)N2 - 1), 2 * p) : sw_idx<LOGTB>(k2p, 2 * p + 1);
+                    const int ib = self ? sw_idx<LOGTB>(k2p, 2 * p + 1) : sw_idx<LOGTB>(k2p, 2 * p);
+                    pa[q] = d[ia];
+                    pb[q] = d[ib];
+                }
+#pragma unroll
+                for (int q = 0; q < PER2; ++q) {
+                    const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
+                    float2 a0 = lo2(r[q]), b0 = pa[q];
+                    if (q == 0) {  // k2 = 0 only here; imaginary parts of the DC and Nyquist bins are ignored
+                        const bool dc = self && kq0 == 0;
+                        b0 = dc ? make_float2(xnyq.x, 0.f) : b0;
+                        a0.y = dc ? 0.f : a0.y;
+                    }
+                    z[q] = join(split_inv(a0, b0, cmul(base_a, wq)), split_inv(hi2(r[q]), pb[q], cmul(base_b, wq)));
+                }
+            }
+            __syncthreads();
+            first_stage_store<LOGTB, true>(d, kq0, 2 * p, z);
+            __syncthreads();
+            constexpr int sh = 22 - logM;
+            const float2 ratio_a = twiddle(tb, ((uint32_t)DK * ka) << sh);
+            const float2 ratio_b = twiddle(tb, ((uint32_t)DK * kb) << sh);
+            float2 cur_a = twiddle(tb, ((uint32_t)kq0 * ka) << sh);
+            float2 cur_b = twiddle(tb, ((uint32_t)kq0 * kb) << sh);
+            if (i + 1 < tpm) load_spec(u, i + 1, tid, true);
+            run_fft_1024<LOGN2, LOGTB, NT, true, 3>(d, tw, tid);
+            if (i == 0 && !team_wait(tc.loaded, members * u, tc, s_ok)) return;
+            {
+                float4* dst = reinterpret_cast<float4*>(scratch + (size_t)slot * M);
+#pragma unroll
+                for (int q = 0; q < PER2; ++q) {
+                    const uint32_t n2 = (uint32_t)(kq0 + q * DK);
+                    const float4 v = lds_load2<LOGTB>(d, (int)n2, 2 * p);
+                    dst[n2 * (N1 >> 1) + pp] = join(cmulc(lo2(v), cur_a), cmulc(hi2(v), cur_b));
+                    cur_a = cmul(cur_a, ratio_a);
+                    cur_b = cmul(cur_b, ratio_b);
+                }
+            }
+            __syncthreads();
+        }
+        team_arrive_after_stores(tc.stored);
+        // ================= inverse transforms over k1 =================
+        if (!team_wait(tc.stored, members * (u + 1u), tc, s_ok)) return;
+        (void)tile_of(u, 0, c, slot, tl);
+        load_mid(slot, tl, opaque_lane(tid0));
+        for (uint32_t i = 0; i < tpm; ++i) {
+            const int tid = opaque_lane(tid0);
+            (void)tile_of(u, i, c, slot, tl);
+#pragma unroll
+            for (int q = 0; q < PER2; ++q) {
+                const int w = tid + q * NT, kp = w & (HP - 1), col = w >> LOGHP;
+                d[sw_idx<LOGTA>(kp, col)] = lo2(r[q]);
+                d[sw_idx<LOGTA>((int)mirror_row((uint32_t)kp, N1), col)] = hi2(r[q]);
+            }
+            __syncthreads();
+            if (i + 1 < tpm) {
+                uint32_t c2, slot2, tl2;
+                (void)tile_of(u, i + 1, c2, slot2, tl2);
+                load_mid(slot2, tl2, tid);
+            } else {
+                if (tid0 == 0) __hip_atomic_fetch_add(tc.loaded, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                load_spec(u + nteams, 0, tid, u + nteams < turns);
+            }
+            {
+                run_fft_1024<LOGN1, LOGTA, NT, true, 0>(d, tw, tid);
+                // a chunk past the end starts beyond n: the guarded branch below then stores nothing
+                const size_t cbase = (size_t)c * (2 * (size_t)M);
+                const uint32_t col0 = tl << LOGTA;
+                if ((aligned & 2) && cbase + 2 * (size_t)M <= n) {  // whole chunk inside the output: no guards
+                    float4* dst = reinterpret_cast<float4*>(out + cbase) + (col0 >> 1);
+#pragma unroll
+                    for (int q = 0; q < PER2; ++q) {
+                        const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
+                        const float4 v = lds_load2<LOGTA>(d, n1, 2 * bp);
+                        dst[(uint32_t)n1 * (N2 >> 1) + bp] = make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < PER2; ++q) {
+                        const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
+                        const float4 v = lds_load2<LOGTA>(d, n1, 2 * bp);
+                        const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
+                        store_pair(out, gi, n, aligned & 1, make_float2(v.x * scale, v.y * scale));
+                        store_pair(out, gi + 2, n, aligned & 1, make_float2(v.z * scale, v.w * scale));
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+template <int LOGN1, int LOGN2>
+__global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_fused_inv(
+    const float2* __restrict__ spec, uint32_t sstride, size_t n, uint32_t C, int aligned, float gain,
+    float2* __restrict__ scratch_all, float* __restrict__ out, Tables tb, uint32_t* __restrict__ ctl, uint32_t nteams,
+    int split_log, uint32_t spin_limit)
+{
+    extern __shared__ float2 smem[];
+    float2* d = smem;
+    float2* tw = smem + (1 << kLogE);
+    uint32_t* s_ok = reinterpret_cast<uint32_t*>(tw + kTwEntries);
+    const int tid0 = threadIdx.x;
+    const uint32_t x = blockIdx.x & (kXcds - 1u), y = blockIdx.x >> 3;
+    const uint32_t members = (uint32_t)kXcdWgs / nteams;
+    uint32_t team = 0, mi = y;
+    if (nteams == 2) {
+        team = (y >> split_log) & 1u;
+        const uint32_t lowmask = (1u << split_log) - 1u;
+        mi = ((y >> (split_log + 1)) << split_log) | (y & lowmask);
+    }
+    TeamCtl tc;
+    tc.stored = ctl + kCtlStored + 64 * x;
+    tc.loaded = ctl + kCtlLoaded + 64 * x;
+    tc.gave_up = ctl + kCtlGaveUp;
+    tc.spin_limit = spin_limit;
+    if (tid0 == 0) {
+        const uint32_t me = xcc_id() + 1u;
+        const uint32_t prev = atomicCAS(ctl + kCtlXcc + x, 0u, me);
+        if (prev != 0u && prev != me) {
+            __hip_atomic_store(tc.gave_up, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        }
+    }
+    load_shared_twiddles<kNT>(tw, tb, tid0);
+    float2* scratch = scratch_all + (size_t)x * ((size_t)kTurnTiles << kLogE);
+    __syncthreads();
+    fused_inv_run<LOGN1, LOGN2>(spec, sstride, n, C, aligned, gain, scratch, out, tb, x, team, nteams, mi, members, tc, d,
+                                tw, s_ok, tid0);
+}
+
+}  // namespace
+
+FusedKnobs fused_knobs()
+{
+    FusedKnobs k;
+    k.enabled = 0;  // off until measured faster on the GPU
+    k.teams = 1;
+    k.split_log = 5;
+    k.spin_limit = 1u << 18;  // a poll takes about a microsecond: a quarter of a second before a wait gives up
+    if (const char* e = std::getenv("FFTSP_FUSED")) k.enabled = std::atoi(e) != 0;
+    if (const char* e = std::getenv("FFTSP_FUSED_TEAMS")) k.teams = std::atoi(e) == 2 ? 2 : 1;
+    if (const char* e = std::getenv("FFTSP_FUSED_SPLIT")) k.split_log = std::atoi(e) == 0 ? 0 : 5;
+    if (const char* e = std::getenv("FFTSP_FUSED_SPIN")) k.spin_limit = (uint32_t)std::strtoul(e, nullptr, 10);
+    return k;
+}
+
+// Which chunk lengths and counts take the fused kernels: two-pass lengths whose chunks fit a turn (2^15 .. 2^20
+// samples), and enough tiles that the team scratch (32 MiB) is no larger than the per-pass intermediate it replaces.
+bool fused_applies(int logL, size_t C)
+{
+    const int logM = logL - 1;
+    if (logM < 14 || logM > 19) return false;
+    return (C << (logM - kLogE)) >= (size_t)kXcds * kTurnTiles;
+}
+
+size_t fused_scratch_bytes() { return (size_t)kXcds * ((size_t)kTurnTiles << kLogE) * sizeof(float2); }
+
+hipError_t launch_fused_rfft(const float* in, size_t n, int logL, size_t C, float2* spec, uint32_t sstride,
+                             float2* scratch, Tables t, uint32_t* hist, uint32_t* ctl, const FusedKnobs& knobs,
+                             hipStream_t s)
+{
+    const int logM = logL - 1;
+    if (!fused_applies(logL, C) || C > 0x7fffffu) return hipErrorInvalidValue;
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(in);
+    const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
+    const int logN1 = (logM + 1) / 2;
+    const uint32_t nteams = knobs.teams == 2 ? 2u : 1u;
+    const int split_log = knobs.split_log == 0 ? 0 : 5;
+#define FFTSP_FUSED_FWD(a, b)                                                                                         \
+    do {                                                                                                              \
+        auto kern = k_fused_fwd<a, b>;                                                                                \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                       \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds);              \
+        if (e != hipSuccess) return e;                                                                                \
+        FFTSP_LAUNCH("rfft_fused", kern, dim3(kXcds * kXcdWgs), dim3(kNT), kFusedLds, s, in, n, (uint32_t)C, aligned, \
+                     scratch, spec, sstride, t, hist, ctl, nteams, split_log, knobs.spin_limit);                     \
+    } while (0)
+    switch (logM) {
+        case 14: FFTSP_FUSED_FWD(7, 7); break;
+        case 15: FFTSP_FUSED_FWD(8, 7); break;
+        case 16: FFTSP_FUSED_FWD(8, 8); break;
+        case 17: FFTSP_FUSED_FWD(9, 8); break;
+        case 18: FFTSP_FUSED_FWD(9, 9); break;
+        case 19: FFTSP_FUSED_FWD(10, 9); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef FFTSP_FUSED_FWD
+    (void)logN1;
+    return hipGetLastError();
+}
+
+// ctl: the control block, zero.  The decoded spectrum is the codec's own buffer (paired order).
+hipError_t launch_fused_irfft(const float2* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out,
+                              float2* scratch, Tables t, float gain, uint32_t* ctl, const FusedKnobs& knobs, hipStream_t s)
+{
+    const int logM = logL - 1;
+    if (!fused_applies(logL, C) || C > 0x7fffffu) return hipErrorInvalidValue;
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(out);
+    const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
+    const uint32_t nteams = knobs.teams == 2 ? 2u : 1u;
+    const int split_log = knobs.split_log == 0 ? 0 : 5;
+#define FFTSP_FUSED_INV(a, b)                                                                                            \
+    do {                                                                                                                 \
+        auto kern = k_fused_inv<a, b>;                                                                                   \
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),                                          \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds);                 \
+        if (e != hipSuccess) return e;                                                                                   \
+        FFTSP_LAUNCH("irfft_fused", kern, dim3(kXcds * kXcdWgs), dim3(kNT), kFusedLds, s, spec, sstride, n, (uint32_t)C, \
+                     aligned, gain, scratch, out, t, ctl, nteams, split_log, knobs.spin_limit);                         \
+    } while (0)
+    switch (logM) {
+        case 14: FFTSP_FUSED_INV(7, 7); break;
+        case 15: FFTSP_FUSED_INV(8, 7); break;
+        case 16: FFTSP_FUSED_INV(8, 8); break;
+        case 17: FFTSP_FUSED_INV(9, 8); break;
+        case 18: FFTSP_FUSED_INV(9, 9); break;
+        case 19: FFTSP_FUSED_INV(10, 9); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef FFTSP_FUSED_INV
+    return hipGetLastError();
+}
+
+}  // namespace fftsp

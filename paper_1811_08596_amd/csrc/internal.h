@@ -82,9 +82,13 @@ constexpr int kHistBits = 12;                 // first radix-select digit: top 1
 constexpr int kHistBins = 1 << kHistBits;
 constexpr int kKeyShift = 31 - kHistBits;     // bucket = key >> 19
 
+constexpr size_t kControlBytes = 4096;  // control block at the start of every workspace
+constexpr int kCtlGaveUpWord = 1;       // u32 index of the fused kernels' give-up word inside the control block
+
 // Where everything lives inside the caller's workspace (byte offsets, 256-aligned).
 struct Workspace {
-    size_t status;    // u32[64]   word 0 = device status
+    size_t status;    // u32[1024] control block: word 0 = device status, word 1 = "the fused transform gave up",
+                      //           from word 32 on the hand-over counters of the fused kernels (fused.hip)
     size_t hist;      // u32[C][kHistBins]         (directly after status: one fill zeroes both)
     size_t sel;       // u32[C][8]  bstar, need, tau, quota, pbase, vmax, -, decode verdict
     size_t tinfo;     // u32[C][Tn][4]  n_def, vmax_def, n_cand, -
@@ -152,7 +156,7 @@ static inline Workspace make_workspace(size_t C, uint32_t L, int time_domain = 0
     Workspace w;
     size_t B = codec_bins(L, time_domain), Tn = codec_tiles(L, time_domain), W = (B + 31) / 32;
     size_t off = 0;
-    w.status = off; off += 256;
+    w.status = off; off += kControlBytes;
     w.hist = off;   off = align256(off + C * kHistBins * 4);
     w.sel = off;    off = align256(off + C * 8 * 4);
     w.tinfo = off;  off = align256(off + C * Tn * 16);
@@ -206,14 +210,39 @@ hipError_t get_tables(Tables* out);
 // pair_spec != 0 asks the two-pass kernels to write the spectrum in paired order; *pair_log receives log2(N1)
 // if they did, 0 otherwise (single-workgroup sizes always write natural order).
 // tab != nullptr: per-tensor launch, chunk c is in[tab->goff[c] .. + tab->glen[c]) (n is not used)
+// only_if (optional, two-pass sizes): device word; the kernels return at once unless it is non-zero
 hipError_t launch_rfft(const float* in, size_t n, int logL, size_t C, float* spec, uint32_t sstride, float2* mid,
                        Tables t, uint32_t* hist, uint32_t* zero_ptr, size_t zero_words, int* hist_done, int pair_spec,
-                       int* pair_log, const ChunkTable* tab, hipStream_t s);
+                       int* pair_log, const ChunkTable* tab, hipStream_t s, const uint32_t* only_if = nullptr);
 // log2(N1) of the two-pass factorisation for chunk length 2^logL, 0 for single-workgroup sizes
 int fft_pair_log(int logL);
 // pair_spec != 0: the spectrum is in paired order (two-pass sizes only); the output is gain/L times the plain sum
 hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out, float2* mid,
-                        Tables t, int pair_spec, float gain, const ChunkTable* tab, hipStream_t s);
+                        Tables t, int pair_spec, float gain, const ChunkTable* tab, hipStream_t s,
+                        const uint32_t* only_if = nullptr);
+
+// Fused two-pass transforms whose intermediate stays in the L2 caches (fused.hip).  They need the control block
+// zeroed beforehand (launch_zero_control) and the per-pass kernels enqueued behind them with only_if = the give-up
+// word, which redo the transform if the fused kernel could not finish.
+struct FusedKnobs {
+    int enabled;          // 0: never take the fused kernels
+    int teams;            // teams per XCD: 1 or 2
+    int split_log;        // two teams: 0 = neighbouring workgroups alternate, 5 = first and second half
+    uint32_t spin_limit;  // polls before a hand-over wait gives up
+};
+FusedKnobs fused_knobs();  // defaults overridden by the FFTSP_FUSED* environment variables (read at every call)
+bool fused_applies(int logL, size_t C);
+size_t fused_scratch_bytes();
+// spec: the codec's own buffer (paired order); hist: u32[C][kHistBins], already zero; ctl: the control block, zero
+hipError_t launch_fused_rfft(const float* in, size_t n, int logL, size_t C, float2* spec, uint32_t sstride,
+                             float2* scratch, Tables t, uint32_t* hist, uint32_t* ctl, const FusedKnobs& knobs,
+                             hipStream_t s);
+// the receiver's transform: spec is the codec's own decoded spectrum (paired order); ctl: the control block, zero
+hipError_t launch_fused_irfft(const float2* spec, uint32_t sstride, size_t n, int logL, size_t C, float* out,
+                              float2* scratch, Tables t, float gain, uint32_t* ctl, const FusedKnobs& knobs,
+                              hipStream_t s);
+// zeroes the control block and the histograms behind it (one fill)
+hipError_t launch_zero_control(uint8_t* ws_base, const Workspace& w, size_t C, hipStream_t s);
 
 // Half-precision variant: chunk lengths of the two-pass FFT only (2^15 and up); spec and mid are the codec's own
 // buffers, read and written as binary16 pairs (sstride in complex values); the histogram is always produced.

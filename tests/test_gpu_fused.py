@@ -1,0 +1,93 @@
+"""The fused, cache-resident two-pass transforms (csrc/fused.hip) against the oracle and against the per-pass kernels.
+
+Calls with at least 512 tiles of 8192 points take the fused kernels; the small parity cases never do, so the
+cases here are sized for them: chunk lengths 2^15 .. 2^20, several turns per XCD, a ragged last chunk, a last
+turn that is only partly filled.  Parity with the oracle is the same contract as everywhere (tests/test_gpu_parity.py:
+spectra and reconstructions within 1e-5, bytes identical on the oracle's spectrum); on top of it the fused kernels
+must agree bit for bit with the per-pass kernels they replace, whatever the team layout, and also when a hand-over
+wait expires and the stand-by kernels redo the transform.
+"""
+import numpy as np
+import pytest
+
+from paper_1811_08596_amd import workloads
+from tests.gpu_harness import Device
+from tests.test_gpu_parity import full_parity
+
+pytestmark = pytest.mark.gpu
+
+GAVE_UP_WORD = 1  # u32 index inside the workspace's control block
+
+
+@pytest.fixture(scope="module")
+def dev():
+    return Device()
+
+
+def round_trip(dev, g, L, theta, bits):
+    """(packed bytes, reconstruction, give-up word after compress, after decompress)"""
+    t, f = dev.torch, dev.f
+    n = g.size
+    gd = dev.to_dev(g)
+    nb = f.packed_bytes(n, L, theta, bits)
+    ws = dev.ws_for(n, L, bits)
+    packed = t.full((nb,), 0xEE, dtype=t.uint8, device=dev.dev)
+    f.compress(gd, L, theta, bits, packed, ws)
+    dev.sync()
+    gave_c = int(ws[4 * GAVE_UP_WORD:4 * GAVE_UP_WORD + 4].view(t.int32).item())
+    out = t.full((n + 64,), 7.0, dtype=t.float32, device=dev.dev)
+    f.decompress(packed, nb, out[:n], L, theta, bits, ws)
+    assert f.device_status(ws) == 0
+    gave_d = int(ws[4 * GAVE_UP_WORD:4 * GAVE_UP_WORD + 4].view(t.int32).item())
+    assert (out[n:] == 7.0).all().item()
+    return packed.cpu().numpy(), out[:n].cpu().numpy(), gave_c, gave_d
+
+
+CASES = [
+    # (log2 L, chunks, samples missing from the last chunk)
+    (15, 257, 1234),   # 32 chunks per turn: 9 turns, the last one holds a single chunk
+    (16, 130, 5),
+    (17, 70, 99),
+    (18, 33, 70000),
+    (20, 9, 4321),     # one chunk per turn; XCD 0 takes two turns
+]
+
+
+@pytest.mark.parametrize("logL,C,tail", CASES)
+def test_fused_transforms_match_the_oracle(dev, ref, monkeypatch, logL, C, tail):
+    monkeypatch.setenv("FFTSP_FUSED", "1")
+    L = 1 << logL
+    g = workloads.small_mixed(C * L - tail, seed=logL)
+    full_parity(dev, ref, g, L, 0.5, 8, end_to_end=True)
+
+
+@pytest.mark.parametrize("logL,C,tail", CASES)
+def test_fused_equals_per_pass_bit_for_bit(dev, monkeypatch, logL, C, tail):
+    L = 1 << logL
+    g = workloads.small_mixed(C * L - tail, seed=100 + logL)
+    monkeypatch.setenv("FFTSP_FUSED", "0")
+    want_p, want_r, gc, gd = round_trip(dev, g, L, 0.3, 8)
+    assert gc != 1 and gd != 1                     # the word is not even written on this path
+    for teams, split in ((1, 5), (2, 5), (2, 0)):
+        monkeypatch.setenv("FFTSP_FUSED", "1")
+        monkeypatch.setenv("FFTSP_FUSED_TEAMS", str(teams))
+        monkeypatch.setenv("FFTSP_FUSED_SPLIT", str(split))
+        got_p, got_r, gc, gd = round_trip(dev, g, L, 0.3, 8)
+        assert gc == 0 and gd == 0, "the fused kernels gave up on an idle GPU"
+        assert np.array_equal(got_p, want_p), f"teams={teams} split={split}: packed bytes differ"
+        assert np.array_equal(got_r.view(np.uint32), want_r.view(np.uint32)), f"teams={teams} split={split}"
+
+
+def test_expired_wait_hands_over_to_the_stand_by_kernels(dev, monkeypatch):
+    """A spin limit of zero makes the first hand-over wait that is not already satisfied expire: every workgroup
+    leaves, the give-up word is set, and the per-pass kernels behind the fused one produce the result."""
+    L, C = 1 << 17, 70
+    g = workloads.small_mixed(C * L - 99, seed=7)
+    monkeypatch.setenv("FFTSP_FUSED", "0")
+    want_p, want_r, _, _ = round_trip(dev, g, L, 0.5, 8)
+    monkeypatch.setenv("FFTSP_FUSED", "1")
+    monkeypatch.setenv("FFTSP_FUSED_SPIN", "0")
+    got_p, got_r, gc, gd = round_trip(dev, g, L, 0.5, 8)
+    assert gc == 1 and gd == 1
+    assert np.array_equal(got_p, want_p)
+    assert np.array_equal(got_r.view(np.uint32), want_r.view(np.uint32))
