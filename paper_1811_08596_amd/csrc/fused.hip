@@ -54,6 +54,21 @@ __device__ __forceinline__ float4 ld_l2(const float4* p)
                        __uint_as_float((uint32_t)(b >> 32)));
 }
 
+// Streaming accesses for data that is touched once (gradient in, spectrum out): the non-temporal hint keeps them
+// from displacing the scratch region's lines in L2.
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld_stream(const float4* p)
+{
+    const floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void st_stream(float4* p, float4 v)
+{
+    floatx4 w;
+    w.x = v.x; w.y = v.y; w.z = v.z; w.w = v.w;
+    __builtin_nontemporal_store(w, reinterpret_cast<floatx4*>(p));
+}
+
 // XCD this wave runs on (hardware register XCC_ID, bits 3:0)
 __device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & 15u; }
 
@@ -210,7 +225,7 @@ __device__ __forceinline__ void fused_fwd_run(const float* __restrict__ in, size
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
                 const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
-                r[q] = src[ok ? (uint32_t)n1 * (N2 >> 1) + bp : 0u];
+                r[q] = ld_stream(src + (ok ? (uint32_t)n1 * (N2 >> 1) + bp : 0u));
             }
         } else {
             if (!ok) return;
@@ -344,7 +359,7 @@ __device__ __forceinline__ void fused_fwd_run(const float* __restrict__ in, size
                             }
                             count(xm, dc);
                         }
-                        reinterpret_cast<float4*>(out)[((uint32_t)k2 << (LOGN1 - 1)) + pp] = join(xa, xb);
+                        st_stream(reinterpret_cast<float4*>(out) + (((uint32_t)k2 << (LOGN1 - 1)) + pp), join(xa, xb));
                         count(xa, true);
                         count(xb, true);
                     }
@@ -486,7 +501,7 @@ __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, u
         base_b = twiddle(tb, (kb + ((uint32_t)kq0 << LOGN1)) << (21 - logM));
         const float4* X4 = reinterpret_cast<const float4*>(X);
 #pragma unroll
-        for (int q = 0; q < PER2; ++q) r[q] = X4[ok ? ((uint32_t)(kq0 + q * DK) << (LOGN1 - 1)) + pp : 0u];
+        for (int q = 0; q < PER2; ++q) r[q] = ld_stream(X4 + (ok ? ((uint32_t)(kq0 + q * DK) << (LOGN1 - 1)) + pp : 0u));
         xnyq = X[ok ? M : 0u];
     };
     auto load_mid = [&](uint32_t slot, uint32_t tl, int tid) {
@@ -598,7 +613,8 @@ __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, u
                     for (int q = 0; q < PER2; ++q) {
                         const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
                         const float4 v = lds_load2<LOGTA>(d, n1, 2 * bp);
-                        dst[(uint32_t)n1 * (N2 >> 1) + bp] = make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
+                        st_stream(dst + ((uint32_t)n1 * (N2 >> 1) + bp),
+                                  make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale));
                     }
                 } else {
 #pragma unroll
