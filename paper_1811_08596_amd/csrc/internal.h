@@ -94,6 +94,7 @@ struct Workspace {
     size_t tinfo;     // u32[C][Tn][4]  n_def, vmax_def, n_cand, -
     size_t tscan;     // u32[C][Tn][2]  first rank of the tile, equal-key count before the tile
     size_t cand;      // uint2[C][Tn*kTile]  (key, max component bits) of threshold-bucket bins, tile-ordered
+                      //                     (shares its bytes with mid)
     size_t prefix;    // u32[C][ceil(W/16)]  set bits before each group of 16 bitmap words (decode)
     size_t spec;      // float2[C][padded_bins(L)]  spectrum, each chunk on a 128-byte boundary
     size_t mid;       // float2[C][L/2] intermediate of the two-pass FFT
@@ -161,10 +162,13 @@ static inline Workspace make_workspace(size_t C, uint32_t L, int time_domain = 0
     w.sel = off;    off = align256(off + C * 8 * 4);
     w.tinfo = off;  off = align256(off + C * Tn * 16);
     w.tscan = off;  off = align256(off + C * Tn * 8);
-    w.cand = off;   off = align256(off + C * Tn * kTile * 8);
+    // The candidate list and the two-pass intermediate are never alive together (the sender's transform has
+    // finished before the first candidate is written; the receiver has no candidates): one region serves both.
+    const size_t cand_bytes = C * Tn * kTile * 8, mid_bytes = time_domain ? 0 : C * (size_t)L * 4;
+    w.cand = off;
+    w.mid = off;    off = align256(off + (cand_bytes > mid_bytes ? cand_bytes : mid_bytes));
     w.prefix = off; off = align256(off + C * W * 4);
     w.spec = off;   off = align256(off + (time_domain ? 0 : C * (size_t)padded_bins(L) * 8));
-    w.mid = off;    off = align256(off + (time_domain ? 0 : C * (size_t)L * 4));
     w.total = off;
     return w;
 }

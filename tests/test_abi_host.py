@@ -57,7 +57,7 @@ def test_host_arithmetic_matches_oracle(lib, ref):
 def test_headline_sizes(lib):
     n = 62378344
     assert fftsp.packed_bytes(n, 1 << 20, 0.5, 8) == 64 + 60 * (-(-(16 + 4 * 16385 + 4 * (2 * 262145 * 8 // 32 + 1)) // 16) * 16)
-    assert 0 < fftsp.workspace_bytes(n, 1 << 20, 8) < 4 * (1 << 30)
+    assert 0 < fftsp.workspace_bytes(n, 1 << 20, 8) <= 550 * 1000 * 1000   # 2.2 x the gradient
 
 
 def test_argument_errors_come_back_before_any_launch(lib):
@@ -123,7 +123,7 @@ def test_topk_host_arithmetic_and_argument_errors(lib, ref):
                     assert fftsp.topk_packed_bytes(n, L, theta, bits) == ref.topk_packed_bytes(n, L, theta, bits)
     # the time-domain workspace holds no spectrum and no FFT intermediate
     n, L = 1 << 22, 1 << 20
-    assert 0 < fftsp.topk_workspace_bytes(n, L, 8) < fftsp.workspace_bytes(n, L, 8)
+    assert 0 < fftsp.topk_workspace_bytes(n, L, 8) < 8.5 * n      # candidate list (8 bytes per sample) and little else
     a = 4096
     call = lambda **kw: lib.fftsp_topk_compress(kw.get("g", a), kw.get("n", 100), kw.get("L", 64), kw.get("theta", 0.5),
                                                 kw.get("bits", 8), kw.get("p", a), kw.get("cap", 1 << 20),

@@ -57,7 +57,7 @@ def test_config3_all_chunks(dev, ref, alexnet):
             e_gpu, e_or = rel_l2(rec, g), rel_l2(out_or, g)
             print(f"config3 theta=.5: selection mismatches {sel}, code mismatches {codes}, "
                   f"alpha gpu {e_gpu:.6f} oracle {e_or:.6f}", flush=True)
-            assert abs(e_gpu - e_or) <= 1e-3 * e_or + 5e-3 * (sel > 0)
+            assert abs(e_gpu - e_or) <= 1e-3 * e_or
     # other code widths at full size: the decoder fetches 1, 2 or 4 sixteen-byte pieces per lane depending on the width,
     # and only here does a decoding workgroup walk several tiles
     for wide in (5, 12, 32):
@@ -130,8 +130,10 @@ def test_config4_segments(dev, ref):
         assert rel_l2(a, b) <= TOL or not b.any()
 
 
-@pytest.mark.parametrize("iteration", [0, 9])
+@pytest.mark.parametrize("iteration", list(range(10)))
 def test_config5_sampled_chunks(dev, ref, iteration):
+    """Every step of the ten-step kept-fraction schedule (Sec. 3.4, Theorem 2: theta changes from call to call), a
+    fresh draw each; the oracle checks three chunks per step: two that move with the step and the ragged last one."""
     w = workloads.config5(iteration)
     g, L, bits, theta = w.grad, w.chunk_len, w.bits, w.theta
     n = g.size
@@ -144,7 +146,7 @@ def test_config5_sampled_chunks(dev, ref, iteration):
     h = ref.parse_header(packed)
     S = h["S"]
     assert (h["n"], h["L"], h["C"], h["k"]) == (n, L, C, ref.kept_per_chunk(L, theta))
-    for c in (0, 17, C - 1):
+    for c in (iteration, 11 + 2 * iteration, C - 1):
         print(f"config5[{iteration}]: oracle on chunk {c}", flush=True)
         gc = g[c * L:(c + 1) * L]
         spec_or = ref.rfft(gc, L)

@@ -1,5 +1,5 @@
-"""The library's calls enqueue kernels only (no allocation, no memset, no host synchronisation after the first call
-on a device), so a caller can record them into a HIP graph.  A graph is replayed several times with eager work and
+"""The library's calls enqueue kernels only (no allocation, no memset, no host synchronisation, from the first call
+on: the twiddle tables are constants in the code object), so a caller can record them into a HIP graph.  A graph is replayed several times with eager work and
 synchronisations in between, and every replay is checked against the eager result."""
 import numpy as np
 import pytest
@@ -31,7 +31,7 @@ def test_per_tensor_round_trip_replays_from_a_graph(dev):
         f.compress_segments(g, offs, theta, bits, packed, ws)
         f.decompress_segments(packed, nb, out, offs, theta, bits, ws)
 
-    step()                                                 # first call on the device builds the twiddle tables
+    step()                                                 # the per-tensor path creates its side streams on first use
     torch.cuda.synchronize()
     want_packed, want_out = packed.clone(), out.clone()
     graph = torch.cuda.CUDAGraph()
@@ -104,3 +104,59 @@ def test_uniform_round_trip_replays_from_a_graph(dev, ref):
     assert st == 0
     want = ref.decompress(por, n, L, theta, bits, nthreads=8)
     assert np.linalg.norm(back - want) <= 1e-5 * np.linalg.norm(want)
+
+
+FIRST_CALL_SCRIPT = r"""
+import sys
+import numpy as np
+import torch
+sys.path.insert(0, sys.argv[1])
+from paper_1811_08596_amd import fftsp, workloads
+fftsp.load()
+dev = torch.device("cuda:0")
+L, theta, bits = 1 << 15, 0.4, 8
+n = 14 * L - 5
+nb = fftsp.packed_bytes(n, L, theta, bits)
+ws = torch.full((fftsp.workspace_bytes(n, L, bits),), 0xFF, dtype=torch.uint8, device=dev)
+g0 = workloads.small_mixed(n, seed=8)
+g = torch.from_numpy(g0).to(dev)
+packed = torch.zeros(nb, dtype=torch.uint8, device=dev)
+out = torch.zeros(n, dtype=torch.float32, device=dev)
+torch.cuda.synchronize()
+graph = torch.cuda.CUDAGraph()
+side = torch.cuda.Stream()
+side.wait_stream(torch.cuda.current_stream())
+with torch.cuda.stream(side):
+    with torch.cuda.graph(graph, stream=side):
+        # the first calls into the library in this process
+        fftsp.compress(g, L, theta, bits, packed, ws, side)
+        fftsp.decompress(packed, nb, out, L, theta, bits, ws, side)
+torch.cuda.synchronize()
+for replay in range(3):
+    g.copy_(torch.from_numpy(g0 * np.float32(1.0 + 0.25 * replay)).to(dev))
+    packed.fill_(0xEE)
+    out.fill_(float("nan"))
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    got_p, got_o = packed.clone(), out.clone()
+    fftsp.compress(g, L, theta, bits, packed, ws)
+    fftsp.decompress(packed, nb, out, L, theta, bits, ws)
+    assert fftsp.device_status(ws) == 0
+    assert torch.equal(got_p, packed), replay
+    assert torch.equal(got_o.view(torch.int32), out.view(torch.int32)), replay
+print("FIRST_CALL_CAPTURE_OK")
+"""
+
+
+def test_first_library_call_of_a_process_may_sit_inside_a_capture(tmp_path):
+    """A fresh process records its very first compress + decompress into a graph (nothing is allocated, copied or
+    filled on first use), replays it on new inputs and compares each replay with eager calls."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    script = tmp_path / "first_call.py"
+    script.write_text(FIRST_CALL_SCRIPT)
+    r = subprocess.run([sys.executable, str(script), root], capture_output=True, text=True, timeout=170)
+    assert r.returncode == 0 and "FIRST_CALL_CAPTURE_OK" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
