@@ -86,12 +86,57 @@ __device__ __forceinline__ void bf8(float2* v)
     }
 }
 
+// 16 points: four radix-4 butterflies over n1 (elements n0, n0+4, n0+8, n0+12), the inner twiddles W16^(n0 k0),
+// four radix-4 butterflies over n0; output k = k0 + 4 k1.  One LDS round trip where two radix-4 stages take two.
+template <bool INV>
+__device__ __forceinline__ void bf16(float2* v)
+{
+    const float c1 = 0.92387953251128674f, s1 = 0.38268343236508977f, h = 0.70710678118654752440f;
+    float2 y[4][4];  // y[n0][k0]
+#pragma unroll
+    for (int n0 = 0; n0 < 4; ++n0) {
+        float2 t[4] = {v[n0], v[n0 + 4], v[n0 + 8], v[n0 + 12]};
+        bf4<INV>(t);
+#pragma unroll
+        for (int k0 = 0; k0 < 4; ++k0) y[n0][k0] = t[k0];
+    }
+    // W16^m = (cos(m pi/8), -sin(m pi/8)), conjugated for the inverse
+    auto rot = [](float2 a, float wr, float wi) {  // a * (wr + i wi) forward, a * (wr - i wi) inverse
+        return INV ? make_float2(a.x * wr + a.y * wi, a.y * wr - a.x * wi)
+                   : make_float2(a.x * wr - a.y * wi, a.y * wr + a.x * wi);
+    };
+    y[1][1] = rot(y[1][1], c1, -s1);   // W^1
+    y[1][2] = rot(y[1][2], h, -h);     // W^2
+    y[1][3] = rot(y[1][3], s1, -c1);   // W^3
+    y[2][1] = rot(y[2][1], h, -h);     // W^2
+    y[2][2] = rot90<INV>(y[2][2]);     // W^4 = -i
+    y[2][3] = rot(y[2][3], -h, -h);    // W^6
+    y[3][1] = rot(y[3][1], s1, -c1);   // W^3
+    y[3][2] = rot(y[3][2], -h, -h);    // W^6
+    y[3][3] = rot(y[3][3], -c1, s1);   // W^9
+#pragma unroll
+    for (int k0 = 0; k0 < 4; ++k0) {
+        float2 t[4] = {y[0][k0], y[1][k0], y[2][k0], y[3][k0]};
+        bf4<INV>(t);
+#pragma unroll
+        for (int k1 = 0; k1 < 4; ++k1) v[k0 + 4 * k1] = t[k1];
+    }
+}
+
 template <int RL, bool INV>
 __device__ __forceinline__ void butterfly(float2* v)
 {
     if constexpr (RL == 1) bf2<INV>(v);
     if constexpr (RL == 2) bf4<INV>(v);
     if constexpr (RL == 3) bf8<INV>(v);
+    if constexpr (RL == 4) bf16<INV>(v);
+}
+
+// log2 of the next stage's radix when `rem` binary stages remain: as few LDS round trips as a lane's sixteen
+// points allow (radix 16 where the count is not a multiple of three).
+__host__ __device__ constexpr int stage_radix_log(int rem)
+{
+    return rem <= 4 ? rem : (rem % 3 == 0 ? 3 : (rem == 5 ? 2 : 4));
 }
 
 // One Stockham stage of radix 2^RL on T = 2^LOGT interleaved R-point transforms.
@@ -134,8 +179,7 @@ template <int LOGR, int LOGT, int NT, bool INV, int NS_LOG = 0>
 __device__ __forceinline__ void run_fft(float2* d, const float2* tw, int tid)
 {
     if constexpr (NS_LOG < LOGR) {
-        constexpr int rem = LOGR - NS_LOG;
-        constexpr int RL = rem == 1 ? 1 : (rem % 3 == 0 ? 3 : 2);
+        constexpr int RL = stage_radix_log(LOGR - NS_LOG);
         fft_stage<LOGR, LOGT, NT, INV, NS_LOG, RL>(d, tw, tid);
         run_fft<LOGR, LOGT, NT, INV, NS_LOG + RL>(d, tw, tid);
     }

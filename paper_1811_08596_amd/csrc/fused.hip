@@ -33,8 +33,10 @@ namespace {
 constexpr int kXcds = 8;         // L2 caches of the chip; workgroup b runs on XCD b % 8
 constexpr int kXcdWgs = 64;      // workgroups of this kernel resident per XCD: 32 compute units x 2
 constexpr int kTurnTiles = 64;   // tiles per turn: 64 x 64 KiB = one L2's worth of intermediate
-// stage twiddles exp(-2 pi i e / 1024): a radix-8 stage reads e < 7/8 of a turn only
-constexpr int kTwEntries = 896;
+constexpr int kSkew = 2;         // a turn's second pass runs this many turns behind its first pass
+constexpr int kBufs = kSkew + 1; // turn buffers per XCD, used round-robin
+// stage twiddles exp(-2 pi i e / 1024): a radix-16 stage reads e < 15/16 of a turn only
+constexpr int kTwEntries = 960;
 // tile, stage twiddles, 16-bit key histogram, one word for the outcome of a wait
 constexpr size_t kFusedLds = ((size_t)(1 << kLogE) + kTwEntries) * sizeof(float2) + kHistLdsWords * sizeof(uint32_t) + 16;
 static_assert(2 * kFusedLds <= 160 * 1024, "two workgroups per compute unit (the kernel has no static LDS)");
@@ -54,27 +56,19 @@ __device__ __forceinline__ float4 ld_l2(const float4* p)
                        __uint_as_float((uint32_t)(b >> 32)));
 }
 
-// Streaming accesses for data that is touched once (gradient in, spectrum out): the non-temporal hint keeps them
-// from displacing the scratch region's lines in L2.
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 ld_stream(const float4* p)
-{
-    const floatx4 v = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p));
-    return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void st_stream(float4* p, float4 v)
-{
-    floatx4 w;
-    w.x = v.x; w.y = v.y; w.z = v.z; w.w = v.w;
-    __builtin_nontemporal_store(w, reinterpret_cast<floatx4*>(p));
-}
-
 // XCD this wave runs on (hardware register XCC_ID, bits 3:0)
 __device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg((3 << 11) | (0 << 6) | 20) & 15u; }
 
+// Members drift up to kSkew turns apart, so arrivals are counted per turn: a ring of kRing counters, turn u in
+// entry u % kRing, which has seen members * (u / kRing + 1) arrivals once every member has arrived for turn u.
+constexpr int kRing = 4;
+static_assert(kRing > kSkew + 1 && (kRing & (kRing - 1)) == 0, "a ring entry is not reused while its turn is awaited");
+__device__ __forceinline__ uint32_t* turn_ctr(uint32_t* ring, uint32_t u) { return ring + (u & (uint32_t)(kRing - 1)); }
+__device__ __forceinline__ uint32_t turn_target(uint32_t members, uint32_t u) { return members * (u / (uint32_t)kRing + 1u); }
+
 struct TeamCtl {
-    uint32_t* stored;   // members that finished storing, over all turns of this XCD
-    uint32_t* loaded;   // members that finished loading, over all turns of this XCD
+    uint32_t* stored;   // ring: members that finished storing a turn's tiles
+    uint32_t* loaded;   // ring: members that finished loading a turn's tiles
     uint32_t* gave_up;  // != 0: some workgroup of the launch gave up; everybody leaves
     uint32_t spin_limit;
 };
@@ -112,7 +106,7 @@ __device__ __forceinline__ void team_arrive_after_stores(uint32_t* ctr)
     if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// stage twiddles for transforms of up to 1024 points from one table: tw[e] = exp(-2 pi i e / 1024), e < 896
+// stage twiddles for transforms of up to 1024 points from one table: tw[e] = exp(-2 pi i e / 1024), e < 960
 template <int NT>
 __device__ __forceinline__ void load_shared_twiddles(float2* tw, const Tables& tb, int tid)
 {
@@ -158,8 +152,7 @@ template <int LOGR, int LOGT, int NT, bool INV, int NS_LOG>
 __device__ __forceinline__ void run_fft_1024(float2* d, const float2* tw, int tid)
 {
     if constexpr (NS_LOG < LOGR) {
-        constexpr int rem = LOGR - NS_LOG;
-        constexpr int RL = rem == 1 ? 1 : (rem % 3 == 0 ? 3 : 2);
+        constexpr int RL = stage_radix_log(LOGR - NS_LOG);
         fft_stage_1024<LOGR, LOGT, NT, INV, NS_LOG, RL>(d, tw, tid);
         run_fft_1024<LOGR, LOGT, NT, INV, NS_LOG + RL>(d, tw, tid);
     }
@@ -171,8 +164,8 @@ __device__ __forceinline__ void run_fft_1024(float2* d, const float2* tw, int ti
 template <int LOGN1, int LOGN2, bool FAST>
 __device__ __forceinline__ void fused_fwd_run(const float* __restrict__ in, size_t n, uint32_t C, int aligned,
                                               float2* __restrict__ scratch, float2* __restrict__ spec, uint32_t sstride,
-                                              const Tables& tb, uint32_t* __restrict__ hist, uint32_t x, uint32_t team,
-                                              uint32_t nteams, uint32_t mi, uint32_t members, const TeamCtl& tc, float2* d,
+                                              const Tables& tb, uint32_t* __restrict__ hist, uint32_t x, uint32_t mi,
+                                              uint32_t members, const TeamCtl& tc, float2* d,
                                               const float2* tw, uint32_t* h16, uint32_t* s_ok, int tid0)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
@@ -225,7 +218,7 @@ __device__ __forceinline__ void fused_fwd_run(const float* __restrict__ in, size
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
                 const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
-                r[q] = ld_stream(src + (ok ? (uint32_t)n1 * (N2 >> 1) + bp : 0u));
+                r[q] = src[ok ? (uint32_t)n1 * (N2 >> 1) + bp : 0u];
             }
         } else {
             if (!ok) return;
@@ -241,9 +234,9 @@ __device__ __forceinline__ void fused_fwd_run(const float* __restrict__ in, size
     auto fill_a = [&](int tid) { first_stage_store<LOGTA, false>(d, tid >> (LOGTA - 1), 2 * (tid & (TA / 2 - 1)), r); };
 
     // ---- pass B pieces ----
-    auto load_b = [&](uint32_t slot, uint32_t tl, int tid) {
+    auto load_b_from = [&](const float2* region, uint32_t slot, uint32_t tl, int tid) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
-        const float4* src = reinterpret_cast<const float4*>(scratch + (size_t)slot * M);
+        const float4* src = reinterpret_cast<const float4*>(region + (size_t)slot * M);
         const uint32_t pp = tl * P + p;
 #pragma unroll
         for (int q = 0; q < PER2; ++q) r[q] = ld_l2(src + (uint32_t)(kq0 + q * DK) * (N1 >> 1) + pp);
@@ -257,129 +250,149 @@ __device__ __forceinline__ void fused_fwd_run(const float* __restrict__ in, size
         atomicAdd(&h16[b >> 1], on ? 1u << ((b & 1u) * 16u) : 0u);
     };
 
-    // the first turn's first tile
-    load_a(team, 0, tid0, true);
-    for (uint32_t u = team; u < turns; u += nteams) {
-        uint32_t c = 0, slot = 0, tl = 0;
-        // ================= pass A =================
-        for (uint32_t i = 0; i < tpm; ++i) {
-            const int tid = opaque_lane(tid0);
-            const bool valid = tile_of(u, i, c, slot, tl);
-            if (valid) fill_a(tid);
-            __syncthreads();
-            const uint32_t col0 = tl << LOGTA;
-            constexpr int sh = 22 - logM;
-            float2 ratio_a[KN], ratio_b[KN], cur_a[KN], cur_b[KN];
+    // A-side twiddles of one tile: W_M^(n2 k1) as a base and a ratio per row pair (see fwd_a_run in fft.hip)
+    struct ATw {
+        float2 ratio_a[KN], ratio_b[KN], cur_a[KN], cur_b[KN];
+    };
+    auto a_twiddles = [&](int tid, uint32_t tl) {
+        ATw t;
+        const uint32_t col0 = tl << LOGTA;
+        constexpr int sh = 22 - logM;
 #pragma unroll
-            for (int kk = 0; kk < KN; ++kk) {
-                const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
-                const uint32_t ka = kp, kb = mirror_row(kp, N1);
-                const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
-                ratio_a[kk] = twiddle(tb, ((uint32_t)DC * ka) << sh);
-                ratio_b[kk] = twiddle(tb, ((uint32_t)DC * kb) << sh);
-                cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
-                cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
-            }
-            if (i + 1 < tpm) load_a(u, i + 1, tid, true);
-            if (valid) run_fft_1024<LOGN1, LOGTA, NT, false, 3>(d, tw, tid);
-            // the region is free once every member of the previous turn has taken its tiles out of it
-            if (i == 0 && !team_wait(tc.loaded, members * u, tc, s_ok)) return;
-            if (valid) {
-                float4* out = reinterpret_cast<float4*>(scratch + (size_t)slot * M);
-#pragma unroll
-                for (int kk = 0; kk < KN; ++kk) {
-                    const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
-                    const uint32_t ka = kp, kb = mirror_row(kp, N1);
-                    const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
-#pragma unroll
-                    for (int j = 0; j < NCOL; ++j) {
-                        const uint32_t col = cfirst + j * DC, n2 = col0 + col;
-                        const float2 va = cmul(d[sw_idx<LOGTA>((int)ka, (int)col)], cur_a[kk]);
-                        const float2 vb = cmul(d[sw_idx<LOGTA>((int)kb, (int)col)], cur_b[kk]);
-                        out[n2 * (uint32_t)HP + kp] = join(va, vb);
-                        cur_a[kk] = cmul(cur_a[kk], ratio_a[kk]);
-                        cur_b[kk] = cmul(cur_b[kk], ratio_b[kk]);
-                    }
-                }
-            }
-            __syncthreads();  // the tile has left LDS
+        for (int kk = 0; kk < KN; ++kk) {
+            const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
+            const uint32_t ka = kp, kb = mirror_row(kp, N1);
+            const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
+            t.ratio_a[kk] = twiddle(tb, ((uint32_t)DC * ka) << sh);
+            t.ratio_b[kk] = twiddle(tb, ((uint32_t)DC * kb) << sh);
+            t.cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
+            t.cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
         }
-        team_arrive_after_stores(tc.stored);
-        // ================= pass B =================
-        if (!team_wait(tc.stored, members * (u + 1u), tc, s_ok)) return;
-        bool valid = tile_of(u, 0, c, slot, tl);
-        if (valid) load_b(slot, tl, opaque_lane(tid0));
-        for (uint32_t i = 0; i < tpm; ++i) {
-            const int tid = opaque_lane(tid0);
-            valid = tile_of(u, i, c, slot, tl);
-            if (valid) fill_b(tid);
+        return t;
+    };
+    auto a_store = [&](int tid, float2* region, uint32_t slot, uint32_t tl, ATw& t) {
+        float4* out = reinterpret_cast<float4*>(region + (size_t)slot * M);
+        const uint32_t col0 = tl << LOGTA;
+#pragma unroll
+        for (int kk = 0; kk < KN; ++kk) {
+            const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
+            const uint32_t ka = kp, kb = mirror_row(kp, N1);
+            const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
+#pragma unroll
+            for (int j = 0; j < NCOL; ++j) {
+                const uint32_t col = cfirst + j * DC, n2 = col0 + col;
+                const float2 va = cmul(d[sw_idx<LOGTA>((int)ka, (int)col)], t.cur_a[kk]);
+                const float2 vb = cmul(d[sw_idx<LOGTA>((int)kb, (int)col)], t.cur_b[kk]);
+                out[n2 * (uint32_t)HP + kp] = join(va, vb);
+                t.cur_a[kk] = cmul(t.cur_a[kk], t.ratio_a[kk]);
+                t.cur_b[kk] = cmul(t.cur_b[kk], t.ratio_b[kk]);
+            }
+        }
+    };
+    // the real-FFT split of the tile in LDS, the spectrum store and the key histogram (see k_fwd_b in fft.hip)
+    auto b_split_store = [&](int tid, uint32_t c, uint32_t tl, float2 base_a, float2 base_b) {
+        const int p = tid & (P - 1), kq0 = tid >> LOGP;
+        const uint32_t pp = tl * P + p;
+        const bool self = pp == 0;
+        float2* out = spec + (size_t)c * (size_t)sstride;
+#pragma unroll
+        for (int q0 = 0; q0 < PER2; q0 += BATCH) {
+            float2 a0[BATCH], a1[BATCH], pa[BATCH], pb[BATCH];
+#pragma unroll
+            for (int v = 0; v < BATCH; ++v) {
+                const int k2 = kq0 + (q0 + v) * DK, k2p = (int)N2 - 1 - k2;
+                const int ia = self ? sw_idx<LOGTB>(((int)N2 - k2) & ((int)N2 - 1), 2 * p) : sw_idx<LOGTB>(k2p, 2 * p + 1);
+                const int ib = self ? sw_idx<LOGTB>(k2p, 2 * p + 1) : sw_idx<LOGTB>(k2p, 2 * p);
+                a0[v] = d[sw_idx<LOGTB>(k2, 2 * p)];
+                a1[v] = d[sw_idx<LOGTB>(k2, 2 * p + 1)];
+                pa[v] = d[ia];
+                pb[v] = d[ib];
+            }
+#pragma unroll
+            for (int v = 0; v < BATCH; ++v) {
+                const int q = q0 + v, k2 = kq0 + q * DK;
+                const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
+                float2 xa = split_fwd(a0[v], pa[v], cmul(base_a, wq));
+                const float2 xb = split_fwd(a1[v], pb[v], cmul(base_b, wq));
+                if (q == 0) {  // k2 = 0 only here: bin 0 and the Nyquist bin come from Z[0] alone
+                    const bool dc = self && kq0 == 0;
+                    const float2 xm = make_float2(a0[v].x - a0[v].y, 0.f);
+                    if (dc) {
+                        xa = make_float2(a0[v].x + a0[v].y, 0.f);
+                        out[M] = xm;
+                    }
+                    count(xm, dc);
+                }
+                reinterpret_cast<float4*>(out)[((uint32_t)k2 << (LOGN1 - 1)) + pp] = join(xa, xb);
+                count(xa, true);
+                count(xb, true);
+            }
+        }
+    };
+    auto flush_hist = [&](uint32_t c) {
+        uint32_t* g = hist + (size_t)c * kHistBins;
+        for (int i = tid0; i < kHistLdsWords; i += NT) {
+            const uint32_t v = h16[i];
+            if (v) {
+                if (v & 0xFFFFu) atomicAdd(&g[2 * i], v & 0xFFFFu);
+                if (v >> 16) atomicAdd(&g[2 * i + 1], v >> 16);
+                h16[i] = 0u;
+            }
+        }
+    };
+    auto region_of = [&](uint32_t u) { return scratch + (size_t)(u % (uint32_t)kBufs) * ((size_t)kTurnTiles << kLogE); };
+
+    // Slot s of the walk: pass A of turn s, then pass B of turn s - kSkew.  What a wait refers to lies two or three
+    // tiles back in every member's walk, so it has normally long happened; a tile's loads are issued one tile ahead
+    // (the second pass's before the first pass's FFT, the first pass's before the second pass's FFT).
+    load_a(0, 0, tid0, true);
+    for (uint32_t s = 0; s < turns + (uint32_t)kSkew; ++s) {
+        uint32_t ca = 0, slota = 0, tla = 0, cb = 0, slotb = 0, tlb = 0;
+        const bool has_a = s < turns && tile_of(s, 0, ca, slota, tla);
+        const bool in_b = s >= (uint32_t)kSkew;
+        const uint32_t ub = s - (uint32_t)kSkew;
+        const bool has_b = in_b && tile_of(ub, 0, cb, slotb, tlb);
+        int tid = opaque_lane(tid0);
+        if (has_a) fill_a(tid);
+        __syncthreads();
+        ATw at = a_twiddles(tid, tla);
+        if (in_b) {
+            // turn ub's intermediate is complete once all members have stored their tiles of it
+            if (!team_wait(turn_ctr(tc.stored, ub), turn_target(members, ub), tc, s_ok)) return;
+            if (has_b) load_b_from(region_of(ub), slotb, tlb, tid);
+        }
+        if (s < turns) {
+            if (has_a) run_fft_1024<LOGN1, LOGTA, NT, false, 3>(d, tw, tid);
+            // the buffer is free once every member has taken its tile of the turn that used it last out of it
+            if (s >= (uint32_t)kBufs) {
+                const uint32_t uold = s - (uint32_t)kBufs;
+                if (!team_wait(turn_ctr(tc.loaded, uold), turn_target(members, uold), tc, s_ok)) return;
+            }
+            if (has_a) a_store(tid, region_of(s), slota, tla, at);
+            __syncthreads();  // the tile has left LDS
+            team_arrive_after_stores(turn_ctr(tc.stored, s));
+        }
+        tid = opaque_lane(tid0);
+        if (in_b) {
+            if (has_b) fill_b(tid);
             __syncthreads();
+            if (tid0 == 0)
+                __hip_atomic_fetch_add(turn_ctr(tc.loaded, ub), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        load_a(s + 1u, 0, tid, s + 1u < turns);
+        if (in_b) {
             const int p = tid & (P - 1), kq0 = tid >> LOGP;
-            const uint32_t pp = tl * P + p;
+            const uint32_t pp = tlb * P + p;
             const uint32_t ka = pp, kb = mirror_row(pp, N1);
-            const bool self = pp == 0;
             const float2 base_a = twiddle(tb, (ka + ((uint32_t)kq0 << LOGN1)) << (21 - logM));
             const float2 base_b = twiddle(tb, (kb + ((uint32_t)kq0 << LOGN1)) << (21 - logM));
-            if (i + 1 < tpm) {
-                uint32_t c2, slot2, tl2;
-                if (tile_of(u, i + 1, c2, slot2, tl2)) load_b(slot2, tl2, tid);
-            } else {
-                // every lane has its last tile of the turn in LDS: the region may be overwritten
-                if (tid0 == 0) __hip_atomic_fetch_add(tc.loaded, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                load_a(u + nteams, 0, tid, u + nteams < turns);
-            }
-            if (valid) {
+            if (has_b) {
                 run_fft_1024<LOGN2, LOGTB, NT, false, 3>(d, tw, tid);
-                float2* out = spec + (size_t)c * (size_t)sstride;
-#pragma unroll
-                for (int q0 = 0; q0 < PER2; q0 += BATCH) {
-                    float2 a0[BATCH], a1[BATCH], pa[BATCH], pb[BATCH];
-#pragma unroll
-                    for (int v = 0; v < BATCH; ++v) {
-                        const int k2 = kq0 + (q0 + v) * DK, k2p = (int)N2 - 1 - k2;
-                        const int ia = self ? sw_idx<LOGTB>(((int)N2 - k2) & ((int)N2 - 1), 2 * p) : sw_idx<LOGTB>(k2p, 2 * p + 1);
-                        const int ib = self ? sw_idx<LOGTB>(k2p, 2 * p + 1) : sw_idx<LOGTB>(k2p, 2 * p);
-                        a0[v] = d[sw_idx<LOGTB>(k2, 2 * p)];
-                        a1[v] = d[sw_idx<LOGTB>(k2, 2 * p + 1)];
-                        pa[v] = d[ia];
-                        pb[v] = d[ib];
-                    }
-#pragma unroll
-                    for (int v = 0; v < BATCH; ++v) {
-                        const int q = q0 + v, k2 = kq0 + q * DK;
-                        const float2 wq = make_float2(kW32re[2 * q * kSplitStep], kW32im[2 * q * kSplitStep]);
-                        float2 xa = split_fwd(a0[v], pa[v], cmul(base_a, wq));
-                        const float2 xb = split_fwd(a1[v], pb[v], cmul(base_b, wq));
-                        if (q == 0) {  // k2 = 0 only here: bin 0 and the Nyquist bin come from Z[0] alone
-                            const bool dc = self && kq0 == 0;
-                            const float2 xm = make_float2(a0[v].x - a0[v].y, 0.f);
-                            if (dc) {
-                                xa = make_float2(a0[v].x + a0[v].y, 0.f);
-                                out[M] = xm;
-                            }
-                            count(xm, dc);
-                        }
-                        st_stream(reinterpret_cast<float4*>(out) + (((uint32_t)k2 << (LOGN1 - 1)) + pp), join(xa, xb));
-                        count(xa, true);
-                        count(xb, true);
-                    }
-                }
+                b_split_store(tid, cb, tlb, base_a, base_b);
             }
             __syncthreads();  // the tile has left LDS; the LDS histogram is complete for it
+            if (has_b) flush_hist(cb);
         }
-        // a member's tiles of one turn lie in one chunk: flush its keys' first digits
-        if (tile_of(u, 0, c, slot, tl)) {
-            uint32_t* g = hist + (size_t)c * kHistBins;
-            for (int i = tid0; i < kHistLdsWords; i += NT) {
-                const uint32_t v = h16[i];
-                if (v) {
-                    if (v & 0xFFFFu) atomicAdd(&g[2 * i], v & 0xFFFFu);
-                    if (v >> 16) atomicAdd(&g[2 * i + 1], v >> 16);
-                    h16[i] = 0u;
-                }
-            }
-        }
-        // (the next turn's first LDS write is behind a barrier of its own loop)
     }
 }
 
@@ -389,14 +402,11 @@ constexpr int kCtlXcc = 32;      // + x: XCD claimed by team slot x, plus one
 constexpr int kCtlStored = 128;  // + 64 x
 constexpr int kCtlLoaded = 160;  // + 64 x
 
-// split_log: which bit of the in-XCD workgroup index y = blockIdx / 8 picks the team when there are two
-// (0: y & 1, 5: y >> 5).
 template <int LOGN1, int LOGN2>
 __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_fused_fwd(const float* __restrict__ in, size_t n, uint32_t C, int aligned,
                                                    float2* __restrict__ scratch_all, float2* __restrict__ spec,
                                                    uint32_t sstride, Tables tb, uint32_t* __restrict__ hist,
-                                                   uint32_t* __restrict__ ctl, uint32_t nteams, int split_log,
-                                                   uint32_t spin_limit)
+                                                   uint32_t* __restrict__ ctl, uint32_t spin_limit)
 {
     extern __shared__ float2 smem[];
     float2* d = smem;
@@ -405,13 +415,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     uint32_t* s_ok = h16 + kHistLdsWords;
     const int tid0 = threadIdx.x;
     const uint32_t x = blockIdx.x & (kXcds - 1u), y = blockIdx.x >> 3;
-    const uint32_t members = (uint32_t)kXcdWgs / nteams;
-    uint32_t team = 0, mi = y;
-    if (nteams == 2) {
-        team = (y >> split_log) & 1u;
-        const uint32_t lowmask = (1u << split_log) - 1u;
-        mi = ((y >> (split_log + 1)) << split_log) | (y & lowmask);
-    }
+    const uint32_t members = (uint32_t)kXcdWgs, mi = y;  // the XCD's 64 workgroups are one team, a tile each per turn
     TeamCtl tc;
     tc.stored = ctl + kCtlStored + 64 * x;
     tc.loaded = ctl + kCtlLoaded + 64 * x;
@@ -428,20 +432,20 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     }
     load_shared_twiddles<kNT>(tw, tb, tid0);
     for (int i = tid0; i < kHistLdsWords; i += kNT) h16[i] = 0u;
-    float2* scratch = scratch_all + (size_t)x * ((size_t)kTurnTiles << kLogE);
+    float2* scratch = scratch_all + (size_t)x * (size_t)kBufs * ((size_t)kTurnTiles << kLogE);
     // only the gradient's last chunk can be ragged; the team that transforms it loads under guards
     constexpr int LOGG = LOGN1 + LOGN2 - kLogE;
     constexpr uint32_t CPR = (uint32_t)kTurnTiles >> LOGG;
     const uint32_t last_group = (C - 1u) / CPR;
     const bool ragged = ((size_t)C << (LOGN1 + LOGN2 + 1)) != n;
-    const bool mine = (last_group % (uint32_t)kXcds) == x && ((last_group / (uint32_t)kXcds) % nteams) == team;
+    const bool mine = (last_group % (uint32_t)kXcds) == x;
     const bool fast = (aligned & 2) != 0 && !(ragged && mine);
     __syncthreads();
     if (fast)
-        fused_fwd_run<LOGN1, LOGN2, true>(in, n, C, aligned, scratch, spec, sstride, tb, hist, x, team, nteams, mi,
+        fused_fwd_run<LOGN1, LOGN2, true>(in, n, C, aligned, scratch, spec, sstride, tb, hist, x, mi,
                                           members, tc, d, tw, h16, s_ok, tid0);
     else
-        fused_fwd_run<LOGN1, LOGN2, false>(in, n, C, aligned, scratch, spec, sstride, tb, hist, x, team, nteams, mi,
+        fused_fwd_run<LOGN1, LOGN2, false>(in, n, C, aligned, scratch, spec, sstride, tb, hist, x, mi,
                                            members, tc, d, tw, h16, s_ok, tid0);
 }
 
@@ -452,8 +456,8 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
 template <int LOGN1, int LOGN2>
 __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, uint32_t sstride, size_t n, uint32_t C,
                                               int aligned, float gain, float2* __restrict__ scratch,
-                                              float* __restrict__ out, const Tables& tb, uint32_t x, uint32_t team,
-                                              uint32_t nteams, uint32_t mi, uint32_t members, const TeamCtl& tc, float2* d,
+                                              float* __restrict__ out, const Tables& tb, uint32_t x, uint32_t mi,
+                                              uint32_t members, const TeamCtl& tc, float2* d,
                                               const float2* tw, uint32_t* s_ok, int tid0)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
@@ -501,11 +505,11 @@ __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, u
         base_b = twiddle(tb, (kb + ((uint32_t)kq0 << LOGN1)) << (21 - logM));
         const float4* X4 = reinterpret_cast<const float4*>(X);
 #pragma unroll
-        for (int q = 0; q < PER2; ++q) r[q] = ld_stream(X4 + (ok ? ((uint32_t)(kq0 + q * DK) << (LOGN1 - 1)) + pp : 0u));
+        for (int q = 0; q < PER2; ++q) r[q] = X4[ok ? ((uint32_t)(kq0 + q * DK) << (LOGN1 - 1)) + pp : 0u];
         xnyq = X[ok ? M : 0u];
     };
-    auto load_mid = [&](uint32_t slot, uint32_t tl, int tid) {
-        const float4* src = reinterpret_cast<const float4*>(scratch + (size_t)slot * M);
+    auto load_mid_from = [&](const float2* region, uint32_t slot, uint32_t tl, int tid) {
+        const float4* src = reinterpret_cast<const float4*>(region + (size_t)slot * M);
         const uint32_t col0 = tl << LOGTA;
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
@@ -514,16 +518,20 @@ __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, u
         }
     };
 
-    load_spec(team, 0, tid0, true);
-    for (uint32_t u = team; u < turns; u += nteams) {
+    auto region_of = [&](uint32_t u) { return scratch + (size_t)(u % (uint32_t)kBufs) * ((size_t)kTurnTiles << kLogE); };
+
+    // Slot s: the split and the transforms over k2 of turn s, then the transforms over k1 of turn s - kSkew (same
+    // skewed walk as the forward kernel).  A tile past the last chunk (last turn of a call whose chunks do not fill
+    // it) is transformed like any other: its loads read one valid dummy address, its stores land in the region or are
+    // dropped by the output guards, so the loop needs no branches around the arithmetic.
+    load_spec(0, 0, tid0, true);
+    for (uint32_t s = 0; s < turns + (uint32_t)kSkew; ++s) {
         uint32_t c = 0, slot = 0, tl = 0;
-        // ================= split + inverse transforms over k2 =================
-        for (uint32_t i = 0; i < tpm; ++i) {
-            const int tid = opaque_lane(tid0);
-            // a tile past the last chunk (last turn of a call whose chunks do not fill it) is transformed like any
-            // other: its loads read one valid dummy address, its stores land in the region or are dropped by the
-            // output guards, so the loop needs no branches around the arithmetic
-            (void)tile_of(u, i, c, slot, tl);
+        const bool in_a = s >= (uint32_t)kSkew;
+        const uint32_t ua = s - (uint32_t)kSkew;
+        int tid = opaque_lane(tid0);
+        if (s < turns) {
+            (void)tile_of(s, 0, c, slot, tl);
             const int p = tid & (P - 1), kq0 = tid >> LOGP;
             const uint32_t pp = tl * P + p;
             const uint32_t ka = pp, kb = mirror_row(pp, N1);
@@ -563,11 +571,19 @@ __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, u
             const float2 ratio_b = twiddle(tb, ((uint32_t)DK * kb) << sh);
             float2 cur_a = twiddle(tb, ((uint32_t)kq0 * ka) << sh);
             float2 cur_b = twiddle(tb, ((uint32_t)kq0 * kb) << sh);
-            if (i + 1 < tpm) load_spec(u, i + 1, tid, true);
+            if (in_a) {
+                if (!team_wait(turn_ctr(tc.stored, ua), turn_target(members, ua), tc, s_ok)) return;
+                uint32_t c2, slot2, tl2;
+                (void)tile_of(ua, 0, c2, slot2, tl2);
+                load_mid_from(region_of(ua), slot2, tl2, tid);
+            }
             run_fft_1024<LOGN2, LOGTB, NT, true, 3>(d, tw, tid);
-            if (i == 0 && !team_wait(tc.loaded, members * u, tc, s_ok)) return;
+            if (s >= (uint32_t)kBufs) {
+                const uint32_t uold = s - (uint32_t)kBufs;
+                if (!team_wait(turn_ctr(tc.loaded, uold), turn_target(members, uold), tc, s_ok)) return;
+            }
             {
-                float4* dst = reinterpret_cast<float4*>(scratch + (size_t)slot * M);
+                float4* dst = reinterpret_cast<float4*>(region_of(s) + (size_t)slot * M);
 #pragma unroll
                 for (int q = 0; q < PER2; ++q) {
                     const uint32_t n2 = (uint32_t)(kq0 + q * DK);
@@ -578,15 +594,17 @@ __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, u
                 }
             }
             __syncthreads();
+            team_arrive_after_stores(turn_ctr(tc.stored, s));
+        } else {
+            // the walk's last slots: only the transforms over k1 are left
+            if (!team_wait(turn_ctr(tc.stored, ua), turn_target(members, ua), tc, s_ok)) return;
+            uint32_t c2, slot2, tl2;
+            (void)tile_of(ua, 0, c2, slot2, tl2);
+            load_mid_from(region_of(ua), slot2, tl2, tid);
         }
-        team_arrive_after_stores(tc.stored);
-        // ================= inverse transforms over k1 =================
-        if (!team_wait(tc.stored, members * (u + 1u), tc, s_ok)) return;
-        (void)tile_of(u, 0, c, slot, tl);
-        load_mid(slot, tl, opaque_lane(tid0));
-        for (uint32_t i = 0; i < tpm; ++i) {
-            const int tid = opaque_lane(tid0);
-            (void)tile_of(u, i, c, slot, tl);
+        tid = opaque_lane(tid0);
+        if (in_a) {
+            (void)tile_of(ua, 0, c, slot, tl);
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
                 const int w = tid + q * NT, kp = w & (HP - 1), col = w >> LOGHP;
@@ -594,37 +612,31 @@ __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, u
                 d[sw_idx<LOGTA>((int)mirror_row((uint32_t)kp, N1), col)] = hi2(r[q]);
             }
             __syncthreads();
-            if (i + 1 < tpm) {
-                uint32_t c2, slot2, tl2;
-                (void)tile_of(u, i + 1, c2, slot2, tl2);
-                load_mid(slot2, tl2, tid);
+            if (tid0 == 0)
+                __hip_atomic_fetch_add(turn_ctr(tc.loaded, ua), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        load_spec(s + 1u, 0, tid, s + 1u < turns);
+        if (in_a) {
+            run_fft_1024<LOGN1, LOGTA, NT, true, 0>(d, tw, tid);
+            // a chunk past the end starts beyond n: the guarded branch below then stores nothing
+            const size_t cbase = (size_t)c * (2 * (size_t)M);
+            const uint32_t col0 = tl << LOGTA;
+            if ((aligned & 2) && cbase + 2 * (size_t)M <= n) {  // whole chunk inside the output: no guards
+                float4* dst = reinterpret_cast<float4*>(out + cbase) + (col0 >> 1);
+#pragma unroll
+                for (int q = 0; q < PER2; ++q) {
+                    const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
+                    const float4 v = lds_load2<LOGTA>(d, n1, 2 * bp);
+                    dst[(uint32_t)n1 * (N2 >> 1) + bp] = make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
+                }
             } else {
-                if (tid0 == 0) __hip_atomic_fetch_add(tc.loaded, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                load_spec(u + nteams, 0, tid, u + nteams < turns);
-            }
-            {
-                run_fft_1024<LOGN1, LOGTA, NT, true, 0>(d, tw, tid);
-                // a chunk past the end starts beyond n: the guarded branch below then stores nothing
-                const size_t cbase = (size_t)c * (2 * (size_t)M);
-                const uint32_t col0 = tl << LOGTA;
-                if ((aligned & 2) && cbase + 2 * (size_t)M <= n) {  // whole chunk inside the output: no guards
-                    float4* dst = reinterpret_cast<float4*>(out + cbase) + (col0 >> 1);
 #pragma unroll
-                    for (int q = 0; q < PER2; ++q) {
-                        const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
-                        const float4 v = lds_load2<LOGTA>(d, n1, 2 * bp);
-                        st_stream(dst + ((uint32_t)n1 * (N2 >> 1) + bp),
-                                  make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale));
-                    }
-                } else {
-#pragma unroll
-                    for (int q = 0; q < PER2; ++q) {
-                        const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
-                        const float4 v = lds_load2<LOGTA>(d, n1, 2 * bp);
-                        const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
-                        store_pair(out, gi, n, aligned & 1, make_float2(v.x * scale, v.y * scale));
-                        store_pair(out, gi + 2, n, aligned & 1, make_float2(v.z * scale, v.w * scale));
-                    }
+                for (int q = 0; q < PER2; ++q) {
+                    const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGTA - 1);
+                    const float4 v = lds_load2<LOGTA>(d, n1, 2 * bp);
+                    const size_t gi = cbase + 2 * ((size_t)n1 * N2 + col0 + 2 * bp);
+                    store_pair(out, gi, n, aligned & 1, make_float2(v.x * scale, v.y * scale));
+                    store_pair(out, gi + 2, n, aligned & 1, make_float2(v.z * scale, v.w * scale));
                 }
             }
             __syncthreads();
@@ -635,8 +647,8 @@ __device__ __forceinline__ void fused_inv_run(const float2* __restrict__ spec, u
 template <int LOGN1, int LOGN2>
 __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_fused_inv(
     const float2* __restrict__ spec, uint32_t sstride, size_t n, uint32_t C, int aligned, float gain,
-    float2* __restrict__ scratch_all, float* __restrict__ out, Tables tb, uint32_t* __restrict__ ctl, uint32_t nteams,
-    int split_log, uint32_t spin_limit)
+    float2* __restrict__ scratch_all, float* __restrict__ out, Tables tb, uint32_t* __restrict__ ctl,
+    uint32_t spin_limit)
 {
     extern __shared__ float2 smem[];
     float2* d = smem;
@@ -644,13 +656,7 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     uint32_t* s_ok = reinterpret_cast<uint32_t*>(tw + kTwEntries);
     const int tid0 = threadIdx.x;
     const uint32_t x = blockIdx.x & (kXcds - 1u), y = blockIdx.x >> 3;
-    const uint32_t members = (uint32_t)kXcdWgs / nteams;
-    uint32_t team = 0, mi = y;
-    if (nteams == 2) {
-        team = (y >> split_log) & 1u;
-        const uint32_t lowmask = (1u << split_log) - 1u;
-        mi = ((y >> (split_log + 1)) << split_log) | (y & lowmask);
-    }
+    const uint32_t members = (uint32_t)kXcdWgs, mi = y;  // the XCD's 64 workgroups are one team, a tile each per turn
     TeamCtl tc;
     tc.stored = ctl + kCtlStored + 64 * x;
     tc.loaded = ctl + kCtlLoaded + 64 * x;
@@ -665,9 +671,9 @@ __global__ __launch_bounds__(kNT) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
         }
     }
     load_shared_twiddles<kNT>(tw, tb, tid0);
-    float2* scratch = scratch_all + (size_t)x * ((size_t)kTurnTiles << kLogE);
+    float2* scratch = scratch_all + (size_t)x * (size_t)kBufs * ((size_t)kTurnTiles << kLogE);
     __syncthreads();
-    fused_inv_run<LOGN1, LOGN2>(spec, sstride, n, C, aligned, gain, scratch, out, tb, x, team, nteams, mi, members, tc, d,
+    fused_inv_run<LOGN1, LOGN2>(spec, sstride, n, C, aligned, gain, scratch, out, tb, x, mi, members, tc, d,
                                 tw, s_ok, tid0);
 }
 
@@ -677,26 +683,16 @@ FusedKnobs fused_knobs()
 {
     FusedKnobs k;
     k.enabled = 0;  // off until measured faster on the GPU
-    k.teams = 1;
-    k.split_log = 5;
     k.spin_limit = 1u << 18;  // a poll takes about a microsecond: a quarter of a second before a wait gives up
     if (const char* e = std::getenv("FFTSP_FUSED")) k.enabled = std::atoi(e) != 0;
-    if (const char* e = std::getenv("FFTSP_FUSED_TEAMS")) k.teams = std::atoi(e) == 2 ? 2 : 1;
-    if (const char* e = std::getenv("FFTSP_FUSED_SPLIT")) k.split_log = std::atoi(e) == 0 ? 0 : 5;
     if (const char* e = std::getenv("FFTSP_FUSED_SPIN")) k.spin_limit = (uint32_t)std::strtoul(e, nullptr, 10);
     return k;
 }
 
-// Which chunk lengths and counts take the fused kernels: two-pass lengths whose chunks fit a turn (2^15 .. 2^20
-// samples), and enough tiles that the team scratch (32 MiB) is no larger than the per-pass intermediate it replaces.
-bool fused_applies(int logL, size_t C)
-{
-    const int logM = logL - 1;
-    if (logM < 14 || logM > 19) return false;
-    return (C << (logM - kLogE)) >= (size_t)kXcds * kTurnTiles;
-}
+static_assert(kFusedScratchBytes == (size_t)kXcds * kBufs * ((size_t)kTurnTiles << kLogE) * sizeof(float2),
+              "the workspace reserves what the kernels address");
 
-size_t fused_scratch_bytes() { return (size_t)kXcds * ((size_t)kTurnTiles << kLogE) * sizeof(float2); }
+bool fused_applies(int logL, size_t C) { return fused_shape(logL, C); }
 
 hipError_t launch_fused_rfft(const float* in, size_t n, int logL, size_t C, float2* spec, uint32_t sstride,
                              float2* scratch, Tables t, uint32_t* hist, uint32_t* ctl, const FusedKnobs& knobs,
@@ -706,9 +702,6 @@ hipError_t launch_fused_rfft(const float* in, size_t n, int logL, size_t C, floa
     if (!fused_applies(logL, C) || C > 0x7fffffu) return hipErrorInvalidValue;
     const uintptr_t addr = reinterpret_cast<uintptr_t>(in);
     const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
-    const int logN1 = (logM + 1) / 2;
-    const uint32_t nteams = knobs.teams == 2 ? 2u : 1u;
-    const int split_log = knobs.split_log == 0 ? 0 : 5;
 #define FFTSP_FUSED_FWD(a, b)                                                                                         \
     do {                                                                                                              \
         auto kern = k_fused_fwd<a, b>;                                                                                \
@@ -716,7 +709,7 @@ hipError_t launch_fused_rfft(const float* in, size_t n, int logL, size_t C, floa
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds);              \
         if (e != hipSuccess) return e;                                                                                \
         FFTSP_LAUNCH("rfft_fused", kern, dim3(kXcds * kXcdWgs), dim3(kNT), kFusedLds, s, in, n, (uint32_t)C, aligned, \
-                     scratch, spec, sstride, t, hist, ctl, nteams, split_log, knobs.spin_limit);                     \
+                     scratch, spec, sstride, t, hist, ctl, knobs.spin_limit);                     \
     } while (0)
     switch (logM) {
         case 14: FFTSP_FUSED_FWD(7, 7); break;
@@ -728,7 +721,6 @@ hipError_t launch_fused_rfft(const float* in, size_t n, int logL, size_t C, floa
         default: return hipErrorInvalidValue;
     }
 #undef FFTSP_FUSED_FWD
-    (void)logN1;
     return hipGetLastError();
 }
 
@@ -740,8 +732,6 @@ hipError_t launch_fused_irfft(const float2* spec, uint32_t sstride, size_t n, in
     if (!fused_applies(logL, C) || C > 0x7fffffu) return hipErrorInvalidValue;
     const uintptr_t addr = reinterpret_cast<uintptr_t>(out);
     const int aligned = ((addr & 7u) == 0 ? 1 : 0) | ((addr & 15u) == 0 ? 2 : 0);
-    const uint32_t nteams = knobs.teams == 2 ? 2u : 1u;
-    const int split_log = knobs.split_log == 0 ? 0 : 5;
 #define FFTSP_FUSED_INV(a, b)                                                                                            \
     do {                                                                                                                 \
         auto kern = k_fused_inv<a, b>;                                                                                   \
@@ -749,7 +739,7 @@ hipError_t launch_fused_irfft(const float2* spec, uint32_t sstride, size_t n, in
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds);                 \
         if (e != hipSuccess) return e;                                                                                   \
         FFTSP_LAUNCH("irfft_fused", kern, dim3(kXcds * kXcdWgs), dim3(kNT), kFusedLds, s, spec, sstride, n, (uint32_t)C, \
-                     aligned, gain, scratch, out, t, ctl, nteams, split_log, knobs.spin_limit);                         \
+                     aligned, gain, scratch, out, t, ctl, knobs.spin_limit);                         \
     } while (0)
     switch (logM) {
         case 14: FFTSP_FUSED_INV(7, 7); break;

@@ -85,6 +85,15 @@ constexpr int kKeyShift = 31 - kHistBits;     // bucket = key >> 19
 constexpr size_t kControlBytes = 4096;  // control block at the start of every workspace
 constexpr int kCtlGaveUpWord = 1;       // u32 index of the fused kernels' give-up word inside the control block
 
+// The fused transforms (fused.hip) take chunk lengths 2^15 .. 2^20 when the call has at least 512 tiles of 8192
+// points, and address three turn buffers of 4 MiB per XCD inside the intermediate's region.
+constexpr size_t kFusedScratchBytes = (size_t)8 * 3 * 64 * 8192 * 8;
+static inline bool fused_shape(int logL, size_t C)
+{
+    const int logM = logL - 1;
+    return logM >= 14 && logM <= 19 && (C << (logM - 13)) >= 512;
+}
+
 // Where everything lives inside the caller's workspace (byte offsets, 256-aligned).
 struct Workspace {
     size_t status;    // u32[1024] control block: word 0 = device status, word 1 = "the fused transform gave up",
@@ -164,7 +173,10 @@ static inline Workspace make_workspace(size_t C, uint32_t L, int time_domain = 0
     w.tscan = off;  off = align256(off + C * Tn * 8);
     // The candidate list and the two-pass intermediate are never alive together (the sender's transform has
     // finished before the first candidate is written; the receiver has no candidates): one region serves both.
-    const size_t cand_bytes = C * Tn * kTile * 8, mid_bytes = time_domain ? 0 : C * (size_t)L * 4;
+    size_t cand_bytes = C * Tn * kTile * 8, mid_bytes = time_domain ? 0 : C * (size_t)L * 4;
+    int logL = 0;
+    while (((size_t)1 << logL) < L) ++logL;
+    if (!time_domain && fused_shape(logL, C) && mid_bytes < kFusedScratchBytes) mid_bytes = kFusedScratchBytes;
     w.cand = off;
     w.mid = off;    off = align256(off + (cand_bytes > mid_bytes ? cand_bytes : mid_bytes));
     w.prefix = off; off = align256(off + C * W * 4);
@@ -230,13 +242,10 @@ hipError_t launch_irfft(const float* spec, uint32_t sstride, size_t n, int logL,
 // word, which redo the transform if the fused kernel could not finish.
 struct FusedKnobs {
     int enabled;          // 0: never take the fused kernels
-    int teams;            // teams per XCD: 1 or 2
-    int split_log;        // two teams: 0 = neighbouring workgroups alternate, 5 = first and second half
     uint32_t spin_limit;  // polls before a hand-over wait gives up
 };
 FusedKnobs fused_knobs();  // defaults overridden by the FFTSP_FUSED* environment variables (read at every call)
 bool fused_applies(int logL, size_t C);
-size_t fused_scratch_bytes();
 // spec: the codec's own buffer (paired order); hist: u32[C][kHistBins], already zero; ctl: the control block, zero
 hipError_t launch_fused_rfft(const float* in, size_t n, int logL, size_t C, float2* spec, uint32_t sstride,
                              float2* scratch, Tables t, uint32_t* hist, uint32_t* ctl, const FusedKnobs& knobs,
