@@ -11,8 +11,9 @@
  *     16-byte aligned.  seg_offsets is a HOST pointer.  The caller owns every
  *     buffer; the library allocates nothing (its two 16 KiB twiddle tables are
  *     constants inside the code object).  The per-tensor entry points create
- *     three streams and four events per device on their first call, which
- *     therefore must not sit inside a stream capture.
+ *     three streams and four events per device on their first call outside a
+ *     stream capture; they create nothing while the caller's stream is being
+ *     captured (see there).
  *   - Calls only enqueue work on `stream` and return; they never synchronise and
  *     never touch the null stream.  Input buffers are not modified.  Output
  *     regions are written completely (padding bytes zero), so results are
@@ -222,7 +223,10 @@ int fftsp_topk_decompress(const void* d_packed, size_t packed_bytes, float* d_gr
  *      than with the number of tensors.  These launch sets run on up to four streams at once (the caller's and
  *      streams of the library's own that fork from and join back into it, so the call is still one unit of work
  *      on the caller's stream and can be captured into a graph); the workspace holds one region per stream, each
- *      sized for the largest group. ---- */
+ *      sized for the largest group.  The side streams belong to the device and are shared by all callers: calls
+ *      from several host threads enqueue one after the other.  A captured call keeps the side streams inside its
+ *      capture until that capture ends; a call made meanwhile on another stream, and a captured call made before
+ *      the side streams exist, runs all its launch sets on the caller's stream alone (same bytes, less overlap). ---- */
 size_t fftsp_packed_bytes_segments(const size_t* seg_offsets, int nseg, float theta, int bits);
 size_t fftsp_workspace_bytes_segments(const size_t* seg_offsets, int nseg, int bits);
 int fftsp_compress_segments(const float* d_grad, const size_t* seg_offsets, int nseg, float theta, int bits,

@@ -833,32 +833,72 @@ static std::vector<int> assign_lanes(const std::vector<SegBatch>& batches, int l
 
 }  // extern "C" (a template cannot have C linkage)
 
-// body(launch set index, stream, lane) enqueues one launch set; sets of one lane run in index order on its stream
+// The capture `s` is being recorded into: its id, 0 if none, ~0 if the capture is broken.
+static hipError_t capture_of(hipStream_t s, unsigned long long* id)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    unsigned long long i = 0;
+    const hipError_t e = hipStreamGetCaptureInfo(s, &st, &i);
+    if (e != hipSuccess) return e;
+    *id = st == hipStreamCaptureStatusNone ? 0ull : (st == hipStreamCaptureStatusActive ? i : ~0ull);
+    return hipSuccess;
+}
+
+static void destroy_lanes(SegLanes& ln, int streams, int joins, bool fork)
+{
+    for (int i = 0; i < streams; ++i) (void)hipStreamDestroy(ln.s[i]);
+    for (int i = 0; i < joins; ++i) (void)hipEventDestroy(ln.join[i]);
+    if (fork) (void)hipEventDestroy(ln.fork);
+}
+
+// body(launch set index, stream, lane) enqueues one launch set; sets of one lane run in index order on its stream.
+// The side streams belong to the device, not to a caller.  A caller that records its stream into a graph pulls them
+// into that capture until it ends, so a call falls back to the caller's stream alone (lane 0, the same result,
+// the launch sets one after the other) when a side stream is being recorded into a capture other than the
+// caller's own, and when the side streams do not exist yet and the caller is recording (nothing is created while a
+// capture is open).
 template <typename F>
 static hipError_t run_on_lanes(hipStream_t user, const std::vector<int>& lane_of, int lanes, F&& body)
 {
-    if (lanes <= 1) {
+    auto serial = [&]() {
         for (size_t bi = 0; bi < lane_of.size(); ++bi) {
             const hipError_t e = body(bi, user, 0);
             if (e != hipSuccess) return e;
         }
         return hipSuccess;
-    }
+    };
+    if (lanes <= 1) return serial();
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
     std::lock_guard<std::mutex> lock(g_seg_mutex);
     SegLanes& ln = g_seg_lanes[dev];
+    unsigned long long mine = 0;
+    e = capture_of(user, &mine);
+    if (e != hipSuccess) return e;
     if (!ln.ready) {
-        for (int i = 0; i < kSegLanes - 1; ++i) {
+        if (mine != 0) return serial();
+        int streams = 0, joins = 0;
+        for (int i = 0; i < kSegLanes - 1 && e == hipSuccess; ++i) {
             e = hipStreamCreateWithFlags(&ln.s[i], hipStreamNonBlocking);  // default priority
-            if (e == hipSuccess) e = hipEventCreateWithFlags(&ln.join[i], hipEventDisableTiming);
-            if (e != hipSuccess) return e;
+            if (e != hipSuccess) break;
+            ++streams;
+            e = hipEventCreateWithFlags(&ln.join[i], hipEventDisableTiming);
+            if (e == hipSuccess) ++joins;
         }
-        e = hipEventCreateWithFlags(&ln.fork, hipEventDisableTiming);
-        if (e != hipSuccess) return e;
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ln.fork, hipEventDisableTiming);
+        if (e != hipSuccess) {
+            destroy_lanes(ln, streams, joins, false);  // the next call starts over
+            return e;
+        }
         ln.ready = true;
+    }
+    for (int l = 1; l < lanes; ++l) {
+        unsigned long long theirs = 0;
+        e = capture_of(ln.s[l - 1], &theirs);
+        if (e != hipSuccess) return e;
+        if (theirs != 0 && theirs != mine) return serial();
     }
     e = hipEventRecord(ln.fork, user);
     for (int l = 1; l < lanes && e == hipSuccess; ++l) e = hipStreamWaitEvent(ln.s[l - 1], ln.fork, 0);
