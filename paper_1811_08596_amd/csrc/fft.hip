@@ -26,6 +26,24 @@
 namespace fftsp {
 namespace {
 
+// The next tile's loads are issued in at most this many portions: one before the LDS stages, one after each of the
+// first stages.  A wave that issues a whole tile's loads at once stands in the issue until the memory pipeline has
+// taken them; in portions the stages in between proceed meanwhile.
+constexpr int kSpreadA = 2;   // forward pass A (measured: 144 us whole, 137-138 in two portions, 138-141 in three)
+constexpr int kSpreadFB = 3;  // forward pass B (110-112 us -> 108-109)
+constexpr int kSpreadIB = 2;  // inverse pass B (114-116 -> 113)
+constexpr int kSpreadIA = 3;  // inverse pass A (117 -> 115-116)
+template <int LDS_LEVELS, int MOST>
+constexpr int portions()
+{
+    return lds_stages(LDS_LEVELS) + 1 < MOST ? lds_stages(LDS_LEVELS) + 1 : MOST;
+}
+template <int LOGN1>
+constexpr int spread_parts()
+{
+    return portions<LOGN1 - 3, kSpreadA>();
+}
+
 // Where chunk c's samples live: elements [first, limit) of the gradient; pairs != 0 allows 8-byte accesses.
 struct Span {
     size_t first, limit;
@@ -146,6 +164,62 @@ __global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spe
 // 16-byte aligned: two columns per 16-byte load, no guards.  Otherwise every element is loaded under a guard
 // (ragged last chunk, unaligned tensors); the two variants are separate loops so that the guarded one does
 // not put branches between the fast one's loads and their use.
+// One tile of pass A once its first stage is in LDS: the twiddle look-ups of the store loop, `prefetch()` (loads of
+// a later tile, issued here so that they are older than this tile's stores), the LDS stages, and the store loop,
+// which multiplies by W_M^(n2 k1) and writes row k1 next to row N1 - k1.
+template <int LOGN1, bool HALF, typename Prefetch>
+__device__ __forceinline__ void fwd_a_tile(uint32_t t, uint32_t tiles, int logM, typename Cx<HALF>::One* __restrict__ mid,
+                                           const Tables& tb, float2* d, const float2* tw, int tid, float in_scale,
+                                           Prefetch prefetch)
+{
+    constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
+    constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1;
+    constexpr int HP = N1 / 2, LOGHP = LOGN1 - 1;  // row pairs per column
+    constexpr int KN = HP >= NT ? HP / NT : 1;   // distinct row pairs per lane in the store loop
+    constexpr int DC = HP >= NT ? 1 : NT / HP;   // column step between a lane's consecutive stores
+    constexpr int NCOL = PER2 / KN;
+    static_assert(NCOL <= 8, "twiddle recurrence is anchored once");
+    const uint32_t M = 1u << logM;
+    const uint32_t col0 = tile_in_chunk(t, tiles) << LOGT;
+    const int sh = 22 - logM;
+    float2 ratio_a[KN], ratio_b[KN], cur_a[KN], cur_b[KN];
+#pragma unroll
+    for (int kk = 0; kk < KN; ++kk) {
+        const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
+        const uint32_t ka = kp, kb = mirror_row(kp, N1);
+        const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
+        ratio_a[kk] = twiddle(tb, ((uint32_t)DC * ka) << sh);
+        ratio_b[kk] = twiddle(tb, ((uint32_t)DC * kb) << sh);
+        cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
+        cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
+        if constexpr (HALF) {  // the variant's power-of-two factors ride on the twiddles (exact)
+            cur_a[kk] = make_float2(cur_a[kk].x * in_scale, cur_a[kk].y * in_scale);
+            cur_b[kk] = make_float2(cur_b[kk].x * in_scale, cur_b[kk].y * in_scale);
+        }
+    }
+    // the next tile's loads go out in kSpreadA portions: one before the LDS stages, one after each of the first stages
+    prefetch(0);
+    run_fft_between<LOGN1, LOGT, NT, false, 3>(d, tw, tid, [&](int k) {
+        if (k + 1 < spread_parts<LOGN1>()) prefetch(k + 1);
+    });
+    typename Cx<HALF>::Two* out = reinterpret_cast<typename Cx<HALF>::Two*>(mid + (size_t)(t / tiles) * (size_t)M);
+#pragma unroll
+    for (int kk = 0; kk < KN; ++kk) {
+        const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);  // pair of paired positions (2kp, 2kp+1)
+        const uint32_t ka = kp, kb = mirror_row(kp, N1);
+        const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
+#pragma unroll
+        for (int j = 0; j < NCOL; ++j) {
+            const uint32_t col = cfirst + j * DC, n2 = col0 + col;
+            const float2 va = cmul(d[sw_idx<LOGT>((int)ka, (int)col)], cur_a[kk]);
+            const float2 vb = cmul(d[sw_idx<LOGT>((int)kb, (int)col)], cur_b[kk]);
+            out[n2 * (uint32_t)HP + kp] = cx_store<HALF>(join(va, vb));
+            cur_a[kk] = cmul(cur_a[kk], ratio_a[kk]);
+            cur_b[kk] = cmul(cur_b[kk], ratio_b[kk]);
+        }
+    }
+}
+
 template <int LOGN1, bool FAST, bool TABLE, bool HALF>
 __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n, int logM,
                                           typename Cx<HALF>::One* __restrict__ mid, const Tables& tb, int aligned,
@@ -154,17 +228,12 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1, TA = 1 << LOGT;
-    constexpr int HP = N1 / 2, LOGHP = LOGN1 - 1;  // row pairs per column
     static_assert(LOGT >= 2 && (NT % (TA / 2)) == 0, "tile shape");
-    constexpr int KN = HP >= NT ? HP / NT : 1;   // distinct row pairs per lane in the store loop
-    constexpr int DC = HP >= NT ? 1 : NT / HP;   // column step between a lane's consecutive stores
-    constexpr int NCOL = PER2 / KN;
-    static_assert(NCOL <= 8, "twiddle recurrence is anchored once");
     const uint32_t M = 1u << logM, N2 = M >> LOGN1, tiles = N2 >> LOGT;
 
-    float4 r[PER2];
     // live = false: the tile does not exist; the fast loads are still issued, all to one valid address
-    auto load_tile = [&](uint32_t tile, int tid, bool live) {
+    // part p of spread_parts(): loads q with q * parts / PER2 == p; prologue calls pass every part in turn
+    auto load_tile = [&](float4 (&r)[PER2], uint32_t tile, int tid, bool live, int part) {
         // every tile lies in a real chunk, so the span needs no chunk count
         const Span sp = chunk_span<TABLE>(tab, tile / tiles, ~(size_t)0, 2 * (size_t)M, n, aligned & 1);
         const uint32_t col0 = tile_in_chunk(tile, tiles) << LOGT;
@@ -173,11 +242,12 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
                                      : reinterpret_cast<const float4*>(tb.hi);
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
+                if (q * spread_parts<LOGN1>() / PER2 != part) continue;
                 const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
                 r[q] = src[live ? (uint32_t)n1 * (N2 >> 1) + bp : 0u];
             }
         } else {
-            if (!live) return;
+            if (!live || part != 0) return;
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
                 const int w = tid + q * NT, bp = w & (TA / 2 - 1), n1 = w >> (LOGT - 1);
@@ -188,52 +258,23 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
     };
     // r[q] holds rows (tid >> (LOGT-1)) + q * N1/8 of one column pair: the first stage runs on the way into LDS
     static_assert(PER2 == 8 && (NT >> (LOGT - 1)) == N1 / 8, "a lane's loads are the inputs of two radix-8 butterflies");
-    auto fill = [&](int tid) { first_stage_store<LOGT, false>(d, tid >> (LOGT - 1), 2 * (tid & (TA / 2 - 1)), r); };
-    load_tile(t, tid0, true);
-    fill(tid0);
+    auto fill = [&](const float4 (&r)[PER2], int tid) {
+        first_stage_store<LOGT, false>(d, tid >> (LOGT - 1), 2 * (tid & (TA / 2 - 1)), r);
+    };
+    float4 r[PER2];
+#pragma unroll
+    for (int part = 0; part < spread_parts<LOGN1>(); ++part) load_tile(r, t, tid0, true, part);
+    fill(r, tid0);
     __syncthreads();
     for (;;) {
         const int tid = opaque_lane(tid0);
-        const uint32_t col0 = tile_in_chunk(t, tiles) << LOGT;
-        const int sh = 22 - logM;
-        float2 ratio_a[KN], ratio_b[KN], cur_a[KN], cur_b[KN];
-#pragma unroll
-        for (int kk = 0; kk < KN; ++kk) {
-            const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
-            const uint32_t ka = kp, kb = mirror_row(kp, N1);
-            const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
-            ratio_a[kk] = twiddle(tb, ((uint32_t)DC * ka) << sh);
-            ratio_b[kk] = twiddle(tb, ((uint32_t)DC * kb) << sh);
-            cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
-            cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
-            if constexpr (HALF) {  // the variant's power-of-two factors ride on the twiddles (exact)
-                cur_a[kk] = make_float2(cur_a[kk].x * in_scale, cur_a[kk].y * in_scale);
-                cur_b[kk] = make_float2(cur_b[kk].x * in_scale, cur_b[kk].y * in_scale);
-            }
-        }
         const bool more = t + tstep < tend;
-        load_tile(more ? t + tstep : t, tid, more);
-        run_fft<LOGN1, LOGT, NT, false, 3>(d, tw, tid);
-        typename Cx<HALF>::Two* out = reinterpret_cast<typename Cx<HALF>::Two*>(mid + (size_t)(t / tiles) * (size_t)M);
-#pragma unroll
-        for (int kk = 0; kk < KN; ++kk) {
-            const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);  // pair of paired positions (2kp, 2kp+1)
-            const uint32_t ka = kp, kb = mirror_row(kp, N1);
-            const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
-#pragma unroll
-            for (int j = 0; j < NCOL; ++j) {
-                const uint32_t col = cfirst + j * DC, n2 = col0 + col;
-                const float2 va = cmul(d[sw_idx<LOGT>((int)ka, (int)col)], cur_a[kk]);
-                const float2 vb = cmul(d[sw_idx<LOGT>((int)kb, (int)col)], cur_b[kk]);
-                out[n2 * (uint32_t)HP + kp] = cx_store<HALF>(join(va, vb));
-                cur_a[kk] = cmul(cur_a[kk], ratio_a[kk]);
-                cur_b[kk] = cmul(cur_b[kk], ratio_b[kk]);
-            }
-        }
+        fwd_a_tile<LOGN1, HALF>(t, tiles, logM, mid, tb, d, tw, tid, in_scale,
+                                [&](int part) { load_tile(r, more ? t + tstep : t, tid, more, part); });
         if (!more) break;
         t += tstep;
         __syncthreads();
-        fill(tid);
+        fill(r, tid);
         __syncthreads();
     }
 }
@@ -318,12 +359,15 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const typename Cx<HALF>::One* __r
     static_assert(PER2 % BATCH == 0, "batches divide the store loop");
 
     Two r[PER2];
-    auto load_tile = [&](uint32_t tile, int tid, bool live) {
+    constexpr int PARTS = portions<LOGN2 - 3, kSpreadFB>();
+    // part < 0: the whole tile; otherwise the loads q with q * PARTS / PER2 == part
+    auto load_tile = [&](uint32_t tile, int tid, bool live, int part = -1) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
         const Two* src = reinterpret_cast<const Two*>(mid + (live ? (size_t)(tile / tiles) * (size_t)M : 0));
         const uint32_t pp = tile_in_chunk(tile, tiles) * P + p;
 #pragma unroll
-        for (int q = 0; q < PER2; ++q) r[q] = src[live ? (uint32_t)(kq0 + q * DK) * (N1 >> 1) + pp : 0u];
+        for (int q = 0; q < PER2; ++q)
+            if (part < 0 || q * PARTS / PER2 == part) r[q] = src[live ? (uint32_t)(kq0 + q * DK) * (N1 >> 1) + pp : 0u];
     };
     // r[q] holds rows kq0 + q * N2/8 of one slot pair: the first radix-8 stage runs on the way into LDS
     static_assert(PER2 == 8 && DK == N2 / 8, "a lane's loads are the inputs of two radix-8 butterflies");
@@ -357,8 +401,10 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const typename Cx<HALF>::One* __r
         const float2 base_a = twiddle(tb, (ka + ((uint32_t)kq0 << logN1)) << (21 - logM));
         const float2 base_b = twiddle(tb, (kb + ((uint32_t)kq0 << logN1)) << (21 - logM));
         const bool more = t + 1 < tend;
-        load_tile(more ? t + 1 : t, tid, more);
-        run_fft<LOGN2, LOGT, NT, false, 3>(d, tw, tid);
+        load_tile(more ? t + 1 : t, tid, more, 0);
+        run_fft_between<LOGN2, LOGT, NT, false, 3>(d, tw, tid, [&](int k) {
+            if (k + 1 < PARTS) load_tile(more ? t + 1 : t, tid, more, k + 1);
+        });
         const size_t c = t / tiles;
         typename Cx<HALF>::One* out = spec + c * (size_t)sstride;
 #pragma unroll
@@ -457,25 +503,31 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const typename Cx<HALF>::One* __r
     Two r[PER2];
     One xnyq;                // Nyquist bin of the chunk of the tile held in r
     float2 base_a, base_b;   // split twiddles of that tile
-    auto load_tile = [&](uint32_t tile, int tid, bool live) {
+    constexpr int PARTS = portions<LOGN2 - 3, kSpreadIB>();
+    // part < 0: the whole tile; otherwise the loads q with q * PARTS / PER2 == part (the look-ups go with part 0)
+    auto load_tile = [&](uint32_t tile, int tid, bool live, int part = -1) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
         const One* X = spec + (live ? (size_t)(tile / tiles) * (size_t)sstride : 0);
         const uint32_t pp = tile_in_chunk(tile, tiles) * P + p;
         const uint32_t ka = pp, kb = mirror_row(pp, N1);
-        base_a = twiddle(tb, (ka + ((uint32_t)kq0 << logN1)) << (21 - logM));
-        base_b = twiddle(tb, (kb + ((uint32_t)kq0 << logN1)) << (21 - logM));
+        if (part <= 0) {
+            base_a = twiddle(tb, (ka + ((uint32_t)kq0 << logN1)) << (21 - logM));
+            base_b = twiddle(tb, (kb + ((uint32_t)kq0 << logN1)) << (21 - logM));
+        }
         if constexpr (PAIR) {
             const Two* X4 = reinterpret_cast<const Two*>(X);
 #pragma unroll
-            for (int q = 0; q < PER2; ++q) r[q] = X4[live ? ((uint32_t)(kq0 + q * DK) << (logN1 - 1)) + pp : 0u];
+            for (int q = 0; q < PER2; ++q)
+                if (part < 0 || q * PARTS / PER2 == part) r[q] = X4[live ? ((uint32_t)(kq0 + q * DK) << (logN1 - 1)) + pp : 0u];
         } else {
 #pragma unroll
             for (int q = 0; q < PER2; ++q) {
+                if (!(part < 0 || q * PARTS / PER2 == part)) continue;
                 const uint32_t o = (uint32_t)(kq0 + q * DK) << logN1;
                 r[q] = join(X[live ? ka + o : 0u], X[live ? kb + o : 0u]);
             }
         }
-        xnyq = X[live ? M : 0u];
+        if (part <= 0) xnyq = X[live ? M : 0u];
     };
     auto fill = [&](int tid) {
         const int p = tid & (P - 1), kq0 = tid >> LOGP;
@@ -530,8 +582,10 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const typename Cx<HALF>::One* __r
             cur_b = make_float2(cur_b.x * mid_scale, cur_b.y * mid_scale);
         }
         const bool more = t + 1 < tend;
-        load_tile(more ? t + 1 : t, tid, more);
-        run_fft<LOGN2, LOGT, NT, true, 3>(d, tw, tid);
+        load_tile(more ? t + 1 : t, tid, more, 0);
+        run_fft_between<LOGN2, LOGT, NT, true, 3>(d, tw, tid, [&](int k) {
+            if (k + 1 < PARTS) load_tile(more ? t + 1 : t, tid, more, k + 1);
+        });
         Two* dst = reinterpret_cast<Two*>(mid + (size_t)(t / tiles) * (size_t)M);
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
@@ -574,11 +628,14 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const typename Cx<HALF>::One* __r
     load_stage_twiddles<LOGN1, NT>(tw, tb, tid0);
 
     Two r[PER2];
-    auto load_tile = [&](uint32_t tile, int tid, bool live) {
+    constexpr int PARTS = portions<LOGN1, kSpreadIA>();
+    // part < 0: the whole tile; otherwise the loads q with q * PARTS / PER2 == part
+    auto load_tile = [&](uint32_t tile, int tid, bool live, int part = -1) {
         const Two* src = reinterpret_cast<const Two*>(mid + (live ? (size_t)(tile / tiles) * (size_t)M : 0));
         const uint32_t col0 = tile_in_chunk(tile, tiles) << LOGT;
 #pragma unroll
         for (int q = 0; q < PER2; ++q) {
+            if (!(part < 0 || q * PARTS / PER2 == part)) continue;
             const int w = tid + q * NT, kp = w & (HP - 1), col = w >> LOGHP;
             r[q] = src[live ? (uint32_t)(col0 + col) * HP + kp : 0u];
         }
@@ -599,8 +656,10 @@ __global__ __launch_bounds__(kNT) void k_inv_a(const typename Cx<HALF>::One* __r
     for (;;) {
         const int tid = opaque_lane(tid0);
         const bool more = t + tstep < tend;
-        load_tile(more ? t + tstep : t, tid, more);
-        run_fft<LOGN1, LOGT, NT, true>(d, tw, tid);
+        load_tile(more ? t + tstep : t, tid, more, 0);
+        run_fft_between<LOGN1, LOGT, NT, true, 0>(d, tw, tid, [&](int k) {
+            if (k + 1 < PARTS) load_tile(more ? t + tstep : t, tid, more, k + 1);
+        });
         const Span sp = chunk_span<TABLE>(tab, t / tiles, ~(size_t)0, 2 * (size_t)M, n, aligned & 1);
         const size_t cbase = sp.first;
         const uint32_t col0 = tile_in_chunk(t, tiles) << LOGT;
@@ -688,6 +747,7 @@ Grid persistent_grid(size_t total, uint32_t kMaxWgs = 512)  // 512 = 256 compute
 // pass A: 2^glog workgroups (b, b+8, ...) share a run of aligned tile groups; per_wg counts tile groups and wgs
 // is a multiple of 8 * 2^glog
 constexpr int kGroupLog = 1;
+constexpr uint32_t kPassAWgs = 2048;  // most workgroups the forward pass A is cut into
 Grid grouped_grid(size_t groups, int glog, uint32_t kMaxWgs = 512)
 {
     Grid g;
@@ -713,7 +773,7 @@ hipError_t fwd_a(const float* in, size_t n, int logM, size_t C, float2* mid_f32,
     const size_t total = C * (((size_t)1 << (logM - LOGN1)) >> (kLogE - LOGN1));
     const int glog = logM - kLogE >= kGroupLog ? kGroupLog : 1;  // a chunk has 2^(logM-kLogE) >= 2 tiles
     // measured: 143 us against 149 with 512; a stand-by launch (only_if) takes the small grid, which leaves sooner
-    const Grid g = grouped_grid(total >> glog, glog, only_if ? 512 : 2048);
+    const Grid g = grouped_grid(total >> glog, glog, only_if ? 512 : kPassAWgs);
     FFTSP_LAUNCH(only_if ? "rfft_pass_a_standby" : "rfft_pass_a", kern, dim3(g.wgs), dim3(kNT), lds, s, in, n, logM, mid,
                  t, aligned, (uint32_t)(total >> glog), g.per_wg, glog, zero_ptr, zero_words, table_arg<TABLE>(tab),
                  in_scale, only_if);

@@ -185,6 +185,29 @@ __device__ __forceinline__ void run_fft(float2* d, const float2* tw, int tid)
     }
 }
 
+// LDS stages run_fft takes for `rem` remaining levels
+constexpr int lds_stages(int rem)
+{
+    int n = 0;
+    while (rem > 0) {
+        rem -= stage_radix_log(rem);
+        ++n;
+    }
+    return n;
+}
+
+// the same, calling between(k) after LDS stage k (k = 0, 1, ...)
+template <int LOGR, int LOGT, int NT, bool INV, int NS_LOG, int K = 0, typename Between>
+__device__ __forceinline__ void run_fft_between(float2* d, const float2* tw, int tid, Between between)
+{
+    if constexpr (NS_LOG < LOGR) {
+        constexpr int RL = stage_radix_log(LOGR - NS_LOG);
+        fft_stage<LOGR, LOGT, NT, INV, NS_LOG, RL>(d, tw, tid);
+        between(K);
+        run_fft_between<LOGR, LOGT, NT, INV, NS_LOG + RL, K + 1>(d, tw, tid, between);
+    }
+}
+
 template <int LOGR, int NT>
 __device__ __forceinline__ void load_stage_twiddles(float2* tw, const Tables& tb, int tid)
 {
