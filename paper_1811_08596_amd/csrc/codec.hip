@@ -485,7 +485,7 @@ __device__ __forceinline__ void walk_tile(const uint2* __restrict__ tile_cands, 
     }
 }
 
-constexpr int kStageBatch = 12;  // candidates per lane fetched in one go by k_resolve (12 Ki staged / 1024 lanes)
+constexpr int kStageBatch = 9;  // tiles whose candidates a wave of k_resolve fetches in one go
 
 struct HeaderInfo {
     int write;
@@ -554,36 +554,40 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
     }
     const bool staged = s_carry[0] <= stage_cap;
     if (staged) {
-        // flat copy with every lane busy: candidate i belongs to the last tile whose offset is <= i
-        // All of a lane's loads are issued before the first is used: one memory round trip, not one per candidate.
-        const uint32_t total = s_carry[0];
-        for (uint32_t base = 0; base < total; base += kStageBatch * RT) {
+        // A wave per tile, kStageBatch tiles in flight per wave: a tile's candidates are one contiguous run (about 40
+        // for a 2^20 chunk), so a wave fetches them with one coalesced load, and all loads of a batch are issued
+        // before the first is used: one memory round trip per batch, no search for the tile a candidate belongs to.
+        for (uint32_t t0 = (uint32_t)wave; t0 < Tn; t0 += RW * kStageBatch) {
             uint2 v[kStageBatch];
-            uint32_t lo[kStageBatch];
 #pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) lo[u] = 0;
-            // the searches of a batch advance together, so their LDS reads overlap
-            for (uint32_t bit = 1024u; bit; bit >>= 1) {  // MAX_TILES <= 2047
+            for (int u = 0; u < kStageBatch; ++u) {
+                const uint32_t t = t0 + (uint32_t)u * RW;
+                const uint32_t nc = t < Tn ? tnc[t] : 0u;
+                // lanes past the end read their tile's first slot (always allocated) and drop it
+                v[u] = cd[(size_t)(t < Tn ? t : 0u) * kTile + ((uint32_t)lane < nc ? (uint32_t)lane : 0u)];
+            }
 #pragma unroll
-                for (int u = 0; u < kStageBatch; ++u) {
-                    const uint32_t i = base + (uint32_t)u * RT + tid, probe = lo[u] + bit;
-                    if (probe < Tn && toff[probe] <= i) lo[u] = probe;
+            for (int u = 0; u < kStageBatch; ++u) {
+                const uint32_t t = t0 + (uint32_t)u * RW;
+                if (t < Tn && (uint32_t)lane < tnc[t]) {
+                    if constexpr (KEYS)
+                        stage_keys[toff[t] + (uint32_t)lane] = v[u].x;
+                    else
+                        stage[toff[t] + (uint32_t)lane] = v[u];
                 }
             }
-#pragma unroll
+            // the rare tile with more than a row of candidates (runs of equal keys)
+#pragma unroll 1
             for (int u = 0; u < kStageBatch; ++u) {
-                const uint32_t i = base + (uint32_t)u * RT + tid;
-                // lanes past the end read their tile's first slot (always allocated) and drop it
-                v[u] = cd[(size_t)lo[u] * kTile + (i < total ? i - toff[lo[u]] : 0u)];
-            }
-#pragma unroll
-            for (int u = 0; u < kStageBatch; ++u) {
-                const uint32_t i = base + (uint32_t)u * RT + tid;
-                if (i < total) {
+                const uint32_t t = t0 + (uint32_t)u * RW;
+                if (t >= Tn) break;
+                const uint32_t nc = tnc[t], o = toff[t];
+                for (uint32_t i = 64u + (uint32_t)lane; i < nc; i += 64u) {
+                    const uint2 e = cd[(size_t)t * kTile + i];
                     if constexpr (KEYS)
-                        stage_keys[i] = v[u].x;
+                        stage_keys[o + i] = e.x;
                     else
-                        stage[i] = v[u];
+                        stage[o + i] = e;
                 }
             }
         }
