@@ -457,30 +457,50 @@ __device__ __forceinline__ size_t record_offset(const TableArg<TABLE>& tab, size
         return c * S;
 }
 
-// Candidates that did not fit in LDS are walked tile by tile, a wave per tile: the wave fetches up to kWalk rows
-// of 64 candidates in one memory round trip (long runs of equal keys, such as a chunk of zeros, fill whole tiles)
-// and hands them to f(entry, valid) row by row, in candidate order (f is called by the whole wave, so it may use
-// ballots).
-constexpr int kWalk = 8;
-template <typename F>
-__device__ __forceinline__ void walk_tile(const uint2* __restrict__ tile_cands, uint32_t nc, int lane, F&& f)
+// Candidates that did not fit in LDS are walked from memory.
+constexpr int kWalk = 8;  // further rows of 64 candidates of one tile fetched in one round trip
+// All tiles of a chunk, a wave per tile, kWalkTiles tiles per round trip: the first row of candidates of each tile of
+// a batch (usually all a tile has) is fetched before any is used.  begin(t) and end(t) bracket tile t's rows, which
+// go to row(entry, valid) in candidate order; all three are called by the whole wave.
+constexpr int kWalkTiles = 8;
+template <typename B, typename R, typename E>
+__device__ __forceinline__ void walk_tiles(const uint2* __restrict__ cd, const uint32_t* tnc, uint32_t Tn, int wave, int lane,
+                                           B&& begin, R&& row, E&& end)
 {
-    if (nc <= 64u) {  // the usual tile: less than one row of candidates, one load
-        if (nc) f(tile_cands[(uint32_t)lane < nc ? (uint32_t)lane : 0u], (uint32_t)lane < nc);
-        return;
-    }
-    for (uint32_t i0 = 0; i0 < nc; i0 += 64u * kWalk) {
-        uint2 e[kWalk];
-        // all loads are issued before the first is used; rows past the end re-read the tile's first slot
+    for (uint32_t t0 = (uint32_t)wave; t0 < Tn; t0 += RW * kWalkTiles) {
+        uint2 first[kWalkTiles];
 #pragma unroll
-        for (int u = 0; u < kWalk; ++u) {
-            const uint32_t i = i0 + (uint32_t)u * 64u + (uint32_t)lane;
-            e[u] = tile_cands[i < nc ? i : 0u];
+        for (int u = 0; u < kWalkTiles; ++u) {
+            const uint32_t t = t0 + (uint32_t)u * RW;
+            const uint32_t nc = t < Tn ? tnc[t] : 0u;
+            // lanes past the end read their tile's first slot (always allocated) and drop it
+            first[u] = cd[(size_t)(t < Tn ? t : 0u) * kTile + ((uint32_t)lane < nc ? (uint32_t)lane : 0u)];
         }
 #pragma unroll
-        for (int u = 0; u < kWalk; ++u) {
-            const uint32_t row = i0 + (uint32_t)u * 64u;
-            if (row < nc) f(e[u], row + (uint32_t)lane < nc);
+        for (int u = 0; u < kWalkTiles; ++u) {
+            const uint32_t t = t0 + (uint32_t)u * RW;
+            if (t < Tn) {
+                const uint32_t nc = tnc[t];
+                begin(t);
+                if (nc) row(first[u], (uint32_t)lane < nc);
+                if (nc > 64u) {  // long runs of equal keys (a chunk of zeros) fill whole tiles
+                    const uint2* tile_cands = cd + (size_t)t * kTile;
+                    for (uint32_t i0 = 64u; i0 < nc; i0 += 64u * kWalk) {
+                        uint2 e[kWalk];
+#pragma unroll
+                        for (int v = 0; v < kWalk; ++v) {
+                            const uint32_t i = i0 + (uint32_t)v * 64u + (uint32_t)lane;
+                            e[v] = tile_cands[i < nc ? i : 0u];
+                        }
+#pragma unroll
+                        for (int v = 0; v < kWalk; ++v) {
+                            const uint32_t r0 = i0 + (uint32_t)v * 64u;
+                            if (r0 < nc) row(e[v], r0 + (uint32_t)lane < nc);
+                        }
+                    }
+                }
+                end(t);
+            }
         }
     }
 }
@@ -614,23 +634,21 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
                     if ((key & pmask) == prefix) atomicAdd(&h[(key >> shift) & dmask], 1u);
                 }
             } else {
-                for (uint32_t t = wave; t < Tn; t += RW) {
-                    walk_tile(cd + (size_t)t * kTile, tnc[t], lane, [&](uint2 e, bool valid) {
-                        const bool hit = valid && (e.x & pmask) == prefix;
-                        const uint32_t digit = (e.x >> shift) & dmask;
-                        const uint64_t act = __ballot(hit);
-                        if (act) {
-                            // a row whose keys share the digit (a run of equal values, e.g. zeros) is one atomic
-                            const int first = __ffsll((unsigned long long)act) - 1;
-                            const uint32_t d0 = __shfl(digit, first, 64);
-                            if (__ballot(hit && digit == d0) == act) {
-                                if (lane == first) atomicAdd(&h[d0], (uint32_t)__popcll(act));
-                            } else if (hit) {
-                                atomicAdd(&h[digit], 1u);
-                            }
+                walk_tiles(cd, tnc, Tn, wave, lane, [](uint32_t) {}, [&](uint2 e, bool valid) {
+                    const bool hit = valid && (e.x & pmask) == prefix;
+                    const uint32_t digit = (e.x >> shift) & dmask;
+                    const uint64_t act = __ballot(hit);
+                    if (act) {
+                        // a row whose keys share the digit (a run of equal values, e.g. zeros) is one atomic
+                        const int first = __ffsll((unsigned long long)act) - 1;
+                        const uint32_t d0 = __shfl(digit, first, 64);
+                        if (__ballot(hit && digit == d0) == act) {
+                            if (lane == first) atomicAdd(&h[d0], (uint32_t)__popcll(act));
+                        } else if (hit) {
+                            atomicAdd(&h[digit], 1u);
                         }
-                    });
-                }
+                    }
+                }, [](uint32_t) {});
             }
             __syncthreads();
             const uint32_t bin = 1023u - (uint32_t)tid;  // scan from the top digit down
@@ -666,17 +684,16 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             teq[t] = eq;
         }
     } else {
-        for (uint32_t t = wave; t < Tn; t += RW) {
-            uint32_t gt = 0, eq = 0;  // wave-uniform counts from ballots
-            walk_tile(cd + (size_t)t * kTile, tnc[t], lane, [&](uint2 e, bool valid) {
-                gt += (uint32_t)__popcll(__ballot(valid && e.x > tau));
-                eq += (uint32_t)__popcll(__ballot(valid && e.x == tau));
-            });
+        uint32_t gt = 0, eq = 0;  // wave-uniform counts from ballots
+        walk_tiles(cd, tnc, Tn, wave, lane, [&](uint32_t) { gt = eq = 0; }, [&](uint2 e, bool valid) {
+            gt += (uint32_t)__popcll(__ballot(valid && e.x > tau));
+            eq += (uint32_t)__popcll(__ballot(valid && e.x == tau));
+        }, [&](uint32_t t) {
             if (lane == 0) {
                 tgt[t] = gt;
                 teq[t] = eq;
             }
-        }
+        });
     }
     if (tid == 0) {
         s_carry[0] = 0;
@@ -736,18 +753,18 @@ __global__ __launch_bounds__(RT) void k_resolve(uint32_t Tn, uint32_t k, int bit
             }
         }
     } else {
-        for (uint32_t t = wave; t < Tn; t += RW) {
-            const uint32_t take = ttake[t];
+        uint32_t take = 0, eqrun = 0;
+        walk_tiles(cd, tnc, Tn, wave, lane, [&](uint32_t t) {
+            take = ttake[t];
             if (lane == 0 && tdef[t]) vm = tvd[t] > vm ? tvd[t] : vm;
-            uint32_t eqrun = 0;
-            walk_tile(cd + (size_t)t * kTile, tnc[t], lane, [&](uint2 e, bool valid) {
-                const bool iseq = valid && e.x == tau;
-                const uint64_t em = __ballot(iseq);
-                const bool kept = valid && (e.x > tau || (iseq && eqrun + prefix_popc(em) < take));
-                if (kept) vm = e.y > vm ? e.y : vm;
-                eqrun += (uint32_t)__popcll(em);
-            });
-        }
+            eqrun = 0;
+        }, [&](uint2 e, bool valid) {
+            const bool iseq = valid && e.x == tau;
+            const uint64_t em = __ballot(iseq);
+            const bool kept = valid && (e.x > tau || (iseq && eqrun + prefix_popc(em) < take));
+            if (kept) vm = e.y > vm ? e.y : vm;
+            eqrun += (uint32_t)__popcll(em);
+        }, [](uint32_t) {});
     }
     vm = wave_max(vm);
     if (lane == 0 && vm) atomicMax(&s_vmax, vm);
