@@ -345,8 +345,10 @@ __global__ __launch_bounds__(kNT) void k_fwd_b(const typename Cx<HALF>::One* __r
     const int tid0 = threadIdx.x;
     const int logN1 = logM - LOGN2;
     const uint32_t M = 1u << logM, N1 = 1u << logN1, tiles = N1 >> LOGT;
-    uint32_t t = blockIdx.x * per_wg;
-    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
+    // runs differ by at most one tile: the first total - per_wg * gridDim.x workgroups take one more
+    const uint32_t extra = total - per_wg * gridDim.x;
+    uint32_t t = blockIdx.x * per_wg + (blockIdx.x < extra ? blockIdx.x : extra);
+    const uint32_t tend = t + per_wg + (blockIdx.x < extra ? 1u : 0u);
     if (t >= tend) return;
     load_stage_twiddles<LOGN2, NT>(tw, tb, tid0);
     if (CODEC)
@@ -493,8 +495,10 @@ __global__ __launch_bounds__(kNT) void k_inv_b(const typename Cx<HALF>::One* __r
     const int tid0 = threadIdx.x;
     const int logN1 = logM - LOGN2;
     const uint32_t M = 1u << logM, N1 = 1u << logN1, tiles = N1 >> LOGT;
-    uint32_t t = blockIdx.x * per_wg;
-    const uint32_t tend = t + per_wg < total ? t + per_wg : total;
+    // runs differ by at most one tile: the first total - per_wg * gridDim.x workgroups take one more
+    const uint32_t extra = total - per_wg * gridDim.x;
+    uint32_t t = blockIdx.x * per_wg + (blockIdx.x < extra ? blockIdx.x : extra);
+    const uint32_t tend = t + per_wg + (blockIdx.x < extra ? 1u : 0u);
     if (t >= tend) return;
     load_stage_twiddles<LOGN2, NT>(tw, tb, tid0);
     constexpr int DK = NT >> LOGP;
@@ -736,11 +740,14 @@ hipError_t small_inv(const float2* spec, uint32_t sstride, size_t n, size_t C, f
 struct Grid {
     uint32_t wgs, per_wg;
 };
-Grid persistent_grid(size_t total, uint32_t kMaxWgs = 512)  // 512 = 256 compute units x 2 resident workgroups
+// Every workgroup takes per_wg tiles and the first total - per_wg * wgs of them one more.  With 512 workgroups
+// (256 compute units x 2 resident) the two workgroups of a compute unit are b and b + 256, so the longer runs pair
+// up with the shorter ones and every compute unit gets the same number of tiles.
+Grid persistent_grid(size_t total, uint32_t kMaxWgs = 512)
 {
     Grid g;
-    g.per_wg = (uint32_t)((total + kMaxWgs - 1) / kMaxWgs);
-    g.wgs = (uint32_t)((total + g.per_wg - 1) / g.per_wg);
+    g.wgs = (uint32_t)(total < kMaxWgs ? total : kMaxWgs);
+    g.per_wg = (uint32_t)(total / g.wgs);
     return g;
 }
 
