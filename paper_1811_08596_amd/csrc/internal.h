@@ -85,13 +85,14 @@ constexpr int kKeyShift = 31 - kHistBits;     // bucket = key >> 19
 constexpr size_t kControlBytes = 4096;  // control block at the start of every workspace
 constexpr int kCtlGaveUpWord = 1;       // u32 index of the fused kernels' give-up word inside the control block
 
-// The fused transforms (fused.hip) take chunk lengths 2^15 .. 2^20 when the call has at least 512 tiles of 8192
-// points, and address three turn buffers of 4 MiB per XCD inside the intermediate's region.
+// The fused transforms (fused.hip) take chunk lengths 2^15 .. 2^20 and address three turn buffers of 4 MiB per XCD
+// inside the intermediate's region, so they take calls whose own intermediate is at least that large (96 MiB: about
+// 25 million samples); smaller calls keep the per-pass kernels and their workspace stays what those need.
 constexpr size_t kFusedScratchBytes = (size_t)8 * 3 * 64 * 8192 * 8;
 static inline bool fused_shape(int logL, size_t C)
 {
     const int logM = logL - 1;
-    return logM >= 14 && logM <= 19 && (C << (logM - 13)) >= 512;
+    return logM >= 14 && logM <= 19 && (C << logL) * 4 >= kFusedScratchBytes;
 }
 
 // Where everything lives inside the caller's workspace (byte offsets, 256-aligned).
@@ -173,10 +174,7 @@ static inline Workspace make_workspace(size_t C, uint32_t L, int time_domain = 0
     w.tscan = off;  off = align256(off + C * Tn * 8);
     // The candidate list and the two-pass intermediate are never alive together (the sender's transform has
     // finished before the first candidate is written; the receiver has no candidates): one region serves both.
-    size_t cand_bytes = C * Tn * kTile * 8, mid_bytes = time_domain ? 0 : C * (size_t)L * 4;
-    int logL = 0;
-    while (((size_t)1 << logL) < L) ++logL;
-    if (!time_domain && fused_shape(logL, C) && mid_bytes < kFusedScratchBytes) mid_bytes = kFusedScratchBytes;
+    const size_t cand_bytes = C * Tn * kTile * 8, mid_bytes = time_domain ? 0 : C * (size_t)L * 4;
     w.cand = off;
     w.mid = off;    off = align256(off + (cand_bytes > mid_bytes ? cand_bytes : mid_bytes));
     w.prefix = off; off = align256(off + C * W * 4);

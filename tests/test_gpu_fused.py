@@ -1,7 +1,7 @@
 """The fused, cache-resident two-pass transforms (csrc/fused.hip) against the oracle and against the per-pass kernels.
 
-Calls with at least 512 tiles of 8192 points take the fused kernels; the small parity cases never do, so the
-cases here are sized for them: chunk lengths 2^15 .. 2^20, several turns per XCD, a ragged last chunk, a last
+Calls whose two-pass intermediate is at least 96 MiB (about 25 million samples) take the fused kernels; the small
+parity cases never do, so the cases here are sized for them: chunk lengths 2^15 .. 2^20, several turns per XCD, a ragged last chunk, a last
 turn that is only partly filled.  Parity with the oracle is the same contract as everywhere (tests/test_gpu_parity.py:
 spectra and reconstructions within 1e-5, bytes identical on the oracle's spectrum); on top of it the fused sender
 must produce the very bytes of the per-pass kernels it replaces, and the fused receiver
@@ -46,12 +46,12 @@ def round_trip(dev, g, L, theta, bits):
 
 
 CASES = [
-    # (log2 L, chunks, samples missing from the last chunk)
-    (15, 257, 1234),   # 32 chunks per turn: 9 turns, the last one holds a single chunk
-    (16, 130, 5),
-    (17, 70, 99),
-    (18, 33, 70000),
-    (20, 9, 4321),     # one chunk per turn; XCD 0 takes two turns
+    # (log2 L, chunks, samples missing from the last chunk); at least 96 MiB of intermediate each
+    (15, 769, 1234),   # 32 chunks per turn: 25 turns, the last one holds a single chunk
+    (16, 390, 5),
+    (17, 200, 99),
+    (18, 100, 70000),
+    (20, 25, 4321),    # one chunk per turn; XCD 0 takes four turns
     (20, 35, 0),       # five turns on some XCDs: every turn buffer is reused
 ]
 
@@ -81,7 +81,7 @@ def test_fused_agrees_with_per_pass_kernels(dev, monkeypatch, logL, C, tail):
 def test_expired_wait_hands_over_to_the_stand_by_kernels(dev, monkeypatch):
     """A spin limit of zero makes the first hand-over wait that is not already satisfied expire: every workgroup
     leaves, the give-up word is set, and the per-pass kernels behind the fused one produce the result."""
-    L, C = 1 << 17, 70
+    L, C = 1 << 17, 200
     g = workloads.small_mixed(C * L - 99, seed=7)
     monkeypatch.setenv("FFTSP_FUSED", "0")
     want_p, want_r, _, _ = round_trip(dev, g, L, 0.5, 8)
