@@ -159,18 +159,36 @@ __global__ __launch_bounds__(NT) void k_inv_small(const float2* __restrict__ spe
 // acknowledged.  The loads of the batch are unconditional (on the last tile they read one valid dummy address),
 // which keeps the code between issue and use free of branches that would make the waits conservative.
 
-// Forward pass A: N1-point FFTs down the columns of the N1 x N2 view of z, for tiles of TA adjacent columns.
-// FAST: every tile of this workgroup's run lies in a chunk that is wholly inside the input, and the input is
-// 16-byte aligned: two columns per 16-byte load, no guards.  Otherwise every element is loaded under a guard
-// (ragged last chunk, unaligned tensors); the two variants are separate loops so that the guarded one does
-// not put branches between the fast one's loads and their use.
+// Column-to-column ratios of pass A's twiddles W_M^(n2 k1) for the row pairs a lane stores: they depend on the lane
+// alone, so a workgroup looks them up once for all its tiles.
+template <int LOGN1>
+struct PassARatios {
+    static constexpr int HP = (1 << LOGN1) / 2;
+    static constexpr int KN = HP >= kNT ? HP / kNT : 1;
+    float2 a[KN], b[KN];
+};
+template <int LOGN1>
+__device__ __forceinline__ PassARatios<LOGN1> pass_a_ratios(const Tables& tb, int logM, int tid)
+{
+    constexpr int N1 = 1 << LOGN1, HP = N1 / 2, KN = PassARatios<LOGN1>::KN;
+    constexpr int DC = HP >= kNT ? 1 : kNT / HP;
+    PassARatios<LOGN1> r;
+#pragma unroll
+    for (int kk = 0; kk < KN; ++kk) {
+        const uint32_t kp = (uint32_t)(tid + kk * kNT) & (HP - 1);
+        r.a[kk] = twiddle(tb, ((uint32_t)DC * kp) << (22 - logM));
+        r.b[kk] = twiddle(tb, ((uint32_t)DC * mirror_row(kp, N1)) << (22 - logM));
+    }
+    return r;
+}
+
 // One tile of pass A once its first stage is in LDS: the twiddle look-ups of the store loop, `prefetch()` (loads of
 // a later tile, issued here so that they are older than this tile's stores), the LDS stages, and the store loop,
 // which multiplies by W_M^(n2 k1) and writes row k1 next to row N1 - k1.
 template <int LOGN1, bool HALF, typename Prefetch>
 __device__ __forceinline__ void fwd_a_tile(uint32_t t, uint32_t tiles, int logM, typename Cx<HALF>::One* __restrict__ mid,
                                            const Tables& tb, float2* d, const float2* tw, int tid, float in_scale,
-                                           Prefetch prefetch)
+                                           const PassARatios<LOGN1>& ratio, Prefetch prefetch)
 {
     constexpr int NT = kNT, LOGE = kLogE, PER2 = kPer / 2;
     constexpr int N1 = 1 << LOGN1, LOGT = LOGE - LOGN1;
@@ -182,14 +200,12 @@ __device__ __forceinline__ void fwd_a_tile(uint32_t t, uint32_t tiles, int logM,
     const uint32_t M = 1u << logM;
     const uint32_t col0 = tile_in_chunk(t, tiles) << LOGT;
     const int sh = 22 - logM;
-    float2 ratio_a[KN], ratio_b[KN], cur_a[KN], cur_b[KN];
+    float2 cur_a[KN], cur_b[KN];
 #pragma unroll
     for (int kk = 0; kk < KN; ++kk) {
         const uint32_t kp = (uint32_t)(tid + kk * NT) & (HP - 1);
         const uint32_t ka = kp, kb = mirror_row(kp, N1);
         const uint32_t cfirst = (uint32_t)(tid + kk * NT) >> LOGHP;
-        ratio_a[kk] = twiddle(tb, ((uint32_t)DC * ka) << sh);
-        ratio_b[kk] = twiddle(tb, ((uint32_t)DC * kb) << sh);
         cur_a[kk] = twiddle(tb, ((col0 + cfirst) * ka) << sh);
         cur_b[kk] = twiddle(tb, ((col0 + cfirst) * kb) << sh);
         if constexpr (HALF) {  // the variant's power-of-two factors ride on the twiddles (exact)
@@ -214,12 +230,17 @@ __device__ __forceinline__ void fwd_a_tile(uint32_t t, uint32_t tiles, int logM,
             const float2 va = cmul(d[sw_idx<LOGT>((int)ka, (int)col)], cur_a[kk]);
             const float2 vb = cmul(d[sw_idx<LOGT>((int)kb, (int)col)], cur_b[kk]);
             out[n2 * (uint32_t)HP + kp] = cx_store<HALF>(join(va, vb));
-            cur_a[kk] = cmul(cur_a[kk], ratio_a[kk]);
-            cur_b[kk] = cmul(cur_b[kk], ratio_b[kk]);
+            cur_a[kk] = cmul(cur_a[kk], ratio.a[kk]);
+            cur_b[kk] = cmul(cur_b[kk], ratio.b[kk]);
         }
     }
 }
 
+// Forward pass A: N1-point FFTs down the columns of the N1 x N2 view of z, for tiles of TA adjacent columns.
+// FAST: every tile of this workgroup's run lies in a chunk that is wholly inside the input, and the input is
+// 16-byte aligned: two columns per 16-byte load, no guards.  Otherwise every element is loaded under a guard
+// (ragged last chunk, unaligned tensors); the two variants are separate loops so that the guarded one does
+// not put branches between the fast one's loads and their use.
 template <int LOGN1, bool FAST, bool TABLE, bool HALF>
 __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n, int logM,
                                           typename Cx<HALF>::One* __restrict__ mid, const Tables& tb, int aligned,
@@ -264,12 +285,13 @@ __device__ __forceinline__ void fwd_a_run(const float* __restrict__ in, size_t n
     float4 r[PER2];
 #pragma unroll
     for (int part = 0; part < spread_parts<LOGN1>(); ++part) load_tile(r, t, tid0, true, part);
+    const PassARatios<LOGN1> ratio = pass_a_ratios<LOGN1>(tb, logM, tid0);
     fill(r, tid0);
     __syncthreads();
     for (;;) {
         const int tid = opaque_lane(tid0);
         const bool more = t + tstep < tend;
-        fwd_a_tile<LOGN1, HALF>(t, tiles, logM, mid, tb, d, tw, tid, in_scale,
+        fwd_a_tile<LOGN1, HALF>(t, tiles, logM, mid, tb, d, tw, tid, in_scale, ratio,
                                 [&](int part) { load_tile(r, more ? t + tstep : t, tid, more, part); });
         if (!more) break;
         t += tstep;
