@@ -832,7 +832,7 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::
 {
     using E = typename Elem<REAL>::T;
     constexpr uint32_t CODES = Elem<REAL>::kCodes;
-    __shared__ uint32_t cw[kTile * 2 + 2];  // code words of this tile (bits = 32 worst case)
+    __shared__ __align__(16) uint32_t cw[kTile * 2 + 8];  // code words of this tile (bits = 32 worst case), see shw
     __shared__ uint32_t bmw[kTile / 32];
     __shared__ uint32_t weq[4], wfl[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -842,7 +842,7 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::
     const uint32_t rank0 = tscan[(c * Tn + tile) * 2 + 0], eq0 = tscan[(c * Tn + tile) * 2 + 1];
     const uint32_t twoN = CODES * (uint32_t)bits;  // code bits per kept bin
     const int shift = 23 - m;
-    const uint32_t lds_words = (uint32_t)kTile * twoN / 32u + 2u;
+    const uint32_t lds_words = (uint32_t)kTile * twoN / 32u + 2u + 3u;
 
     // the spectrum tile is staged in the LDS words that later hold the packed codes
     const typename Stored<REAL, HALF>::T* X = spec + c * (size_t)sstride;
@@ -901,6 +901,12 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::
     for (int w = 0; w < wave; ++w) rank += wfl[w];
     const uint32_t total = wfl[0] + wfl[1] + wfl[2] + wfl[3];
     const uint32_t w0 = (twoN * rank0) >> 5;
+    uint32_t* rec = reinterpret_cast<uint32_t*>(records + record_offset<TABLE>(tab, c, S));
+    uint32_t* bitmap = rec + 4;
+    uint32_t* codes = bitmap + W;
+    // The tile's code words are built in LDS at cw[shw + i] for the record's word w0 + i, with shw chosen so that an
+    // LDS word and its place in memory are aligned alike: whole 16-byte groups then go out as one store each.
+    const uint32_t shw = (uint32_t)((reinterpret_cast<uintptr_t>(codes + w0) >> 2) & 3u);
     // the one or two binary32 patterns a bin is coded from
     auto part = [](const E& v, int h) __attribute__((always_inline)) {
         if constexpr (REAL)
@@ -912,8 +918,8 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::
         // 8-bit codes: a survivor is one aligned 16-bit store (bin) or one byte (sample), no read-modify-write
         uint16_t* cw16 = reinterpret_cast<uint16_t*>(cw);
         uint8_t* cw8 = reinterpret_cast<uint8_t*>(cw);
-        const uint32_t base16 = rank0 - 2u * w0;  // first survivor's 16-bit slot inside cw (two codes each)
-        const uint32_t base8 = rank0 - 4u * w0;   // first survivor's byte inside cw (one code each)
+        const uint32_t base16 = rank0 - 2u * w0 + 2u * shw;  // first survivor's 16-bit slot inside cw (two codes each)
+        const uint32_t base8 = rank0 - 4u * w0 + 4u * shw;   // first survivor's byte inside cw (one code each)
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             if ((flbits >> r) & 1u) {
@@ -935,7 +941,7 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::
                 const uint32_t rk = rank + prefix_popc(fm[r]);
                 const uint32_t cre = quantize(part(z[r], 0), pbase, bits, shift);
                 const uint32_t cim = quantize(part(z[r], 1), pbase, bits, shift);
-                uint32_t p = twoN * rk - (w0 << 5);  // bit position inside cw
+                uint32_t p = twoN * rk - (w0 << 5) + (shw << 5);  // bit position inside cw
 #pragma unroll
                 for (int h = 0; h < (int)CODES; ++h) {
                     const uint32_t code = h ? cim : cre;
@@ -949,9 +955,6 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::
         }
     }
     __syncthreads();
-    uint32_t* rec = reinterpret_cast<uint32_t*>(records + record_offset<TABLE>(tab, c, S));
-    uint32_t* bitmap = rec + 4;
-    uint32_t* codes = bitmap + W;
     if (tid < kTile / 32) {
         const uint32_t wi = tile * (kTile / 32) + tid;
         if (wi < W) bitmap[wi] = bmw[tid];
@@ -961,12 +964,26 @@ __global__ __launch_bounds__(NT) void k_emit(const typename Stored<REAL, HALF>::
         const uint32_t rec_words = (uint32_t)(S / 4) - 4u - W;  // code words the record has room for
         const uint32_t nw_all = w1 - w0 + 1u;
         const uint32_t nw = w0 >= rec_words ? 0u : (nw_all < rec_words - w0 ? nw_all : rec_words - w0);
-        for (uint32_t i = tid; i < nw; i += NT) {
-            const uint32_t v = cw[i];
-            if (i == 0 || i == nw - 1u)
-                atomicOr(&codes[w0 + i], v);  // may be shared with the neighbouring tile (zeroed by k_resolve)
-            else
-                codes[w0 + i] = v;
+        // group g = LDS words 4g .. 4g+3 = record words w0 - shw + 4g .. (16-byte aligned in memory)
+        const uint32_t groups = (shw + nw + 3u) >> 2;
+        uint32_t* gbase = codes + w0 - shw;
+        for (uint32_t g = tid; g < groups; g += NT) {
+            const uint32_t i0 = 4u * g;  // LDS index of the group's first word; its tile word index is i0 - shw
+            if (i0 >= shw + 1u && i0 + 3u + 1u < shw + nw) {
+                // all four words lie strictly inside the tile's run
+                *reinterpret_cast<uint4*>(gbase + i0) = *reinterpret_cast<const uint4*>(cw + i0);
+            } else {
+#pragma unroll
+                for (uint32_t j = 0; j < 4u; ++j) {
+                    const uint32_t li = i0 + j;
+                    if (li < shw || li >= shw + nw) continue;
+                    const uint32_t i = li - shw, v = cw[li];
+                    if (i == 0 || i == nw - 1u)
+                        atomicOr(&codes[w0 + i], v);  // may be shared with the neighbouring tile (zeroed by k_resolve)
+                    else
+                        codes[w0 + i] = v;
+                }
+            }
         }
     }
 }
