@@ -6,13 +6,13 @@
 // XCD, 4 MiB each) carry it instead.  Workgroups are dispatched to XCDs round-robin by index, so the 64 resident
 // workgroups b = x, x+8, ... of XCD x form a team that shares one L2.  A team works in turns; a turn is 64 tiles of
 // 8192 points (4 MiB of intermediate: one chunk of 2^20 samples, or several shorter chunks):
-//     pass A on the team's tiles   -> stored into the team's 4 MiB scratch region (stays dirty in L2)
-//     every member arrives         -> "stored" counter
-//     pass B on the team's tiles   <- loaded from scratch with L1-bypassing loads (hits in L2)
-//     every member arrives         -> "loaded" counter, which the next turn's stores wait for
-// The same 4 MiB are reused turn after turn, so the lines are overwritten in L2 and rarely travel to memory.
-// With two teams per XCD (32 members, two tiles each per pass) the turns of the two teams alternate on the one
-// scratch region, so that one team computes while the other waits for its hand-over.
+//     pass A on the team's tiles   -> stored into one of the team's three 4 MiB turn buffers
+//     every member arrives         -> the turn's "stored" counter
+//     pass B on the team's tiles   <- loaded from the buffer with L1-bypassing loads (served by L2)
+//     every member arrives         -> the turn's "loaded" counter, which the stores that reuse the buffer wait for
+// A member runs pass A of turn s and pass B of turn s - 2 in one slot of its walk, so that what a wait refers to
+// lies two tiles back and has normally long happened.  Measured, the kernels are slower than the per-pass ones
+// (a team advances at the pace of its slowest member), so they are off unless FFTSP_FUSED=1 is set.
 //
 // Hand-over protocol.  Writers: plain stores, then every wave waits until its stores are acknowledged by L2
 // (vmcnt(0)), a workgroup barrier, and one device-scope atomic increment.  Readers: poll the counter with
